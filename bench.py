@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched token-sampling hot path on ONE MI355X.
+
+A step is one sip_sample() call: the whole path (history penalties, temperature, softmax
+statistics, top-k / top-p / min-p, seeded draw, best-n logprobs) over one [B, V] batch that
+is already resident in HBM.  The workload is the configuration the headline metric is
+quoted on: B=256, V=152064, fp32 (workload C3, benchmark configs[2]).
+
+To keep the logits from simply living in the 256 MB last-level cache between steps, the
+steps rotate over several distinct logits buffers whose total size exceeds it.
+
+Prints one JSON line (see the keys below).  The CPU oracle is timed first, in this same
+process, before the GPU is touched.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+import workloads
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+LLC_BYTES = 256 << 20
+
+
+def algorithmic_bytes(w) -> int:
+    """Bytes one call has to move: every logit once, the history once, the per-row
+    parameters, and the outputs (id + (1+n) x (id, logprob))."""
+    esz = 4 if w.dtype == "f32" else 2
+    nnz = 0 if w.hist_tokens is None else int(w.hist_tokens.size)
+    n = max(w.k_logprobs, -1)
+    per_row_out = 4 + (8 * (1 + n) if n >= 0 else 0)
+    return w.B * w.V * esz + 4 * nnz + 8 * (w.B + 1) * (1 if nnz else 0) + w.B * (32 + per_row_out)
+
+
+def cpu_baseline(w, max_rows: int) -> dict:
+    """The oracle as it stands, rows spread over host threads (numpy releases the GIL in its
+    sort / exp / cumsum loops)."""
+    from oracle import sip_oracle as O
+    cores = min(16, os.cpu_count() or 1)
+    rows = list(range(min(max_rows, w.B)))
+
+    def one(b):
+        return O.sample_batch(w.logits, w.params, w.hist_indptr, w.hist_tokens, 0, 0, w.k_logprobs, rows=[b])[0].token
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        list(ex.map(one, rows))
+    dt = time.perf_counter() - t0
+    return {"value": len(rows) / dt, "unit": "rows/s", "cores": cores, "kind": "oracle",
+            "sample": f"{len(rows)} of {w.B} rows of {w.name}, step 0, {dt:.2f} s wall on {cores} threads"}
+
+
+def read_traffic(name: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a
+    summary for this workload has been recorded under profiles/."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{name}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, help="0..4 = C1..C5 (default 2 = C3, the headline)")
+    ap.add_argument("--cpu-rows", type=int, default=256, help="rows of the workload the oracle is timed on (0 = skip)")
+    ap.add_argument("--check", action="store_true", help="also compare step 0 with the oracle on 16 rows")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (rows are independent; see DESIGN.md for how the "
+              "path would shard) -- run with --gpus 1", file=sys.stderr)
+        return 2
+
+    w = workloads.make(args.workload)
+    cpu = cpu_baseline(w, args.cpu_rows) if args.cpu_rows > 0 else None
+
+    import torch
+    import paper_2506_22033_amd as sip
+    from tests import sip_harness as H
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    sip.load()
+    dev = torch.device("cuda:0")
+    d = H.to_device(w)
+    esz = 4 if w.dtype == "f32" else 2
+    nbuf = max(2, -(-2 * LLC_BYTES // (w.B * w.V * esz)) + 1)
+    nbuf = min(nbuf, 8)
+    bufs = [d.logits] + [torch.roll(d.logits, shifts=j, dims=0).contiguous() for j in range(1, nbuf)]
+    nnz = 0 if d.tokens is None else d.tokens.numel()
+    dt_code = sip.SIP_F32 if w.dtype == "f32" else sip.SIP_BF16
+    ws = torch.empty(max(256, sip.sip_workspace_bytes(w.B, w.V, dt_code, nnz, w.k_logprobs)),
+                     dtype=torch.uint8, device=dev)
+    out_ids = torch.empty(w.B, dtype=torch.int32, device=dev)
+    out_lp_ids = torch.empty(w.B, 1 + w.k_logprobs, dtype=torch.int32, device=dev)
+    out_lp = torch.empty(w.B, 1 + w.k_logprobs, dtype=torch.float32, device=dev)
+
+    stream = torch.cuda.Stream(device=dev)
+
+    def step(i):
+        sip.sip_sample(bufs[i % nbuf], d.params, d.indptr, d.tokens, 0, i, w.k_logprobs, out_ids=out_ids,
+                       out_lp_ids=out_lp_ids, out_lp=out_lp, workspace=ws, V=w.V, stream=stream)
+
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        for i in range(args.steps):
+            step(args.warmup + i)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall * 1e3 / args.steps
+    launch_ms = gpu_ms / args.steps                 # HIP-event time per call on the launch stream
+    alg = algorithmic_bytes(w)
+    achieved = alg / (launch_ms * 1e-3) / 1e9
+
+    if args.check:
+        out = H.run_gpu(d, 0, 0)
+        st = H.compare(w, out, 0, 0, rows=range(0, w.B, max(1, w.B // 16)))
+        print(f"check: rows={st.rows} flagged={st.flagged} mismatch={st.flagged_mismatch} "
+              f"max|dlogprob|={st.max_lp_err:.2e}", file=sys.stderr)
+
+    res = {
+        "metric": "sampled rows/sec at B=256, V=152064 fp32" if args.workload == 2 else f"sampled rows/sec ({w.name})",
+        "value": w.B / (ms_per_step * 1e-3),
+        "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.dtype == "f32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B}, V={w.V}, {w.dtype}; {w.recipe}",
+                   "logits_buffers_rotated": nbuf, "k_logprobs": w.k_logprobs},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(w.name),
+                     "algorithmic_bytes_per_launch": alg, "launch_ms_hip_events": launch_ms,
+                     "kernel": "whole sip_sample call"},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,116 @@
+/*
+ * sip.h -- C boundary of the MI355X (gfx950) batched token sampler.
+ *
+ * One call turns a [B, V] logits matrix into B token ids and their log-probabilities:
+ * penalties from each row's token history, temperature, softmax, top-k / top-p / min-p
+ * filtering and one seeded categorical draw per row.  This is the "Sampling" step at the
+ * end of every decode iteration (paper Sec. 2.1 step 3,
+ *   p = Filter(softmax(ApplyPenalty(z, y_<s) / tau); k, p),  y_s ~ Categorical(p);
+ * restated operation by operation in Sec. 5.1).
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless it says "host".  The caller owns every
+ *    buffer.  The library allocates nothing, never synchronises and never writes to
+ *    `logits`; all work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream).
+ *  - Errors are reported by return code only.  Argument errors are detected on the host
+ *    before anything is enqueued; nothing has been written in that case.  Bad *data* in
+ *    device memory (NaN logits, top_p <= 0, temperature < 0, history offsets that do not
+ *    describe a CSR) gives unspecified results for the affected rows but never an
+ *    out-of-bounds access: history offsets are clamped to [0, hist_nnz], token ids
+ *    outside [0, V) are skipped.
+ *  - Concurrent calls are allowed on different streams if they use different workspaces.
+ *  - Same inputs, seed, step and row ids give the same output bits on every call.
+ */
+#ifndef SIP_H_
+#define SIP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SIP_F32 = 0, SIP_BF16 = 1 } sip_dtype;
+
+typedef enum {
+  SIP_OK = 0,
+  SIP_ERR_INVALID_ARG = 1, /* NULL required pointer, non-positive size, misaligned rows, ... */
+  SIP_ERR_UNSUPPORTED = 2, /* shape outside what the kernels are built for (see SIP_MAX_*) */
+  SIP_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned or smaller than sip_workspace_bytes() */
+  SIP_ERR_HIP = 4          /* a HIP runtime call (kernel launch) failed */
+} sip_status;
+
+#define SIP_MAX_V (1 << 19)        /* largest vocabulary the kernels support            */
+#define SIP_MAX_K_LOGPROBS 64      /* largest k_logprobs                                */
+
+/*
+ * Per-row sampling parameters (Sec. 2.1 step 3: tau, k, p; Sec. 7.1 "Workload" adds min-p
+ * and the repetition / frequency / presence penalties).  A HOST struct of DEVICE arrays of
+ * length B.  A NULL array switches the feature off for every row.
+ */
+typedef struct {
+  const float* temperature;        /* NULL => 1.  0 => greedy row (lowest-index arg max).            */
+  const int32_t* top_k;            /* NULL, <= 0 or >= V => off.  1 => greedy row.  Ties at the k-th
+                                      largest value are all kept.                                   */
+  const float* top_p;              /* NULL or >= 1 => off; otherwise in (0, 1).  Measured on the mass
+                                      that survives top-k; ties at the cut are kept together.        */
+  const float* min_p;              /* NULL or <= 0 => off; keeps p_v >= min_p * p_max, decided as
+                                      fp32 (s_v - s_max) >= fp32(ln min_p).  Applied after top-p.     */
+  const float* repetition_penalty; /* NULL or 1 => off; seen tokens: z > 0 ? z / r : z * r           */
+  const float* frequency_penalty;  /* NULL or 0 => off; seen tokens: z -= f * count                  */
+  const float* presence_penalty;   /* NULL or 0 => off; seen tokens: z -= p                          */
+  const int64_t* row_id;           /* NULL => batch position b.  Otherwise the id that keys the
+                                      row's random stream, so results do not depend on where a
+                                      sequence sits in the batch.                                    */
+} sip_params;
+
+/*
+ * Bytes of device scratch sip_sample() needs for this shape.  Depends only on its
+ * arguments; returns 0 for an invalid shape.  The workspace must be 256-byte aligned; its
+ * contents need not be preserved between calls and need not be initialised.
+ */
+size_t sip_workspace_bytes(int32_t B, int32_t V, sip_dtype dtype, int64_t hist_nnz, int32_t k_logprobs);
+
+/*
+ * Sample one token per row (Sec. 2.1 step 3 (1)-(3)).
+ *
+ *  logits        [B, row_stride] row-major, fp32 or bf16 (SIP_BF16: raw 16-bit patterns);
+ *                only the first V entries of a row are read; base pointer and
+ *                row_stride * sizeof(element) must be multiples of 16 bytes; never written.
+ *  params        host struct, see sip_params; NULL = every feature off.
+ *  hist_indptr   [B+1] CSR offsets into hist_tokens: row b's previously generated tokens
+ *                y_<s are hist_tokens[indptr[b] .. indptr[b+1]).  NULL (with hist_nnz = 0)
+ *                = no history, penalties do nothing.
+ *  hist_tokens   [hist_nnz] token ids; duplicates allowed (the count drives the frequency
+ *                penalty); ids outside [0, V) are ignored.
+ *  seed, step    key and counter of the Philox4x32-10 stream: counter = (row_id lo, row_id
+ *                hi, step lo, step hi), key = (seed lo, seed hi); the row's uniform is the
+ *                top 24 bits of output word 0 times 2^-24.
+ *  out_ids       [B] sampled token per row.
+ *  out_lp_ids    [B, 1 + k_logprobs] column 0: the sampled token; columns 1..k: the
+ *  out_lp        k_logprobs most probable tokens, descending, ties lowest index first, and
+ *                [B, 1 + k_logprobs] their log-probabilities = log-softmax over the full
+ *                vocabulary of the penalised, temperature-scaled logits, before any filter
+ *                (greedy rows: temperature taken as 1).  Both NULL iff k_logprobs < 0.
+ *  workspace     device scratch of at least sip_workspace_bytes(...) bytes.
+ *
+ * Returns SIP_OK once everything is enqueued.
+ */
+sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stride, sip_dtype dtype,
+                      const sip_params* params,
+                      const int64_t* hist_indptr, const int32_t* hist_tokens, int64_t hist_nnz,
+                      uint64_t seed, uint64_t step,
+                      int32_t* out_ids, int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Host string for a status code (static storage, never NULL). */
+const char* sip_status_string(sip_status status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int sip_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIP_H_ */

@@ -1,0 +1,146 @@
+"""ctypes binding of libsip.so: the same entry points as include/sip.h, with torch tensors
+standing in for device pointers.  Argument marshalling only -- every step of the sampling
+path runs in the library's kernels.  There is no fallback: without the compiled library
+(or without a GPU) the calls raise."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsip.so")
+
+SIP_F32, SIP_BF16 = 0, 1
+SIP_OK, SIP_ERR_INVALID_ARG, SIP_ERR_UNSUPPORTED, SIP_ERR_WORKSPACE, SIP_ERR_HIP = range(5)
+SIP_MAX_V = 1 << 19
+SIP_MAX_K_LOGPROBS = 64
+
+PARAM_FIELDS = ("temperature", "top_k", "top_p", "min_p", "repetition_penalty",
+                "frequency_penalty", "presence_penalty", "row_id")
+_PARAM_DTYPES = {"temperature": torch.float32, "top_k": torch.int32, "top_p": torch.float32,
+                 "min_p": torch.float32, "repetition_penalty": torch.float32,
+                 "frequency_penalty": torch.float32, "presence_penalty": torch.float32,
+                 "row_id": torch.int64}
+
+
+class SipParams(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in PARAM_FIELDS]
+
+
+class SipError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"sip_sample failed: {sip_status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libsip.so (built by paper_2506_22033_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2506_22033_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no fallback path")
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.sip_workspace_bytes.restype = ctypes.c_size_t
+        lib.sip_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_int64,
+                                            ctypes.c_int32]
+        lib.sip_sample.restype = ctypes.c_int
+        lib.sip_sample.argtypes = [
+            ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int,
+            ctypes.POINTER(SipParams), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+            ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        lib.sip_status_string.restype = ctypes.c_char_p
+        lib.sip_status_string.argtypes = [ctypes.c_int]
+        lib.sip_version.restype = ctypes.c_int
+        lib.sip_version.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def sip_version() -> int:
+    return int(load().sip_version())
+
+
+def sip_status_string(status: int) -> str:
+    return load().sip_status_string(int(status)).decode()
+
+
+def sip_workspace_bytes(B: int, V: int, dtype: int, hist_nnz: int, k_logprobs: int) -> int:
+    return int(load().sip_workspace_bytes(B, V, dtype, hist_nnz, k_logprobs))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def dtype_code(logits: torch.Tensor) -> int:
+    if logits.dtype == torch.float32:
+        return SIP_F32
+    if logits.dtype in (torch.bfloat16, torch.uint16, torch.int16):
+        return SIP_BF16
+    raise TypeError(f"logits must be float32 or bfloat16 (or raw 16-bit patterns), got {logits.dtype}")
+
+
+def make_params(params: Optional[Dict[str, Optional[torch.Tensor]]], B: int) -> SipParams:
+    sp = SipParams()
+    for name in PARAM_FIELDS:
+        t = None if params is None else params.get(name)
+        if t is not None:
+            if t.dtype != _PARAM_DTYPES[name] or t.numel() != B or not t.is_contiguous() or not t.is_cuda:
+                raise TypeError(f"params[{name!r}] must be a contiguous device tensor of {B} x {_PARAM_DTYPES[name]}")
+        setattr(sp, name, _ptr(t))
+    return sp
+
+
+def sip_sample(logits: torch.Tensor, params: Optional[Dict[str, Optional[torch.Tensor]]],
+               hist_indptr: Optional[torch.Tensor], hist_tokens: Optional[torch.Tensor],
+               seed: int, step: int, k_logprobs: int, *,
+               out_ids: Optional[torch.Tensor] = None, out_lp_ids: Optional[torch.Tensor] = None,
+               out_lp: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+               V: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None
+               ) -> Tuple[torch.Tensor, Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """Enqueue one sampling call on ``stream`` (default: torch's current stream).
+
+    ``logits`` is a 2-D device tensor whose rows are contiguous; ``V`` (default: its width)
+    may be smaller than the row stride.  Outputs and workspace are allocated with torch when
+    not supplied.  Returns (ids [B], logprob ids [B,1+k] or None, logprobs [B,1+k] or None)."""
+    lib = load()
+    if not logits.is_cuda or logits.dim() != 2 or logits.stride(1) != 1:
+        raise TypeError("logits must be a 2-D device tensor with contiguous rows")
+    B = logits.shape[0]
+    V = logits.shape[1] if V is None else int(V)
+    dt = dtype_code(logits)
+    dev = logits.device
+    nnz = 0
+    if hist_indptr is not None and hist_tokens is not None:
+        if hist_indptr.dtype != torch.int64 or hist_tokens.dtype != torch.int32:
+            raise TypeError("hist_indptr must be int64 and hist_tokens int32")
+        if hist_indptr.numel() != B + 1:
+            raise TypeError("hist_indptr must have B + 1 entries")
+        nnz = hist_tokens.numel()
+    if out_ids is None:
+        out_ids = torch.empty(B, dtype=torch.int32, device=dev)
+    if k_logprobs >= 0:
+        if out_lp_ids is None:
+            out_lp_ids = torch.empty(B, 1 + k_logprobs, dtype=torch.int32, device=dev)
+        if out_lp is None:
+            out_lp = torch.empty(B, 1 + k_logprobs, dtype=torch.float32, device=dev)
+    if workspace is None:
+        need = sip_workspace_bytes(B, V, dt, nnz, k_logprobs)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    sp = make_params(params, B)
+    s = torch.cuda.current_stream(dev) if stream is None else stream
+    status = lib.sip_sample(_ptr(logits), B, V, logits.stride(0), dt, ctypes.byref(sp),
+                            _ptr(hist_indptr) if nnz else None, _ptr(hist_tokens) if nnz else None, nnz,
+                            seed, step, _ptr(out_ids), _ptr(out_lp_ids), _ptr(out_lp), k_logprobs,
+                            _ptr(workspace), workspace.numel() * workspace.element_size(), s.cuda_stream)
+    if status != SIP_OK:
+        raise SipError(status)
+    return out_ids, out_lp_ids, out_lp

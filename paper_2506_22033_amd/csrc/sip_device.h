@@ -1,0 +1,111 @@
+// Device-side building blocks shared by the sampler kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sip.h"
+
+namespace sip {
+
+constexpr int kWave = 64;
+constexpr int kFixShift = 40;          // masses are carried as integers in units of 2^-40 of the row maximum's mass
+constexpr float kFixScale = 1099511627776.0f;   // 2^40
+
+// Everything one call needs, passed by value to the kernels.
+struct Args {
+  const void* logits;
+  int B, V;
+  long long row_stride;
+  sip_params p;
+  const long long* indptr;
+  const int* tokens;
+  long long nnz;
+  unsigned long long seed, step;
+  int* out_ids;
+  int* out_lp_ids;
+  float* out_lp;
+  int k_lp;
+  // workspace
+  float* side_z;          // [nnz]  penalised value of the r-th distinct history token of a row
+  unsigned int* side_c;   // [nnz]  its multiplicity
+};
+
+// ---------------------------------------------------------------- keys
+// Order-preserving map fp32 -> u32 (larger float <=> larger key); -0 and +0 share a key.
+__device__ __forceinline__ uint32_t key_of(float s) {
+  s = s + 0.0f;
+  uint32_t b = __float_as_uint(s);
+  return b ^ ((b & 0x80000000u) ? 0xFFFFFFFFu : 0x80000000u);
+}
+
+// ---------------------------------------------------------------- Philox4x32-10
+// Salmon et al., SC'11.  counter = (row lo, row hi, step lo, step hi), key = (seed lo, seed hi).
+__device__ __forceinline__ uint32_t philox_word0(unsigned long long seed, unsigned long long row,
+                                                 unsigned long long step) {
+  uint32_t c0 = (uint32_t)row, c1 = (uint32_t)(row >> 32), c2 = (uint32_t)step, c3 = (uint32_t)(step >> 32);
+  uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  return c0;
+}
+
+// ---------------------------------------------------------------- wave / block collectives
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+__device__ __forceinline__ unsigned long long shfl_u64(unsigned long long v, int src) {
+  int lo = __shfl((int)(uint32_t)v, src, kWave), hi = __shfl((int)(uint32_t)(v >> 32), src, kWave);
+  return ((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+__device__ __forceinline__ unsigned long long shfl_up_u64(unsigned long long v, int d) {
+  int lo = __shfl_up((int)(uint32_t)v, d, kWave), hi = __shfl_up((int)(uint32_t)(v >> 32), d, kWave);
+  return ((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int m) {
+  int lo = __shfl_xor((int)(uint32_t)v, m, kWave), hi = __shfl_xor((int)(uint32_t)(v >> 32), m, kWave);
+  return ((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += shfl_xor_u64(v, o);
+  return v;
+}
+// inclusive prefix sum across the 64 lanes
+__device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long long v) {
+  const int l = lane_id();
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    unsigned long long t = shfl_up_u64(v, d);
+    if (l >= d) v += t;
+  }
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+  const int l = lane_id();
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    uint32_t t = (uint32_t)__shfl_up((int)v, d, kWave);
+    if (l >= d) v += t;
+  }
+  return v;
+}
+
+// fp32 mass in (0, 1] -> integer units of 2^-40 (truncating); exact above 2^-16
+__device__ __forceinline__ unsigned long long fix_of(float e) {
+  return (unsigned long long)(e * kFixScale);
+}
+
+}  // namespace sip

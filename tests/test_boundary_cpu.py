@@ -1,0 +1,95 @@
+"""Host-side checks of the C boundary that need no GPU: the library loads, exports every
+symbol include/sip.h declares, sizes its workspace sensibly and rejects bad arguments on
+the host before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2506_22033_amd as sip
+from paper_2506_22033_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sip.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sip_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sip.load()
+    names = declared_functions()
+    assert {"sip_sample", "sip_workspace_bytes", "sip_status_string", "sip_version"} <= set(names)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert sip.sip_version() >= 100
+
+
+def test_status_strings():
+    seen = {sip.sip_status_string(s) for s in range(5)}
+    assert len(seen) == 5 and "ok" in seen
+    assert sip.sip_status_string(99) == "unknown status"
+
+
+def test_workspace_query():
+    small = sip.sip_workspace_bytes(4, 32000, sip.SIP_F32, 0, 5)
+    big = sip.sip_workspace_bytes(256, 152064, sip.SIP_F32, 256 * 1024, 20)
+    assert small > 0 and small % 256 == 0 and big % 256 == 0
+    assert big >= 256 * 1024 * 8
+    assert sip.sip_workspace_bytes(0, 10, sip.SIP_F32, 0, 0) == 0
+    assert sip.sip_workspace_bytes(1, 0, sip.SIP_F32, 0, 0) == 0
+    assert sip.sip_workspace_bytes(1, sip.SIP_MAX_V + 1, sip.SIP_F32, 0, 0) == 0
+    assert sip.sip_workspace_bytes(1, 10, 7, 0, 0) == 0
+    assert sip.sip_workspace_bytes(1, 10, sip.SIP_F32, -1, 0) == 0
+    assert sip.sip_workspace_bytes(1, 10, sip.SIP_F32, 0, sip.SIP_MAX_K_LOGPROBS + 1) == 0
+
+
+def _call(**over):
+    """sip_sample with fake but well-formed device addresses; every case below must be
+    rejected on the host, so nothing is ever dereferenced or launched."""
+    lib = sip.load()
+    a = dict(logits=0x10000, B=4, V=1000, stride=1000, dtype=sip.SIP_F32, params=None, indptr=None, tokens=None,
+             nnz=0, seed=0, step=0, out_ids=0x20000, out_lp_ids=0x30000, out_lp=0x40000, k=5,
+             ws=0x50000, ws_bytes=1 << 20, stream=None)
+    a.update(over)
+    p = a["params"]
+    return lib.sip_sample(a["logits"], a["B"], a["V"], a["stride"], a["dtype"],
+                          ctypes.byref(p) if p is not None else None, a["indptr"], a["tokens"], a["nnz"],
+                          a["seed"], a["step"], a["out_ids"], a["out_lp_ids"], a["out_lp"], a["k"],
+                          a["ws"], a["ws_bytes"], a["stream"])
+
+
+@pytest.mark.parametrize("over,want", [
+    (dict(B=0), binding.SIP_ERR_INVALID_ARG),
+    (dict(B=-3), binding.SIP_ERR_INVALID_ARG),
+    (dict(V=0), binding.SIP_ERR_INVALID_ARG),
+    (dict(logits=None), binding.SIP_ERR_INVALID_ARG),
+    (dict(out_ids=None), binding.SIP_ERR_INVALID_ARG),
+    (dict(dtype=5), binding.SIP_ERR_INVALID_ARG),
+    (dict(stride=999), binding.SIP_ERR_INVALID_ARG),                 # stride < V
+    (dict(stride=1001), binding.SIP_ERR_INVALID_ARG),                # rows not 16-byte aligned
+    (dict(logits=0x10004), binding.SIP_ERR_INVALID_ARG),             # base not 16-byte aligned
+    (dict(dtype=binding.SIP_BF16, stride=1004), binding.SIP_ERR_INVALID_ARG),
+    (dict(k=-1), binding.SIP_ERR_INVALID_ARG),                       # logprob buffers given but k < 0
+    (dict(out_lp=None), binding.SIP_ERR_INVALID_ARG),                # k >= 0 needs both buffers
+    (dict(k=-2, out_lp=None, out_lp_ids=None), binding.SIP_ERR_INVALID_ARG),
+    (dict(nnz=10), binding.SIP_ERR_INVALID_ARG),                     # history size without arrays
+    (dict(nnz=-1), binding.SIP_ERR_INVALID_ARG),
+    (dict(V=binding.SIP_MAX_V + 8, stride=binding.SIP_MAX_V + 8), binding.SIP_ERR_UNSUPPORTED),
+    (dict(k=binding.SIP_MAX_K_LOGPROBS + 1), binding.SIP_ERR_UNSUPPORTED),
+    (dict(ws=None), binding.SIP_ERR_WORKSPACE),
+    (dict(ws=0x50010), binding.SIP_ERR_WORKSPACE),                   # not 256-byte aligned
+    (dict(ws_bytes=16), binding.SIP_ERR_WORKSPACE),
+    (dict(nnz=1 << 20, indptr=0x60000, tokens=0x70000, ws_bytes=1 << 20), binding.SIP_ERR_WORKSPACE),
+])
+def test_bad_arguments_are_rejected_on_the_host(over, want):
+    assert _call(**over) == want
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        sip.sip_sample(torch.zeros(2, 8), None, None, None, 0, 0, 0)
