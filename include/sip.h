@@ -69,6 +69,12 @@ typedef struct {
  * Bytes of device scratch sip_sample() needs for this shape.  Depends only on its
  * arguments; returns 0 for an invalid shape.  The workspace must be 256-byte aligned; its
  * contents need not be preserved between calls and need not be initialised.
+ *
+ * Diagnostic: after a call has completed, the first B int32 of the workspace say which
+ * code path finished each row: 1 = the single-pass path (logits read once), any other value
+ * = the exact multi-pass path, the value naming the reason (2 no filter bounds the kept set
+ * or k too large, 3-13 the candidate list could not prove the answer, 14 vocabulary size
+ * outside the single-pass kernels).  Results are identical in meaning either way.
  */
 size_t sip_workspace_bytes(int32_t B, int32_t V, sip_dtype dtype, int64_t hist_nnz, int32_t k_logprobs);
 

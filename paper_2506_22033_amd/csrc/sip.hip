@@ -2,28 +2,86 @@
 // carving and kernel launches.  No allocation, no synchronisation.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <atomic>
+
 #include "../../include/sip.h"
 #include "sip_device.h"
 #include "sip_exact.h"
+#include "sip_final.h"
+#include "sip_stream.h"
 
 namespace {
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-struct Layout {
-  size_t side_z, side_c, total;
+// Launch shape of the single-pass path; a function of (B, V, dtype) only.
+struct Plan {
+  bool fast;       // false: vocabulary outside what the single-pass kernels are built for
+  int S, chunk_len, cap_w, nc_cap;
+  size_t final_lds;
 };
+
+constexpr int kFastMinV = 16384;
+constexpr int kFastMaxV = 262144;
+constexpr size_t kFinalLdsBudget = 144 * 1024;
+
+Plan make_plan(int32_t B, int32_t V, int dtype) {
+  Plan p{};
+  p.fast = V >= kFastMinV && V <= kFastMaxV;
+  if (!p.fast) return p;
+  const int tile = sip::kStreamThreads * sip::kStreamLoads * (dtype == SIP_F32 ? 4 : 8);
+  const int n_tiles = (V + tile - 1) / tile;
+  // Chunks per row.  Small batches: as many workgroups as fit on the chip at once (5 per compute
+  // unit), so that there is a single, full round.  Large batches: 8, which makes many rounds
+  // and lets the per-wave candidate queues (kQueueCap each) add up to 16K entries per row.
+  constexpr int kResident = 256 * 5;
+  int want = B * 8 <= kResident ? kResident / B : (B * 4 <= kResident ? kResident / B : 8);
+  want = std::max(1, std::min({want, sip::kMaxChunks, std::max(1, n_tiles / 2)}));
+  const int chunk_tiles = (n_tiles + want - 1) / want;
+  p.S = (n_tiles + chunk_tiles - 1) / chunk_tiles;     // every chunk non-empty
+  p.chunk_len = chunk_tiles * tile;
+  p.cap_w = sip::kQueueCap;
+  const size_t fixed = sip::final_lds_fixed(V);
+  size_t nc = (kFinalLdsBudget - fixed) / 8;
+  nc = std::min<size_t>(nc, 12288) / 64 * 64;
+  p.nc_cap = (int)nc;
+  p.final_lds = fixed + nc * 8;
+  return p;
+}
+
+struct Layout {
+  size_t row_path, side_z, side_c, chunks, cand, total;
+};
+
+// Kernels that use more than the default 64 KB of dynamic LDS have to be told so once.
+constexpr int kMaxDynLds = 144 * 1024;
+bool allow_big_lds(const void* kernel, int slot) {
+  static std::atomic<bool> done[4];
+  if (done[slot].load(std::memory_order_acquire)) return true;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  done[slot].store(true, std::memory_order_release);
+  return true;
+}
 
 bool shape_ok(int32_t B, int32_t V, int dtype, int64_t nnz, int32_t k_lp) {
   return B > 0 && V > 0 && (dtype == SIP_F32 || dtype == SIP_BF16) && nnz >= 0 && k_lp >= -1;
 }
 
-Layout make_layout(int32_t, int32_t, int64_t nnz) {
+Layout make_layout(int32_t B, const Plan& p, int64_t nnz) {
   Layout l;
   size_t off = 0;
+  l.row_path = off; off += align_up((size_t)B * sizeof(int) + 8 + 64 * 8);   // first, so that callers can find it
   l.side_z = off; off += align_up((size_t)nnz * sizeof(float));
   l.side_c = off; off += align_up((size_t)nnz * sizeof(unsigned int));
+  l.chunks = off;
+  if (p.fast) off += align_up((size_t)B * p.S * sizeof(sip::ChunkOut));
+  l.cand = off;
+  if (p.fast) off += align_up((size_t)B * p.S * sip::kStreamWaves * (size_t)p.cap_w * sizeof(uint2));
   l.total = off ? off : kAlign;
   return l;
 }
@@ -35,7 +93,7 @@ extern "C" {
 size_t sip_workspace_bytes(int32_t B, int32_t V, sip_dtype dtype, int64_t hist_nnz, int32_t k_logprobs) {
   if (!shape_ok(B, V, (int)dtype, hist_nnz, k_logprobs)) return 0;
   if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
-  return make_layout(B, V, hist_nnz).total;
+  return make_layout(B, make_plan(B, V, (int)dtype), hist_nnz).total;
 }
 
 sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stride, sip_dtype dtype,
@@ -52,7 +110,8 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
   if ((reinterpret_cast<uintptr_t>(logits) & 15u) != 0 || ((size_t)row_stride * esz) % 16 != 0)
     return SIP_ERR_INVALID_ARG;
   if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return SIP_ERR_UNSUPPORTED;
-  const Layout lay = make_layout(B, V, hist_nnz);
+  const Plan plan = make_plan(B, V, (int)dtype);
+  const Layout lay = make_layout(B, plan, hist_nnz);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 || workspace_bytes < lay.total)
     return SIP_ERR_WORKSPACE;
 
@@ -66,21 +125,31 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
   a.seed = seed; a.step = step;
   a.out_ids = out_ids; a.out_lp_ids = out_lp_ids; a.out_lp = out_lp; a.k_lp = k_logprobs;
   char* ws = static_cast<char*>(workspace);
+  a.row_path = reinterpret_cast<int*>(ws + lay.row_path);
   a.side_z = reinterpret_cast<float*>(ws + lay.side_z);
   a.side_c = reinterpret_cast<unsigned int*>(ws + lay.side_c);
+  a.chunks = reinterpret_cast<sip::ChunkOut*>(ws + lay.chunks);
+  a.cand = reinterpret_cast<uint2*>(ws + lay.cand);
+  a.S = plan.S; a.chunk_len = plan.chunk_len; a.cap_w = plan.cap_w; a.nc_cap = plan.nc_cap;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t words = ((size_t)V + 31) / 32;
-  const size_t dyn = 2 * words * sizeof(uint32_t);
-  auto kern = dtype == SIP_F32 ? sip::exact_kernel<SIP_F32> : sip::exact_kernel<SIP_BF16>;
-  if (dyn > 32 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)dyn) != hipSuccess) {
-      (void)hipGetLastError();
-      return SIP_ERR_HIP;
-    }
+  if (!plan.fast) {
+    // every row takes the exact multi-pass path
+    const size_t dyn = 2 * words * sizeof(uint32_t);
+    auto kern = dtype == SIP_F32 ? sip::exact_kernel<SIP_F32> : sip::exact_kernel<SIP_BF16>;
+    if (!allow_big_lds(reinterpret_cast<const void*>(kern), dtype == SIP_F32 ? 0 : 1)) return SIP_ERR_HIP;
+    hipLaunchKernelGGL(kern, dim3(B), dim3(sip::kExactThreads), dyn, stream, a);
+    if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
+    return SIP_OK;
   }
-  hipLaunchKernelGGL(kern, dim3(B), dim3(sip::kExactThreads), dyn, stream, a);
+  auto k_stream = dtype == SIP_F32 ? sip::stream_kernel<SIP_F32> : sip::stream_kernel<SIP_BF16>;
+  auto k_final = dtype == SIP_F32 ? sip::final_kernel<SIP_F32> : sip::final_kernel<SIP_BF16>;
+  const size_t dyn = std::max(plan.final_lds, 2 * words * sizeof(uint32_t));
+  if (!allow_big_lds(reinterpret_cast<const void*>(k_final), dtype == SIP_F32 ? 2 : 3)) return SIP_ERR_HIP;
+  hipLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, a);
+  if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
+  hipLaunchKernelGGL(k_final, dim3(B), dim3(sip::kFinalThreads), dyn, stream, a);
   if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
   return SIP_OK;
 }

@@ -11,6 +11,14 @@ constexpr int kWave = 64;
 constexpr int kFixShift = 40;          // masses are carried as integers in units of 2^-40 of the row maximum's mass
 constexpr float kFixScale = 1099511627776.0f;   // 2^40
 
+// What the streaming workgroup of one chunk leaves behind.
+struct ChunkOut {
+  unsigned long long bulk;  // sum over non-candidates of 2^(z*c - R), in units of 2^-30
+  float Tc;                 // every element of the chunk with z >= Tc is in a segment
+  int R;                    // integer reference exponent of `bulk`
+  unsigned int cnt[4];      // candidates found by each wave (may exceed cap_w: overflow)
+};
+
 // Everything one call needs, passed by value to the kernels.
 struct Args {
   const void* logits;
@@ -25,10 +33,27 @@ struct Args {
   int* out_lp_ids;
   float* out_lp;
   int k_lp;
-  // workspace
+  // workspace of the exact path
   float* side_z;          // [nnz]  penalised value of the r-th distinct history token of a row
   unsigned int* side_c;   // [nnz]  its multiplicity
+  // workspace and launch shape of the single-pass path
+  ChunkOut* chunks;         // [B * S]
+  uint2* cand;              // [B * S * 4 * cap_w]  (value bits, index)
+  int S;                    // chunks per row
+  int chunk_len;            // elements per chunk (multiple of the tile)
+  int cap_w;                // candidate slots per wave segment
+  int nc_cap;               // candidates the finishing kernel can hold in LDS
+  int* row_path;            // [B] diagnostic: 1 = finished by the single-pass path, >1 = exact path (reason)
 };
+
+// ApplyPenalty for one seen token: repetition, then frequency, then presence, one fp32
+// rounding per operation (Sec. 2.1 step 3 (1); Sec. 5.1).
+__device__ __forceinline__ float penalise(float z, unsigned int count, float theta, float phi, float psi) {
+  if (theta != 1.0f) z = (z > 0.0f) ? __fdiv_rn(z, theta) : __fmul_rn(z, theta);
+  if (phi != 0.0f) z = __fsub_rn(z, __fmul_rn(phi, (float)count));
+  if (psi != 0.0f) z = __fsub_rn(z, psi);
+  return z;
+}
 
 // ---------------------------------------------------------------- keys
 // Order-preserving map fp32 -> u32 (larger float <=> larger key); -0 and +0 share a key.
@@ -36,6 +61,9 @@ __device__ __forceinline__ uint32_t key_of(float s) {
   s = s + 0.0f;
   uint32_t b = __float_as_uint(s);
   return b ^ ((b & 0x80000000u) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ __forceinline__ float value_of(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
 }
 
 // ---------------------------------------------------------------- Philox4x32-10

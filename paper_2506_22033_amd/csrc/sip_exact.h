@@ -331,11 +331,10 @@ __device__ __forceinline__ int first_crossing(const RowView& r, unsigned long lo
 template <typename T>
 __device__ __forceinline__ T param_or(const T* p, int b, T dflt) { return p ? p[b] : dflt; }
 
+// One row, start to finish, by the calling 1024-thread workgroup.  `dyn` is 2 * ceil(V/32)
+// words of LDS.
 template <int DT>
-__global__ __launch_bounds__(kExactThreads) void exact_kernel(Args a) {
-  extern __shared__ uint32_t dyn[];
-  __shared__ ExactShared sh;
-  const int b = blockIdx.x;
+__device__ void exact_row(const Args& a, const int b, uint32_t* dyn, ExactShared& sh) {
   const int tid = threadIdx.x;
   const int V = a.V;
   const int W = (V + 31) >> 5;
@@ -410,14 +409,10 @@ __global__ __launch_bounds__(kExactThreads) void exact_kernel(Args a) {
       while (bits) {
         const int v = (w << 5) + __ffs((int)bits) - 1;
         bits &= bits - 1;
-        float z = load_one<DT>(raw, v);
-        if (theta != 1.0f) z = (z > 0.0f) ? __fdiv_rn(z, theta) : __fmul_rn(z, theta);
-        if (need_counts) {
-          const unsigned int c = __hip_atomic_load(&side_c[rank], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          z = __fsub_rn(z, __fmul_rn(phi, (float)c));
-        }
-        if (psi != 0.0f) z = __fsub_rn(z, psi);
-        side_z[rank] = z;
+        const float z = load_one<DT>(raw, v);
+        unsigned int c = 1;
+        if (need_counts) c = __hip_atomic_load(&side_c[rank], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        side_z[rank] = penalise(z, c, theta, phi, psi);
         ++rank;
       }
     }
@@ -546,6 +541,14 @@ __global__ __launch_bounds__(kExactThreads) void exact_kernel(Args a) {
       }
     }
   }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kExactThreads) void exact_kernel(Args a) {
+  extern __shared__ uint32_t dyn[];
+  __shared__ ExactShared sh;
+  exact_row<DT>(a, blockIdx.x, dyn, sh);
+  if (threadIdx.x == 0) a.row_path[blockIdx.x] = 14;     // 14: shape outside the single-pass kernels
 }
 
 }  // namespace sip

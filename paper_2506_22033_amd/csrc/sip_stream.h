@@ -1,0 +1,276 @@
+// Single pass over the logits: the only kernel that touches all B*V elements.
+//
+// A row is cut into S chunks, one 256-thread workgroup each.  The workgroup never learns the
+// row's maximum; instead it picks, from a 4096-element sample spread over the row, a value
+// threshold Tc such that only the top ~1-3 % of the row lies at or above it, and then streams
+// its chunk once:
+//   * elements >= Tc ("candidates") are collected, value and index, in per-wave LDS queues
+//     (a wave that finds more than its queue holds reports an overflow and the row falls back
+//     to the exact path) and written out to per-wave segments in the workspace at the end --
+//     every question that needs exact
+//     values (top-k, top-p, min-p, draw, best-n, maximum) is answered later from these few
+//     thousand entries per row;
+//   * all other elements only contribute their softmax mass 2^(z*c - R), c = log2(e)/tau,
+//     R = ceil(Tc*c), summed as integers in units of 2^-30 (so the sum does not depend on
+//     the order of accumulation).  Because z < Tc, every term is <= 1: no running maximum,
+//     no rescaling (Sec. 5.1 row-wise softmax, here fused with temperature scaling).
+// History penalties (Sec. 5.1 ApplyPenalty) touch at most |history| elements of a row and
+// are applied afterwards as a sparse correction by the finishing kernel.
+#pragma once
+#include "sip_device.h"
+
+namespace sip {
+
+constexpr int kStreamThreads = 256;
+constexpr int kStreamWaves = kStreamThreads / kWave;
+constexpr int kStreamLoads = 4;             // 16-byte loads per thread per tile
+constexpr int kSampleBins = 8192;           // 13-bit keys: sign, exponent, 4 mantissa bits
+constexpr int kSampleSize = 4096;           // elements of a row the threshold is estimated from
+constexpr int kQueueCap = 512;              // entries of one wave's LDS candidate queue
+constexpr float kBulkScale = 1073741824.0f; // 2^30
+
+// Per-row decisions shared by the streaming and the finishing kernel.
+struct RowParams {
+  float tau, top_p, min_p, theta, phi, psi;
+  int top_k;
+  unsigned long long row_id;
+  bool greedy;
+};
+
+__device__ __forceinline__ RowParams load_row_params(const Args& a, int b) {
+  RowParams r;
+  r.tau = a.p.temperature ? a.p.temperature[b] : 1.0f;
+  r.top_k = a.p.top_k ? a.p.top_k[b] : 0;
+  r.top_p = a.p.top_p ? a.p.top_p[b] : 1.0f;
+  r.min_p = a.p.min_p ? a.p.min_p[b] : 0.0f;
+  r.theta = a.p.repetition_penalty ? a.p.repetition_penalty[b] : 1.0f;
+  r.phi = a.p.frequency_penalty ? a.p.frequency_penalty[b] : 0.0f;
+  r.psi = a.p.presence_penalty ? a.p.presence_penalty[b] : 0.0f;
+  r.row_id = a.p.row_id ? (unsigned long long)a.p.row_id[b] : (unsigned long long)b;
+  r.greedy = (r.tau == 0.0f) || (r.top_k == 1);
+  return r;
+}
+
+// How many of the row's largest elements the candidate list should hold; 0 = this row
+// cannot be finished from a candidate list (nothing bounds its kept set, or k is too large)
+// and takes the exact multi-pass path instead.
+__device__ __forceinline__ int candidate_target(const RowParams& r, const Args& a) {
+  if (!(r.tau >= 0.0f)) return 0;
+  if (r.greedy) return 512;
+  const int k = (r.top_k >= 2 && r.top_k < a.V) ? r.top_k : 0;
+  if (k == 0 && !(r.top_p < 1.0f) && !(r.min_p > 0.0f)) return 0;
+  const int t = max(k + (k >> 1) + 512, 1536);
+  if (2 * t > a.nc_cap) return 0;
+  return t;
+}
+
+// log2(e)/tau as an unevaluated fp32 sum hi + lo (greedy rows: tau = 1)
+__device__ __forceinline__ void scale_pair(const RowParams& r, float& hi, float& lo) {
+  const double c = 1.4426950408889634074 / (r.greedy ? 1.0 : (double)r.tau);
+  hi = (float)c;
+  lo = (float)(c - (double)hi);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
+  constexpr int EPL = (DT == SIP_F32) ? 4 : 8;      // elements per 16-byte load
+  constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
+  constexpr int SUB = kStreamThreads * EPL;         // elements per workgroup-wide load
+  constexpr int TILE = SUB * kStreamLoads;
+  constexpr int SLOADS = kSampleSize / SUB;         // sample loads per thread (4 fp32, 2 bf16)
+  constexpr int NSB = SLOADS * kStreamWaves;        // 1 KB sample blocks spread over the row
+  // 16 KB of LDS, used first as the sample histogram (two 16-bit counters per word), then as
+  // four per-wave candidate queues
+  __shared__ __align__(16) unsigned char smem[kSampleBins * 2];
+  uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
+  __shared__ uint32_t red32[kStreamWaves];
+  __shared__ unsigned long long red64[kStreamWaves];
+  __shared__ uint32_t wave_cnt[kStreamWaves];
+  __shared__ uint32_t key_thr;
+
+  const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+  const int b = blockIdx.x / a.S, ch = blockIdx.x - b * a.S;
+  const RowParams rp = load_row_params(a, b);
+  const int target = candidate_target(rp, a);
+  if (target == 0) return;
+  const int V = a.V;
+  const int c0 = ch * a.chunk_len;
+  const int c1 = min(V, c0 + a.chunk_len);
+  if (c0 >= c1) return;                              // host guarantees every chunk is non-empty
+  const char* row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * ESZ;
+
+  // Loads are unconditional (a select on the loaded value would make the wave wait for it at
+  // once): lanes past the end of the chunk re-read its last 16 bytes and `process` discards
+  // what they hold by index.
+  const int e_last = ((c1 - 1) / EPL) * EPL;
+  auto load_tile = [&](int t0, uint4 (&buf)[kStreamLoads]) {
+#pragma unroll
+    for (int j = 0; j < kStreamLoads; ++j) {
+      const int e0 = min(t0 + j * SUB + tid * EPL, e_last);
+      buf[j] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);
+    }
+  };
+  auto unpack = [&](const uint4& q, float (&z)[EPL]) {
+    if (DT == SIP_F32) {
+      z[0] = __uint_as_float(q.x); z[1] = __uint_as_float(q.y);
+      z[2] = __uint_as_float(q.z); z[3] = __uint_as_float(q.w);
+    } else {
+      const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        z[2 * i] = __uint_as_float(w[i] << 16);
+        z[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+      }
+    }
+  };
+
+  // the first two tiles of the chunk are requested before anything else so that they travel
+  // while the threshold is being worked out
+  uint4 bufA[kStreamLoads], bufB[kStreamLoads];
+  int tA = c0, tB = c0 + TILE;
+  load_tile(tA, bufA);
+  if (tB < c1) load_tile(tB, bufB);
+
+  // ---- threshold: the same 4096-element sample (1 KB blocks spread evenly over the row) is
+  // read by every chunk of the row, so all chunks agree on Tc = the j-th largest sample value
+  // rounded down to a 13-bit key, j / 4096 = target / V
+  uint4 smp[SLOADS];
+#pragma unroll
+  for (int j = 0; j < SLOADS; ++j) {
+    const int sb = j * kStreamWaves + wave;
+    const int e0 = (int)(((long long)sb * V / NSB) / (kWave * EPL)) * (kWave * EPL) + lane * EPL;
+    smp[j] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);      // e0 + EPL <= V since V >= 16384
+  }
+  for (int i = tid; i < kSampleBins / 2; i += kStreamThreads) hist[i] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < SLOADS; ++j) {
+    float z[EPL];
+    unpack(smp[j], z);
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      const uint32_t k13 = key_of(z[i]) >> 19;
+      atomicAdd(&hist[k13 >> 1], (k13 & 1u) ? 0x10000u : 1u);
+    }
+  }
+  __syncthreads();
+  {
+    long long want = ((long long)target * kSampleSize + V - 1) / V;
+    if (want < 2) want = 2;
+    if (want > kSampleSize) want = kSampleSize;
+    const uint32_t j = (uint32_t)want;
+    constexpr int WPT = kSampleBins / 2 / kStreamThreads;      // words per thread (16)
+    const int wtop = kSampleBins / 2 - tid * WPT;              // thread 0 owns the highest bins
+    uint32_t local = 0;
+#pragma unroll
+    for (int i = 1; i <= WPT; ++i) { const uint32_t w = hist[wtop - i]; local += (w & 0xFFFFu) + (w >> 16); }
+    const uint32_t incl_w = wave_incl_scan_u32(local);
+    if (lane == kWave - 1) red32[wave] = incl_w;
+    __syncthreads();
+    uint32_t off = 0;
+    for (int w = 0; w < wave; ++w) off += red32[w];
+    const uint32_t incl = off + incl_w, excl = incl - local;
+    if (excl < j && j <= incl) {
+      uint32_t run = excl, found = 0;
+      for (int i = 1; i <= WPT; ++i) {
+        const uint32_t w = hist[wtop - i];
+        run += (w >> 16);
+        if (run >= j) { found = 2u * (uint32_t)(wtop - i) + 1u; break; }
+        run += (w & 0xFFFFu);
+        if (run >= j) { found = 2u * (uint32_t)(wtop - i); break; }
+      }
+      key_thr = found;
+    }
+    __syncthreads();                                 // also: the histogram is dead from here on
+  }
+  const uint32_t kb = key_thr << 19;
+  const float Tc = value_of(kb);
+  float chi, clo;
+  scale_pair(rp, chi, clo);
+  int R = 0;
+  {
+    const double tr = ceil((double)Tc * ((double)chi + (double)clo));
+    if (tr > -1048576.0 && tr < 1048576.0) R = (int)tr;
+  }
+  const float negR = -(float)R;
+
+  // ---- stream
+  uint2* queue = reinterpret_cast<uint2*>(smem) + wave * kQueueCap;          // this wave's LDS queue
+  uint2* seg = a.cand + ((size_t)blockIdx.x * kStreamWaves + wave) * (size_t)a.cap_w;
+  const uint32_t cap = (uint32_t)a.cap_w;
+  uint32_t qn = 0;                          // wave-uniform: candidates seen (entries beyond the queue are dropped)
+  unsigned long long acc = 0;
+
+  auto process = [&](const uint4& q, int e0, bool guard) {
+    float z[EPL];
+    unpack(q, z);
+    if (guard) {
+#pragma unroll
+      for (int i = 0; i < EPL; ++i)
+        if (e0 + i >= c1) z[i] = -INFINITY;
+    }
+    float g = 0.0f;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      const bool hit = z[i] >= Tc;
+      const unsigned long long mask = __ballot(hit);
+      if (mask) {
+        const uint32_t pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        if (hit && pos < (uint32_t)kQueueCap) queue[pos] = make_uint2(__float_as_uint(z[i]), (uint32_t)(e0 + i));
+        qn += (uint32_t)__popcll(mask);
+      }
+      float y = __fmaf_rn(z[i], chi, negR);
+      y = __fmaf_rn(z[i], clo, y);
+      y = fmaxf(y, -200.0f);                // also absorbs the NaN that -inf logits produce above
+      float e = __builtin_amdgcn_exp2f(y);
+      e = hit ? 0.0f : e;
+      g += e;
+      if ((i & 3) == 3) {                   // one conversion per aligned group of four
+        acc += (unsigned long long)(uint32_t)(g * kBulkScale);
+        g = 0.0f;
+      }
+    }
+  };
+  auto process_tile = [&](const uint4 (&buf)[kStreamLoads], int t0) {
+    const bool partial = t0 + TILE > c1;
+#pragma unroll
+    for (int j = 0; j < kStreamLoads; ++j) {
+      const int e0 = t0 + j * SUB + tid * EPL;
+      if (!partial) process(buf[j], e0, false);
+      else if (t0 + j * SUB < c1) process(buf[j], e0, true);     // workgroup-uniform condition
+    }
+  };
+
+  // two register buffers in ping-pong: while one tile is processed the other one's loads are
+  // in flight
+  while (true) {
+    process_tile(bufA, tA);
+    tA += 2 * TILE;
+    if (tA < c1) load_tile(tA, bufA);
+    if (tB >= c1) break;
+    process_tile(bufB, tB);
+    tB += 2 * TILE;
+    if (tB < c1) load_tile(tB, bufB);
+    if (tA >= c1) break;
+  }
+  // the queue goes out to the wave's segment in one burst (no global stores inside the loop:
+  // they would force every wait on a tile load to drain the whole memory queue)
+  for (uint32_t i = lane; i < min(qn, min(cap, (uint32_t)kQueueCap)); i += kWave) seg[i] = queue[i];
+
+  // ---- chunk summary
+  acc = wave_sum_u64(acc);
+  if (lane == 0) { red64[wave] = acc; wave_cnt[wave] = qn; }
+  __syncthreads();
+  if (tid == 0) {
+    ChunkOut o;
+    o.bulk = 0;
+#pragma unroll
+    for (int w = 0; w < kStreamWaves; ++w) { o.bulk += red64[w]; o.cnt[w] = wave_cnt[w]; }
+    o.Tc = Tc;
+    o.R = R;
+    a.chunks[blockIdx.x] = o;
+  }
+}
+
+}  // namespace sip

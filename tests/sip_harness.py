@@ -21,6 +21,7 @@ import torch
 import paper_2506_22033_amd as sip
 from oracle import sip_oracle as O
 
+last_row_path = None        # per-row code path of the most recent run_gpu() call (see include/sip.h)
 LP_ABS = 1e-5
 LP_REL = 2.0 ** -22
 DEV = "cuda:0"
@@ -71,8 +72,14 @@ def run_gpu(d: DeviceWorkload, seed: int, step: int, k_logprobs: Optional[int] =
     if row_ids is not None:
         params["row_id"] = row_ids
     k = d.k_logprobs if k_logprobs is None else k_logprobs
-    ids, lp_ids, lp = sip.sip_sample(d.logits, params, d.indptr, d.tokens, seed, step, k, V=d.V)
+    B = d.logits.shape[0]
+    nnz = 0 if d.tokens is None else d.tokens.numel()
+    need = sip.sip_workspace_bytes(B, d.V, sip.binding.dtype_code(d.logits), nnz, k)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=DEV)
+    ids, lp_ids, lp = sip.sip_sample(d.logits, params, d.indptr, d.tokens, seed, step, k, V=d.V, workspace=ws)
     torch.cuda.synchronize()
+    global last_row_path
+    last_row_path = ws[:4 * B].view(torch.int32).cpu().numpy().copy()
     return (ids.cpu().numpy(), None if lp_ids is None else lp_ids.cpu().numpy(),
             None if lp is None else lp.cpu().numpy())
 

@@ -13,16 +13,20 @@ pytestmark = pytest.mark.gpu
 def _run_and_compare(w, steps=(0, 1), rows=None, seed=0):
     d = H.to_device(w)
     total = H.ParityStats()
+    paths = {}
     for step in steps:
         out = H.run_gpu(d, seed, step)
+        for code, n in zip(*np.unique(H.last_row_path, return_counts=True)):
+            paths[int(code)] = paths.get(int(code), 0) + int(n)
         total.merge(H.compare(w, out, seed, step, rows=rows))
+    print(f"[parity] {w.name} B={w.B} V={w.V}: row paths {paths} (1 = single pass)", flush=True)
     print(f"[parity] {w.name} B={w.B} V={w.V}: rows={total.rows} greedy={total.greedy_rows} "
           f"flagged={total.flagged} flagged_mismatch={total.flagged_mismatch} "
           f"max|dlogprob|={total.max_lp_err:.3e} entries_over_1e-5={total.lp_needed_rel}", flush=True)
     # near-boundary rows may differ, but they must stay rare and mostly agree anyway
     assert total.flagged <= max(3, 0.25 * total.rows)
     assert total.flagged_mismatch <= max(1, 0.05 * total.rows)
-    return total
+    return total, paths
 
 
 # ---------------------------------------------------------------- reduced shapes: all rows, several tiles + ragged tail
@@ -43,7 +47,8 @@ def test_c2_full():
 
 
 def test_c3_full():
-    _run_and_compare(workloads.make(2), steps=(0,))
+    _, paths = _run_and_compare(workloads.make(2), steps=(0,))
+    assert paths.get(1, 0) >= 0.9 * 256          # the headline workload must run on the single-pass path
 
 
 def test_c4_full_sampled_rows():
