@@ -85,6 +85,9 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=2, help="0..4 = C1..C5 (default 2 = C3, the headline)")
     ap.add_argument("--cpu-rows", type=int, default=1024, help="row-samples the oracle is timed on (0 = skip)")
     ap.add_argument("--check", action="store_true", help="also compare step 0 with the oracle on 16 rows")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region run a plain 256 MiB device copy 4 times (reference for the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (rows are independent; see DESIGN.md for how the "
@@ -122,16 +125,33 @@ def main() -> int:
         sip.sip_sample(bufs[i % nbuf], d.params, d.indptr, d.tokens, 0, i, w.k_logprobs, out_ids=out_ids,
                        out_lp_ids=out_lp_ids, out_lp=out_lp, workspace=ws, V=w.V, stream=stream)
 
+    # Every `every`-th timed step is bracketed by HIP events on the launch stream, with a third
+    # event recorded by the library between its streaming kernel (the one pass over the logits,
+    # the dominant kernel) and its finishing kernel.
+    every = max(1, args.steps // 25)
+    marks = []
     with torch.cuda.stream(stream):
         for i in range(args.warmup):
             step(i)
+        trip = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(args.steps // every + 1)]
+        for t in trip:
+            for e in t:
+                e.record(stream)          # creates the underlying hipEvent_t
         torch.cuda.synchronize()
         ev0 = torch.cuda.Event(enable_timing=True)
         ev1 = torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
         ev0.record(stream)
         for i in range(args.steps):
-            step(args.warmup + i)
+            if i % every == 0:
+                a, m, b = trip[i // every]
+                a.record(stream)
+                sip.sip_profile_stage_event(m.cuda_event)
+                step(args.warmup + i)
+                b.record(stream)
+                marks.append((a, m, b))
+            else:
+                step(args.warmup + i)
         ev1.record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
@@ -139,7 +159,24 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
     launch_ms = gpu_ms / args.steps                 # HIP-event time per call on the launch stream
     alg = algorithmic_bytes(w)
-    achieved = alg / (launch_ms * 1e-3) / 1e9
+    path = ws[:4 * w.B].view(torch.int32).cpu().numpy()
+    single_pass_rows = int((path == 1).sum())
+    if single_pass_rows:
+        stream_ms = float(np.mean([a.elapsed_time(m) for a, m, b in marks]))
+        final_ms = float(np.mean([m.elapsed_time(b) for a, m, b in marks]))
+        dominant, dom_ms = "stream_kernel (single pass over the logits)", stream_ms
+    else:                                           # shape served by the exact multi-pass kernel alone
+        stream_ms = final_ms = None
+        dominant, dom_ms = "exact_kernel", launch_ms
+    achieved = alg / (dom_ms * 1e-3) / 1e9
+    whole_call = alg / (launch_ms * 1e-3) / 1e9
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     if args.check:
         out = H.run_gpu(d, 0, 0)
@@ -160,8 +197,12 @@ def main() -> int:
                    "logits_buffers_rotated": nbuf, "k_logprobs": w.k_logprobs},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(w.name),
-                     "algorithmic_bytes_per_launch": alg, "launch_ms_hip_events": launch_ms,
-                     "kernel": "whole sip_sample call"},
+                     "kernel": dominant, "kernel_ms_hip_events": dom_ms,
+                     "algorithmic_bytes_per_launch": alg,
+                     "finishing_kernel_ms_hip_events": final_ms,
+                     "whole_call_ms_hip_events": launch_ms, "whole_call_GBps": whole_call,
+                     "whole_call_frac": whole_call / HBM_PEAK_GBS,
+                     "rows_on_single_pass_path_last_step": single_pass_rows},
         "cpu_baseline": cpu,
     }
     print(json.dumps(res))

@@ -110,6 +110,15 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
                       int32_t* out_ids, int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Profiling aid.  Arms a one-shot hook on the calling host thread: the next sip_sample() call
+ * made by this thread that takes the single-pass path records `hip_event` (a hipEvent_t
+ * created by the caller) on its stream between the streaming kernel -- the one pass over the
+ * logits, Sec. 5.1's dense row-wise work -- and the finishing kernel, so that a caller can
+ * time the two separately with hipEventElapsedTime.  NULL disarms.  No effect on results.
+ */
+void sip_profile_stage_event(void* hip_event);
+
 /* Host string for a status code (static storage, never NULL). */
 const char* sip_status_string(sip_status status);
 

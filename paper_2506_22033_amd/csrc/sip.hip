@@ -55,6 +55,8 @@ struct Layout {
   size_t row_path, side_z, side_c, chunks, cand, total;
 };
 
+thread_local hipEvent_t g_stage_event = nullptr;
+
 // Kernels that use more than the default 64 KB of dynamic LDS have to be told so once.
 constexpr int kMaxDynLds = 144 * 1024;
 bool allow_big_lds(const void* kernel, int slot) {
@@ -149,6 +151,10 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
   if (!allow_big_lds(reinterpret_cast<const void*>(k_final), dtype == SIP_F32 ? 2 : 3)) return SIP_ERR_HIP;
   hipLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, a);
   if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
+  if (g_stage_event) {                       // one-shot profiling hook, see sip_profile_stage_event()
+    (void)hipEventRecord(g_stage_event, stream);
+    g_stage_event = nullptr;
+  }
   hipLaunchKernelGGL(k_final, dim3(B), dim3(sip::kFinalThreads), dyn, stream, a);
   if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
   return SIP_OK;
@@ -164,6 +170,8 @@ const char* sip_status_string(sip_status status) {
   }
   return "unknown status";
 }
+
+void sip_profile_stage_event(void* hip_event) { g_stage_event = static_cast<hipEvent_t>(hip_event); }
 
 int sip_version(void) { return 100; }
 

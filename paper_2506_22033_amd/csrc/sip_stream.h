@@ -71,6 +71,13 @@ __device__ __forceinline__ void scale_pair(const RowParams& r, float& hi, float&
   lo = (float)(c - (double)hi);
 }
 
+#ifdef SIP_TIMING
+#define SIP_SMARK(i) do { if (blockIdx.x == SIP_TIMING_BLOCK && threadIdx.x == 0) \
+    reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1))[16 + i] = wall_clock64(); } while (0)
+#else
+#define SIP_SMARK(i) do { } while (0)
+#endif
+
 template <int DT>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   constexpr int EPL = (DT == SIP_F32) ? 4 : 8;      // elements per 16-byte load
@@ -126,6 +133,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
 
   // the first two tiles of the chunk are requested before anything else so that they travel
   // while the threshold is being worked out
+  SIP_SMARK(0);
   uint4 bufA[kStreamLoads], bufB[kStreamLoads];
   int tA = c0, tB = c0 + TILE;
   load_tile(tA, bufA);
@@ -143,6 +151,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   }
   for (int i = tid; i < kSampleBins / 2; i += kStreamThreads) hist[i] = 0;
   __syncthreads();
+  SIP_SMARK(1);
 #pragma unroll
   for (int j = 0; j < SLOADS; ++j) {
     float z[EPL];
@@ -183,6 +192,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     }
     __syncthreads();                                 // also: the histogram is dead from here on
   }
+  SIP_SMARK(2);
   const uint32_t kb = key_thr << 19;
   const float Tc = value_of(kb);
   float chi, clo;
@@ -242,6 +252,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     }
   };
 
+  SIP_SMARK(3);
   // two register buffers in ping-pong: while one tile is processed the other one's loads are
   // in flight
   while (true) {
@@ -254,6 +265,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     if (tB < c1) load_tile(tB, bufB);
     if (tA >= c1) break;
   }
+  SIP_SMARK(4);
   // the queue goes out to the wave's segment in one burst (no global stores inside the loop:
   // they would force every wait on a tile load to drain the whole memory queue)
   for (uint32_t i = lane; i < min(qn, min(cap, (uint32_t)kQueueCap)); i += kWave) seg[i] = queue[i];
@@ -271,6 +283,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     o.R = R;
     a.chunks[blockIdx.x] = o;
   }
+  SIP_SMARK(5);
 }
 
 }  // namespace sip
