@@ -131,6 +131,43 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
   return v;
 }
 
+// ---------------------------------------------------------------- DPP wave collectives
+// Cross-lane sums and maxima that stay in the VALU (data-parallel-primitive row shifts and
+// row broadcasts) instead of going through the LDS crossbar.  Pattern: Hillis-Steele inside
+// each row of 16 lanes (row_shr 1,2,4,8), then lane 15 of rows 0/2 into rows 1/3
+// (row_bcast:15), then lane 31 into rows 2,3 (row_bcast:31).  Lane i ends up with the
+// inclusive result over lanes 0..i; lane 63 holds the wave total.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t old, uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+#define SIP_DPP_STEPS(OP, ID)                    \
+  v = OP(v, dpp_mov<0x111, 0xf>(ID, v));         \
+  v = OP(v, dpp_mov<0x112, 0xf>(ID, v));         \
+  v = OP(v, dpp_mov<0x114, 0xf>(ID, v));         \
+  v = OP(v, dpp_mov<0x118, 0xf>(ID, v));         \
+  v = OP(v, dpp_mov<0x142, 0xa>(ID, v));         \
+  v = OP(v, dpp_mov<0x143, 0xc>(ID, v));
+__device__ __forceinline__ uint32_t op_add(uint32_t a, uint32_t b) { return a + b; }
+__device__ __forceinline__ uint32_t op_max(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t op_min(uint32_t a, uint32_t b) { return a < b ? a : b; }
+__device__ __forceinline__ uint32_t dpp_scan_add_u32(uint32_t v) { SIP_DPP_STEPS(op_add, 0u) return v; }
+__device__ __forceinline__ uint32_t dpp_scan_max_u32(uint32_t v) { SIP_DPP_STEPS(op_max, 0u) return v; }
+__device__ __forceinline__ uint32_t dpp_scan_min_u32(uint32_t v) { SIP_DPP_STEPS(op_min, 0xFFFFFFFFu) return v; }
+#undef SIP_DPP_STEPS
+__device__ __forceinline__ unsigned long long dpp_scan_add_u64(unsigned long long v) {
+#define SIP_DPP64(CTRL, RM)                                                                   \
+  v += ((unsigned long long)dpp_mov<CTRL, RM>(0u, (uint32_t)(v >> 32)) << 32) | dpp_mov<CTRL, RM>(0u, (uint32_t)v);
+  SIP_DPP64(0x111, 0xf) SIP_DPP64(0x112, 0xf) SIP_DPP64(0x114, 0xf) SIP_DPP64(0x118, 0xf)
+  SIP_DPP64(0x142, 0xa) SIP_DPP64(0x143, 0xc)
+#undef SIP_DPP64
+  return v;
+}
+__device__ __forceinline__ uint32_t last_lane_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readlane((int)v, kWave - 1); }
+__device__ __forceinline__ unsigned long long last_lane_u64(unsigned long long v) {
+  return ((unsigned long long)last_lane_u32((uint32_t)(v >> 32)) << 32) | last_lane_u32((uint32_t)v);
+}
+
 // fp32 mass in (0, 1] -> integer units of 2^-40 (truncating); exact above 2^-16
 __device__ __forceinline__ unsigned long long fix_of(float e) {
   return (unsigned long long)(e * kFixScale);

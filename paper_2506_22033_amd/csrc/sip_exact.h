@@ -19,8 +19,8 @@
 
 namespace sip {
 
-constexpr int kExactThreads = 1024;
-constexpr int kExactWaves = kExactThreads / kWave;
+constexpr int kExactThreads = 1024;                   // the stand-alone kernel's workgroup; exact_row itself
+constexpr int kExactWaves = kExactThreads / kWave;    // adapts to any multiple of 64 up to this
 
 struct ExactShared {
   uint32_t hcnt[256];
@@ -114,8 +114,7 @@ __device__ __forceinline__ unsigned long long block_sum_u64(unsigned long long v
   if (lane_id() == 0) sh.red64[wave_id()] = v;
   __syncthreads();
   unsigned long long t = 0;
-#pragma unroll
-  for (int w = 0; w < kExactWaves; ++w) t += sh.red64[w];
+  for (int w = 0; w < ((int)blockDim.x >> 6); ++w) t += sh.red64[w];
   return t;
 }
 
@@ -126,8 +125,7 @@ __device__ __forceinline__ uint32_t block_excl_scan_u32(uint32_t v, ExactShared&
   if (lane_id() == kWave - 1) sh.red32[wave_id()] = incl;
   __syncthreads();
   uint32_t off = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < kExactWaves; ++w) {
+  for (int w = 0; w < ((int)blockDim.x >> 6); ++w) {
     const uint32_t t = sh.red32[w];
     if (w < wave_id()) off += t;
     tot += t;
@@ -331,10 +329,11 @@ __device__ __forceinline__ int first_crossing(const RowView& r, unsigned long lo
 template <typename T>
 __device__ __forceinline__ T param_or(const T* p, int b, T dflt) { return p ? p[b] : dflt; }
 
-// One row, start to finish, by the calling 1024-thread workgroup.  `dyn` is 2 * ceil(V/32)
-// words of LDS.
+// One row, start to finish, by the calling workgroup (any multiple of 64 threads up to 1024).
+// `dyn` is 2 * ceil(V/32) words of LDS.  Not inlined: it is the rarely taken path of the
+// finishing kernel and must not cost that kernel registers or instruction cache.
 template <int DT>
-__device__ void exact_row(const Args& a, const int b, uint32_t* dyn, ExactShared& sh) {
+__device__ __attribute__((noinline)) void exact_row(const Args& a, const int b, uint32_t* dyn, ExactShared& sh) {
   const int tid = threadIdx.x;
   const int V = a.V;
   const int W = (V + 31) >> 5;
@@ -344,7 +343,7 @@ __device__ void exact_row(const Args& a, const int b, uint32_t* dyn, ExactShared
   RowView r;
   r.row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * (DT == SIP_F32 ? 4 : 2);
   r.V = V;
-  r.wave_range = (((V + kExactWaves - 1) / kExactWaves) + 255) & ~255;
+  r.wave_range = (((V + ((int)blockDim.x >> 6) - 1) / ((int)blockDim.x >> 6)) + 255) & ~255;
   r.bm = bm; r.pre = pre;
   r.tau = param_or(a.p.temperature, b, 1.0f);
   const int top_k = param_or(a.p.top_k, b, 0);
@@ -368,14 +367,14 @@ __device__ void exact_row(const Args& a, const int b, uint32_t* dyn, ExactShared
   if (r.has_pen) {
     float* side_z = a.side_z + lo;
     unsigned int* side_c = a.side_c + lo;
-    for (int w = tid; w < W; w += kExactThreads) bm[w] = 0;
+    for (int w = tid; w < W; w += (int)blockDim.x) bm[w] = 0;
     __syncthreads();
-    for (long long i = lo + tid; i < hi; i += kExactThreads) {
+    for (long long i = lo + tid; i < hi; i += (int)blockDim.x) {
       const int t = a.tokens[i];
       if (t >= 0 && t < V) atomicOr(&bm[t >> 5], 1u << (t & 31));
     }
     __syncthreads();
-    const int per = (W + kExactThreads - 1) / kExactThreads;
+    const int per = (W + (int)blockDim.x - 1) / (int)blockDim.x;
     const int w0 = tid * per, w1 = min(W, w0 + per);
     uint32_t local = 0;
     for (int w = w0; w < w1; ++w) local += __popc(bm[w]);
@@ -385,10 +384,10 @@ __device__ void exact_row(const Args& a, const int b, uint32_t* dyn, ExactShared
     __syncthreads();
     const bool need_counts = (phi != 0.0f);
     if (need_counts) {
-      for (uint32_t i = tid; i < ndist; i += kExactThreads) side_c[i] = 0;
+      for (uint32_t i = tid; i < ndist; i += (int)blockDim.x) side_c[i] = 0;
       __threadfence();
       __syncthreads();
-      for (long long i = lo + tid; i < hi; i += kExactThreads) {
+      for (long long i = lo + tid; i < hi; i += (int)blockDim.x) {
         const int t = a.tokens[i];
         if (t >= 0 && t < V) {
           const uint32_t word = bm[t >> 5];
@@ -403,7 +402,7 @@ __device__ void exact_row(const Args& a, const int b, uint32_t* dyn, ExactShared
     // one fp32 rounding per operation
     RowView raw = r;
     raw.has_pen = false;
-    for (int w = tid; w < W; w += kExactThreads) {
+    for (int w = tid; w < W; w += (int)blockDim.x) {
       uint32_t bits = bm[w];
       uint32_t rank = pre[w];
       while (bits) {
@@ -435,7 +434,7 @@ __device__ void exact_row(const Args& a, const int b, uint32_t* dyn, ExactShared
   if (lane_id() == 0) { sh.redf[wave_id()] = best; sh.redi[wave_id()] = best_i; }
   __syncthreads();
   best = sh.redf[0]; best_i = sh.redi[0];
-  for (int w = 1; w < kExactWaves; ++w) {
+  for (int w = 1; w < ((int)blockDim.x >> 6); ++w) {
     const float ob = sh.redf[w]; const int oi = sh.redi[w];
     if (ob > best || (ob == best && oi < best_i)) { best = ob; best_i = oi; }
   }
@@ -501,7 +500,7 @@ __device__ void exact_row(const Args& a, const int b, uint32_t* dyn, ExactShared
       a.out_lp[(size_t)b * cols] = (float)((double)s - (double)r.m - lnZ);
     }
     const int n = min(a.k_lp, V);
-    for (int c = n + tid; c < a.k_lp; c += kExactThreads) {      // vocabulary smaller than k_logprobs
+    for (int c = n + tid; c < a.k_lp; c += (int)blockDim.x) {      // vocabulary smaller than k_logprobs
       a.out_lp_ids[(size_t)b * cols + 1 + c] = -1;
       a.out_lp[(size_t)b * cols + 1 + c] = -INFINITY;
     }

@@ -1,7 +1,7 @@
-// Finishing kernel of the single-pass path: one 1024-thread workgroup per row turns what the
-// streaming kernel left behind -- a few thousand (value, index) candidates that are complete
-// above a value threshold, plus the integer mass of everything else -- into the row's token,
-// its logprob and the best-n list, without reading the logits again (except for the at most
+// Finishing kernel of the single-pass path: one workgroup per row turns what the streaming
+// kernel left behind -- a few thousand (value, index) candidates that are complete above a
+// value threshold, plus the integer mass of everything else -- into the row's token, its
+// logprob and the best-n list, without reading the logits again (except for the at most
 // |history| elements that carry a penalty).
 //
 // The candidate list L is held in LDS.  Every sum is an integer sum (masses in units of 2^-40
@@ -22,13 +22,17 @@
 
 namespace sip {
 
-constexpr int kFinalThreads = kExactThreads;
+constexpr int kFinalThreads = 512;
 constexpr int kFinalWaves = kFinalThreads / kWave;
 constexpr int kBins = 2048;
+constexpr int kBinsPerThread = kBins / kFinalThreads;
 constexpr int kMembers = 256;        // entries of one bin that can be resolved by all-pairs comparison
 constexpr int kSideMax = 4096;       // distinct history tokens per row the fast path handles
 constexpr int kMaxChunks = 32;
 constexpr int kTopList = 320;        // entries at or above the bin of the n-th best
+constexpr int kTokRegs = 8;          // history tokens a thread keeps in registers between phases
+constexpr int kCandRegs = 8;         // candidate entries a thread requests ahead of time
+constexpr int kSideRegs = kSideMax / kFinalThreads;   // raw logits of side entries, likewise
 
 struct FastShared {
   float Tc[kMaxChunks];
@@ -38,15 +42,17 @@ struct FastShared {
   unsigned long long r64[kFinalWaves];
   long long rcorr[kFinalWaves];
   uint32_t r32[kFinalWaves];
-  float rf[kFinalWaves];
-  int ri[kFinalWaves];
-  uint32_t fail, ndist, nlist, anyc, dropped;
+  uint32_t rkey[kFinalWaves];
+  uint32_t ridx[kFinalWaves];
+  uint32_t fail_seg, ndist, nlist, anyc, dropped;
+  float m_out, zmax_out, trow_out;      // for a second attempt: max of s, max of z', threshold used
+  uint32_t rq_n;                         // candidates found by the second pass
   int bin_k, bin_n, bin_p, bin_low, bin_d;
-  uint32_t above_k, above_n, cnt_complete;
+  uint32_t above_k, above_n;
   uint32_t key_k, key_p, token_key;
   int token;
   unsigned long long s1_part, before_d;
-  uint32_t n_memb;
+  uint32_t n_memb, n_memb2, n_memb3;
   uint32_t m_key[kMembers];
   uint32_t m_idx[kMembers];
   unsigned long long m_E[kMembers];
@@ -56,7 +62,7 @@ struct FastShared {
   uint32_t t_bin[kTopList];
 };
 
-// Bytes of dynamic LDS the finishing kernel needs for vocabulary V and nc_cap candidates.
+// Bytes of dynamic LDS the finishing kernel needs for vocabulary V, before the candidates.
 __host__ __device__ inline size_t final_lds_fixed(int V) {
   const size_t W = ((size_t)V + 31) / 32;
   return ((W * 4 + W * 2 + 15) / 16) * 16 + (size_t)kBins * 12;
@@ -78,9 +84,11 @@ __device__ __forceinline__ float load_elem(const char* row, int v) {
 #endif
 
 template <int DT>
-__device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigned char* dyn, FastShared& fs) {
+__device__ __forceinline__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
+                                        FastShared& fs, const int S, const int chunk_len, const int cap_w) {
+  constexpr int NT = kFinalThreads;
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
-  const int V = a.V, S = a.S;
+  const int V = a.V;
   const int W = (V + 31) >> 5;
   // ---- LDS carving
   uint32_t* bm = reinterpret_cast<uint32_t*>(dyn);
@@ -90,53 +98,14 @@ __device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigne
   uint32_t* hc = reinterpret_cast<uint32_t*>(p2 + (size_t)kBins * 8);
   uint32_t* ck = reinterpret_cast<uint32_t*>(p2 + (size_t)kBins * 12);
   uint32_t* ci = ck + a.nc_cap;
+  uint32_t* cnt = reinterpret_cast<uint32_t*>(hm);         // kSideMax counters, before the bins are needed
   const uint32_t nc_cap = (uint32_t)a.nc_cap;
+  const uint32_t top = nc_cap - 1;                         // side entries grow downwards from here
   const char* row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * (DT == SIP_F32 ? 4 : 2);
-
   auto scaled_s = [&](float z) { return rp.greedy ? z : __fdiv_rn(z, rp.tau); };
-  // checkpoint: returns true (uniformly) if any thread has reported a failure so far
-  auto failed = [&]() {
-    __syncthreads();
-    const uint32_t f = fs.fail;
-    __syncthreads();
-    return f != 0;
-  };
 
   SIP_MARK(0);
-  // ---- (0) chunk summaries
-  if (tid == 0) {
-    fs.fail = 0; fs.ndist = 0; fs.nlist = 0; fs.anyc = 0; fs.dropped = 0;
-    fs.bin_k = -1; fs.bin_n = -1; fs.bin_p = 1 << 30; fs.bin_low = 1 << 30; fs.bin_d = -1;
-    fs.key_p = 0xFFFFFFFFu; fs.s1_part = 0; fs.n_memb = 0; fs.n_top = 0; fs.token = 0x7FFFFFFF;
-  }
-  if (tid < S) {
-    const ChunkOut co = a.chunks[(size_t)b * S + tid];
-    fs.Tc[tid] = co.Tc; fs.R[tid] = co.R; fs.bulk[tid] = co.bulk;
-#pragma unroll
-    for (int w = 0; w < kStreamWaves; ++w) fs.segoff[tid * kStreamWaves + w + 1] = co.cnt[w];
-  }
-  __syncthreads();
-  const int nseg = S * kStreamWaves;
-  if (tid < nseg && fs.segoff[tid + 1] > (uint32_t)a.cap_w) fs.fail = 1;      // a segment overflowed
-  float T_row = -INFINITY;
-  int R_max = -(1 << 30);
-  for (int c = 0; c < S; ++c) { T_row = fmaxf(T_row, fs.Tc[c]); R_max = max(R_max, fs.R[c]); }
-  if (!(T_row == T_row)) fs.fail = 1;
-  if (failed()) return 3;
-  // prefix of segment sizes (thread 0 .. nseg-1 each sum their predecessors; nseg <= 128)
-  uint32_t my_off = 0;
-  if (tid <= nseg)
-    for (int i = 1; i <= tid; ++i) my_off += fs.segoff[i];
-  __syncthreads();
-  if (tid <= nseg) fs.segoff[tid] = my_off;
-  __syncthreads();
-  const uint32_t total_seg = fs.segoff[nseg];
-
-  float chi, clo;
-  scale_pair(rp, chi, clo);
-
-  SIP_MARK(1);
-  // ---- (1) history: which tokens carry a penalty, how often they occur, their penalised value
+  // ---- (0) chunk summaries, history extent; clear the bitmap and the counters meanwhile
   long long lo = 0, hi = 0;
   if (a.indptr && a.tokens && a.nnz > 0) {
     lo = a.indptr[b]; hi = a.indptr[b + 1];
@@ -144,131 +113,227 @@ __device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigne
     hi = hi < lo ? lo : (hi > a.nnz ? a.nnz : hi);
   }
   const bool has_pen = (hi > lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
-  uint32_t ndist = 0;
-  long long corr = 0;               // mass the streaming pass counted for elements that carry a penalty
+  const int nseg = S * kStreamWaves;
+  if (tid == 0) {
+    fs.fail_seg = 0; fs.ndist = 0; fs.nlist = 0; fs.anyc = 0; fs.dropped = 0;
+    fs.bin_k = -1; fs.bin_n = -1; fs.bin_p = 1 << 30; fs.bin_low = 1 << 30; fs.bin_d = -1;
+    fs.key_p = 0xFFFFFFFFu; fs.s1_part = 0; fs.n_memb = 0; fs.n_memb2 = 0; fs.n_memb3 = 0; fs.n_top = 0;
+    fs.token = 0x7FFFFFFF;
+  }
+  if (tid < S) {
+    const ChunkOut co = a.chunks[(size_t)b * a.S + tid];
+    fs.Tc[tid] = co.Tc; fs.R[tid] = co.R; fs.bulk[tid] = co.bulk;
+#pragma unroll
+    for (int w = 0; w < kStreamWaves; ++w) fs.segoff[tid * kStreamWaves + w] = co.cnt[w];
+  }
+  // history tokens of this thread (the first kTokRegs rounds stay in registers)
+  int tok[kTokRegs];
+#pragma unroll
+  for (int j = 0; j < kTokRegs; ++j) {
+    const long long i = lo + tid + (long long)j * NT;
+    tok[j] = (has_pen && i < hi) ? a.tokens[i] : -1;
+  }
   if (has_pen) {
-    uint32_t* cnt = reinterpret_cast<uint32_t*>(hm);       // kSideMax counters, before the bins are needed
-    for (int w = tid; w < W; w += kFinalThreads) bm[w] = 0;
-    for (int i = tid; i < kSideMax; i += kFinalThreads) cnt[i] = 0;
-    __syncthreads();
-    for (long long i = lo + tid; i < hi; i += kFinalThreads) {
+    for (int w = tid; w < W; w += NT) bm[w] = 0;
+    for (int i = tid; i < kSideMax; i += NT) cnt[i] = 0;
+  }
+  __syncthreads();
+
+  SIP_MARK(1);
+  // ---- (1) prefix of the segment sizes (wave 0); presence bitmap of the history (everyone)
+  if (wave == 0) {
+    const uint32_t c0 = 2 * lane < nseg ? fs.segoff[2 * lane] : 0u;
+    const uint32_t c1 = 2 * lane + 1 < nseg ? fs.segoff[2 * lane + 1] : 0u;
+    const uint32_t incl = dpp_scan_add_u32(c0 + c1);
+    const uint32_t total = last_lane_u32(incl);
+    if (c0 > (uint32_t)cap_w || c1 > (uint32_t)cap_w) fs.fail_seg = 1;       // a queue overflowed
+    if (2 * lane < nseg) fs.segoff[2 * lane] = incl - c0 - c1;
+    if (2 * lane + 1 < nseg) fs.segoff[2 * lane + 1] = incl - c1;
+    if (lane == 0) fs.segoff[nseg] = total;
+  }
+  if (has_pen) {
+#pragma unroll
+    for (int j = 0; j < kTokRegs; ++j) {
+      const int t = tok[j];
+      if (t >= 0 && t < V) atomicOr(&bm[t >> 5], 1u << (t & 31));
+    }
+    for (long long i = lo + tid + (long long)kTokRegs * NT; i < hi; i += NT) {
       const int t = a.tokens[i];
       if (t >= 0 && t < V) atomicOr(&bm[t >> 5], 1u << (t & 31));
     }
-    __syncthreads();
-    for (int w = tid; w < W; w += kFinalThreads) {
-      const uint32_t bits = bm[w];
-      if (bits) {
-        const uint32_t base = atomicAdd(&fs.ndist, (uint32_t)__popc(bits));
-        pre[w] = (unsigned short)min(base, 65535u);
-      }
+  }
+  float T_row = -INFINITY;
+  int R_max = -(1 << 30);
+  for (int c = 0; c < S; ++c) { T_row = fmaxf(T_row, fs.Tc[c]); R_max = max(R_max, fs.R[c]); }
+  __syncthreads();
+  if (fs.fail_seg || !(T_row == T_row)) return 3;                             // uniform
+  const uint32_t total_seg = fs.segoff[nseg];
+  if (total_seg > nc_cap) return 5;                                           // uniform
+
+  SIP_MARK(2);
+  // ---- (2) The two dependent global reads of this kernel -- the candidate segments and the raw
+  // logits of the history tokens -- are issued as early as their addresses are known and
+  // consumed as late as possible, with the LDS work in between.
+  // (2a) request this thread's share of the candidates (kCandRegs rounds live in registers)
+  const uint2* segs = a.cand + (size_t)b * (size_t)(a.S * kStreamWaves) * (size_t)a.cap_w;
+  auto cand_addr = [&](uint32_t i) -> const uint2* {       // i < total_seg
+    int s0 = 0, s1 = nseg;                                  // segoff[s0] <= i < segoff[s1]
+    while (s1 - s0 > 1) {
+      const int mid = (s0 + s1) >> 1;
+      if (fs.segoff[mid] <= i) s0 = mid; else s1 = mid;
     }
+    return segs + (size_t)s0 * cap_w + (i - fs.segoff[s0]);
+  };
+  uint2 creg[kCandRegs];
+#pragma unroll
+  for (int r = 0; r < kCandRegs; ++r) {
+    const uint32_t i = (uint32_t)(r * NT + tid);
+    creg[r] = i < total_seg ? *cand_addr(i) : make_uint2(0u, 0xFFFFFFFFu);
+  }
+  // (2b) slots of the distinct history tokens, in token order: each thread owns a contiguous
+  // run of bitmap words
+  uint32_t ndist = 0;
+  if (has_pen) {
+    const int per = (W + NT - 1) / NT;
+    const int w0 = tid * per, w1 = min(W, w0 + per);
+    uint32_t local = 0;
+    for (int w = w0; w < w1; ++w) local += (uint32_t)__popc(bm[w]);
+    const uint32_t incl = dpp_scan_add_u32(local);
+    if (lane == kWave - 1) fs.r32[wave] = incl;
     __syncthreads();
-    ndist = fs.ndist;
-    if (ndist > (uint32_t)kSideMax || ndist > nc_cap) return 4;       // uniform: nothing written yet
-    if (rp.phi != 0.0f) {
-      for (long long i = lo + tid; i < hi; i += kFinalThreads) {
-        const int t = a.tokens[i];
-        if (t >= 0 && t < V) {
-          const uint32_t word = bm[t >> 5];
-          atomicAdd(&cnt[pre[t >> 5] + __popc(word & ((1u << (t & 31)) - 1u))], 1u);
-        }
-      }
-      __syncthreads();
+    uint32_t slot = incl - local;
+#pragma unroll
+    for (int ww = 0; ww < kFinalWaves; ++ww) {
+      const uint32_t t = fs.r32[ww];
+      if (ww < wave) slot += t;
+      ndist += t;
     }
-    for (int w = tid; w < W; w += kFinalThreads) {
+    if (ndist > (uint32_t)kSideMax || ndist > nc_cap) return 4;               // uniform
+    for (int w = w0; w < w1; ++w) {
       uint32_t bits = bm[w];
-      uint32_t slot = pre[w];
-      while (bits) {
-        const int v = (w << 5) + __ffs((int)bits) - 1;
+      if (bits) pre[w] = (unsigned short)slot;
+      while (bits) {                                                          // token of each slot
+        ci[top - slot] = (uint32_t)((w << 5) + __ffs((int)bits) - 1);
         bits &= bits - 1;
-        const float raw = load_elem<DT>(row, v);
-        ck[slot] = __float_as_uint(penalise(raw, cnt[slot], rp.theta, rp.phi, rp.psi));
-        ci[slot] = (uint32_t)v;
-        // the streaming pass saw the raw value: if it was below its chunk's threshold it went
-        // into the bulk sum and has to come out again
-        const int c = v / a.chunk_len;
-        if (!(raw >= fs.Tc[c])) {
-          const float zb = fmaxf(raw, -3.0e38f);
-          float y = __fmaf_rn(zb, chi, -(float)fs.R[c]);
-          y = __fmaf_rn(zb, clo, y);
-          const unsigned long long u = (unsigned long long)(uint32_t)(__builtin_amdgcn_exp2f(y) * kBulkScale);
-          const int sh = R_max - fs.R[c];
-          corr += (long long)(sh < 64 ? (u >> sh) : 0ull);
-        }
         ++slot;
       }
     }
+    __syncthreads();
   }
+  SIP_MARK(11);
+  // (2c) request the raw logits of this thread's side entries
+  float raw[kSideRegs];
+#pragma unroll
+  for (int r = 0; r < kSideRegs; ++r) {
+    const uint32_t i = (uint32_t)(r * NT + tid);
+    raw[r] = i < ndist ? load_elem<DT>(row, (int)ci[top - i]) : 0.0f;
+  }
+  // (2d) candidates -> LDS; entries that carry a penalty are dropped here and come back with
+  // their penalised value in (4)
+  auto append = [&](const uint2& e, bool valid) {
+    bool keep = valid && e.y < (uint32_t)V;
+    if (keep && has_pen) keep = ((bm[e.y >> 5] >> (e.y & 31)) & 1u) == 0;
+    const unsigned long long mask = __ballot(keep);
+    uint32_t wbase = 0;
+    if (lane == 0 && mask) wbase = atomicAdd(&fs.nlist, (uint32_t)__popcll(mask));
+    wbase = (uint32_t)__builtin_amdgcn_readfirstlane((int)wbase);
+    if (keep) {
+      const uint32_t pos = wbase + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                       __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+      ck[pos] = e.x; ci[pos] = e.y;                // pos < total_seg <= nc_cap
+    }
+  };
+#pragma unroll
+  for (int r = 0; r < kCandRegs; ++r)
+    if ((uint32_t)(r * NT) < total_seg) append(creg[r], (uint32_t)(r * NT + tid) < total_seg);   // uniform condition
+  for (uint32_t base = (uint32_t)(kCandRegs * NT); base < total_seg; base += NT) {
+    const uint32_t i = base + tid;
+    uint2 e = make_uint2(0u, 0xFFFFFFFFu);
+    if (i < total_seg) e = *cand_addr(i);
+    append(e, i < total_seg);
+  }
+  // ---- (3) multiplicities of the history tokens
+  if (has_pen && rp.phi != 0.0f) {
+    auto count = [&](int t) {
+      if (t >= 0 && t < V) {
+        const uint32_t word = bm[t >> 5];
+        atomicAdd(&cnt[pre[t >> 5] + __popc(word & ((1u << (t & 31)) - 1u))], 1u);
+      }
+    };
+#pragma unroll
+    for (int j = 0; j < kTokRegs; ++j) count(tok[j]);
+    for (long long i = lo + tid + (long long)kTokRegs * NT; i < hi; i += NT) count(a.tokens[i]);
+  }
+  __syncthreads();
+  const uint32_t n_unpen = fs.nlist;
+  const uint32_t nlist = n_unpen + ndist;
+  if (nlist > nc_cap || nlist == 0) return 5;                                 // uniform
+  // list position i -> LDS index: unpenalised candidates first, side entries from the top
+  auto at = [&](uint32_t i) { return i < n_unpen ? i : top - (i - n_unpen); };
 
-  SIP_MARK(2);
-  // ---- (2) candidates of all segments -> LDS, minus the ones that carry a penalty
-  {
-    const uint2* segs = a.cand + (size_t)b * (size_t)nseg * (size_t)a.cap_w;
-    for (uint32_t base = 0; base < total_seg; base += kFinalThreads) {
-      const uint32_t i = base + tid;
-      bool keep = false;
-      uint2 e = make_uint2(0, 0);
-      if (i < total_seg) {
-        int s0 = 0, s1 = nseg;                     // segoff[s0] <= i < segoff[s1]
-        while (s1 - s0 > 1) {
-          const int mid = (s0 + s1) >> 1;
-          if (fs.segoff[mid] <= i) s0 = mid; else s1 = mid;
-        }
-        e = segs[(size_t)s0 * a.cap_w + (i - fs.segoff[s0])];
-        keep = e.y < (uint32_t)V;
-        if (keep && has_pen) keep = ((bm[e.y >> 5] >> (e.y & 31)) & 1u) == 0;
+  SIP_MARK(4);
+  // ---- (4) penalised values of the side entries; maximum of the list (lowest index on ties)
+  float chi, clo;
+  scale_pair(rp, chi, clo);
+  long long corr = 0;               // mass the streaming pass counted for elements that carry a penalty
+  uint32_t bkey = 0, bidx = 0xFFFFFFFFu;
+  bool anyc = false;
+#pragma unroll
+  for (int r = 0; r < kSideRegs; ++r) {
+    const uint32_t i = (uint32_t)(r * NT + tid);
+    if (i < ndist) {
+      const uint32_t v = ci[top - i];
+      const float rv = raw[r];
+      const float zp = penalise(rv, cnt[i], rp.theta, rp.phi, rp.psi);
+      ck[top - i] = __float_as_uint(zp);
+      // the streaming pass saw the raw value: if it was below its chunk's threshold it went into
+      // the bulk sum and has to come out again
+      const int c = (int)v / chunk_len;
+      if (!(rv >= fs.Tc[c])) {
+        const float zb = fmaxf(rv, -3.0e38f);
+        float y = __fmaf_rn(zb, chi, -(float)fs.R[c]);
+        y = __fmaf_rn(zb, clo, y);
+        y = fmaxf(y, -200.0f);
+        const unsigned long long u = (unsigned long long)(uint32_t)(__builtin_amdgcn_exp2f(y) * kBulkScale);
+        const int sh = R_max - fs.R[c];
+        corr += (long long)(sh < 64 ? (u >> sh) : 0ull);
       }
-      const unsigned long long mask = __ballot(keep);
-      uint32_t wbase = 0;
-      if (lane == 0 && mask) wbase = atomicAdd(&fs.nlist, (uint32_t)__popcll(mask));
-      wbase = (uint32_t)__shfl((int)wbase, 0, kWave);
-      if (keep) {
-        const uint32_t pos = ndist + wbase + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                                 __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-        if (pos < nc_cap) { ck[pos] = e.x; ci[pos] = e.y; }
-      }
+      const uint32_t kz = key_of(zp);
+      if (kz > bkey || (kz == bkey && v < bidx)) { bkey = kz; bidx = v; }
     }
   }
-  __syncthreads();
-  const uint32_t nlist = ndist + fs.nlist;
-  if (nlist > nc_cap || nlist == 0) return 5;                           // uniform
-
-  SIP_MARK(3);
-  // ---- (3) maximum (lowest index on ties) and whether the list is complete where it matters
-  float best = -INFINITY;
-  int best_i = 0x7FFFFFFF;
-  bool anyc = false;
-  for (uint32_t i = tid; i < nlist; i += kFinalThreads) {
+  for (uint32_t i = tid; i < n_unpen; i += NT) {
     const float z = __uint_as_float(ck[i]);
-    const int v = (int)ci[i];
-    if (z > best || (z == best && v < best_i)) { best = z; best_i = v; }
-    anyc |= (i >= ndist) && (z >= T_row);
+    const uint32_t v = ci[i];
+    const uint32_t kz = key_of(z);
+    if (kz > bkey || (kz == bkey && v < bidx)) { bkey = kz; bidx = v; }
+    anyc |= z >= T_row;
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float ob = __shfl_xor(best, o, kWave);
-    const int oi = __shfl_xor(best_i, o, kWave);
-    if (ob > best || (ob == best && oi < best_i)) { best = ob; best_i = oi; }
+  {
+    const uint32_t wk = last_lane_u32(dpp_scan_max_u32(bkey));
+    const uint32_t wi = last_lane_u32(dpp_scan_min_u32(bkey == wk ? bidx : 0xFFFFFFFFu));
+    const unsigned long long uc = dpp_scan_add_u64((unsigned long long)corr);
+    if (lane == kWave - 1) { fs.rkey[wave] = wk; fs.ridx[wave] = wi; fs.rcorr[wave] = (long long)uc; }
+    if (__any(anyc) && lane == 0) fs.anyc = 1;
   }
-  corr = wave_sum((long long)corr);
-  if (lane == 0) { fs.rf[wave] = best; fs.ri[wave] = best_i; fs.rcorr[wave] = corr; }
-  if (__any(anyc) && lane == 0) fs.anyc = 1;
   __syncthreads();
-  best = fs.rf[0]; best_i = fs.ri[0];
-  long long corr_total = fs.rcorr[0];
-  for (int w = 1; w < kFinalWaves; ++w) {
-    const float ob = fs.rf[w]; const int oi = fs.ri[w];
-    if (ob > best || (ob == best && oi < best_i)) { best = ob; best_i = oi; }
+  long long corr_total = 0;
+  bkey = 0; bidx = 0xFFFFFFFFu;
+#pragma unroll
+  for (int w = 0; w < kFinalWaves; ++w) {
+    const uint32_t ok = fs.rkey[w], oi = fs.ridx[w];
+    if (ok > bkey || (ok == bkey && oi < bidx)) { bkey = ok; bidx = oi; }
     corr_total += fs.rcorr[w];
   }
   // an unpenalised candidate at or above T_row proves that nothing outside the list is larger
-  if (!fs.anyc || best_i == 0x7FFFFFFF) return 6;                       // uniform
-  const float m = scaled_s(best);
+  if (!fs.anyc || bidx == 0xFFFFFFFFu) return 6;                              // uniform
+  const int best_i = (int)bidx;
+  const float m = scaled_s(value_of(bkey));
   const float s_c = scaled_s(T_row);            // entries with s > s_c: every such element of the row is in L
   const uint32_t key_c = key_of(s_c);
+  if (tid == 0) { fs.m_out = m; fs.zmax_out = value_of(bkey); fs.trow_out = T_row; }
   const float span = __fsub_rn(m, s_c);
-  if (!(span >= 0.0f) || !(span < 3.0e38f)) return 7;                   // uniform
+  if (!(span >= 0.0f) || !(span < 3.0e38f)) return 7;                         // uniform
   const float binscale = span > 0.0f ? (float)(kBins - 2) / span : 0.0f;
   auto bin_of = [&](float s, uint32_t key) -> int {
     if (key <= key_c) return 0;
@@ -277,63 +342,67 @@ __device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigne
   };
   auto mass = [&](float s) { return fix_of(expf(__fsub_rn(s, m))); };
 
-  SIP_MARK(4);
-  // ---- (4) keys, value histogram (count and mass per bin), suffix sums
-  for (int i = tid; i < kBins; i += kFinalThreads) { hc[i] = 0; hm[i] = 0; }
+  SIP_MARK(5);
+  // ---- (5) keys, value histogram (count and mass per bin), suffix sums
+  for (int i = tid; i < kBins; i += NT) { hc[i] = 0; hm[i] = 0; }            // counters are dead since (4)
   __syncthreads();
-  for (uint32_t i = tid; i < nlist; i += kFinalThreads) {
-    const float s = scaled_s(__uint_as_float(ck[i]));
+  SIP_MARK(12);
+  for (uint32_t i = tid; i < nlist; i += NT) {
+    const uint32_t p = at(i);
+    const float s = scaled_s(__uint_as_float(ck[p]));
     const uint32_t key = key_of(s);
-    ck[i] = key;
+    ck[p] = key;
     const int bin = bin_of(s, key);
     atomicAdd(&hc[bin], 1u);
     const unsigned long long E = mass(s);
     if (E) atomicAdd(&hm[bin], E);
   }
   __syncthreads();
+  SIP_MARK(13);
   const bool k_act = !rp.greedy && rp.top_k >= 2 && rp.top_k < V;
   const uint32_t n_top = (uint32_t)max(0, min(a.k_lp, V));
   unsigned long long S_cand;
   {
-    // thread t owns bins kBins-1-2t (upper) and kBins-2-2t (lower); scan in descending bin order
-    const int bu = kBins - 1 - 2 * tid, bl = bu - 1;
-    const uint32_t cu = hc[bu], cl = hc[bl];
-    const unsigned long long mu = hm[bu], ml = hm[bl];
-    const uint32_t c2 = cu + cl;
-    const unsigned long long m2 = mu + ml;
-    const uint32_t cinc = wave_incl_scan_u32(c2);
-    const unsigned long long minc = wave_incl_scan_u64(m2);
+    // thread t owns bins kBins-1-4t .. kBins-4-4t; scan in descending bin order
+    const int b0 = kBins - 1 - kBinsPerThread * tid;
+    uint32_t c[kBinsPerThread];
+    unsigned long long w[kBinsPerThread];
+    uint32_t csum = 0;
+    unsigned long long msum = 0;
+#pragma unroll
+    for (int j = 0; j < kBinsPerThread; ++j) { c[j] = hc[b0 - j]; w[j] = hm[b0 - j]; csum += c[j]; msum += w[j]; }
+    const uint32_t cinc = dpp_scan_add_u32(csum);
+    const unsigned long long minc = dpp_scan_add_u64(msum);
     if (lane == kWave - 1) { fs.r32[wave] = cinc; fs.r64[wave] = minc; }
     __syncthreads();
-    uint32_t coff = 0, ctot = 0;
-    unsigned long long moff = 0, mtot = 0;
-    for (int w = 0; w < kFinalWaves; ++w) {
-      if (w < wave) { coff += fs.r32[w]; moff += fs.r64[w]; }
-      ctot += fs.r32[w]; mtot += fs.r64[w];
+    uint32_t cex = cinc - csum;
+    unsigned long long mex = minc - msum, mtot = 0;
+#pragma unroll
+    for (int ww = 0; ww < kFinalWaves; ++ww) {
+      if (ww < wave) { cex += fs.r32[ww]; mex += fs.r64[ww]; }
+      mtot += fs.r64[ww];
     }
     S_cand = mtot;
-    const uint32_t cex_u = coff + cinc - c2, cex_l = cex_u + cu;          // entries in bins above
-    const unsigned long long mex_u = moff + minc - m2, mex_l = mex_u + mu;
-    hm[bu] = mex_u; hm[bl] = mex_l;                                        // exclusive suffix mass
-    if (tid == 0) fs.cnt_complete = ctot - hc[0];
-    // bins >= 1 only: bin 0 is the incomplete region
-    if (k_act) {
-      const uint32_t k = (uint32_t)rp.top_k;
-      if (bu >= 1 && cex_u < k && k <= cex_u + cu) { fs.bin_k = bu; fs.above_k = cex_u; }
-      if (bl >= 1 && cex_l < k && k <= cex_l + cl) { fs.bin_k = bl; fs.above_k = cex_l; }
+    const uint32_t k = (uint32_t)rp.top_k;
+    int mylow = 1 << 30;
+#pragma unroll
+    for (int j = 0; j < kBinsPerThread; ++j) {
+      const int bin = b0 - j;
+      hm[bin] = mex;                                                         // exclusive suffix mass
+      if (bin >= 1) {                                                        // bin 0 is the incomplete region
+        if (k_act && cex < k && k <= cex + c[j]) { fs.bin_k = bin; fs.above_k = cex; }
+        if (n_top > 0 && cex < n_top && n_top <= cex + c[j]) { fs.bin_n = bin; fs.above_n = cex; }
+        if (c[j]) mylow = bin;                                               // bins descend: the last one wins
+      }
+      cex += c[j]; mex += w[j];
     }
-    if (n_top > 0) {
-      if (bu >= 1 && cex_u < n_top && n_top <= cex_u + cu) { fs.bin_n = bu; fs.above_n = cex_u; }
-      if (bl >= 1 && cex_l < n_top && n_top <= cex_l + cl) { fs.bin_n = bl; fs.above_n = cex_l; }
-    }
-    if (bu >= 1 && cu) atomicMin(&fs.bin_low, bu);
-    if (bl >= 1 && cl) atomicMin(&fs.bin_low, bl);
+    const uint32_t wlow = last_lane_u32(dpp_scan_min_u32((uint32_t)mylow));
+    if (lane == kWave - 1 && wlow < (1u << 30)) atomicMin(&fs.bin_low, (int)wlow);
   }
   __syncthreads();
-  if ((k_act && fs.bin_k < 0) || (n_top > 0 && fs.bin_n < 0)) return 8;  // uniform: k-th / n-th not provably in L
+  if ((k_act && fs.bin_k < 0) || (n_top > 0 && fs.bin_n < 0)) return 8;      // uniform: k-th / n-th not provably in L
   const int bin_k = k_act ? fs.bin_k : 0, bin_n = fs.bin_n;
 
-  SIP_MARK(5);
   // bulk mass -> units of 2^-40 relative to the maximum
   unsigned long long bulk = 0;
   for (int c = 0; c < S; ++c) {
@@ -342,27 +411,30 @@ __device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigne
   }
   bulk = (long long)bulk > corr_total ? bulk - (unsigned long long)corr_total : 0ull;
   const double ln2 = 0.6931471805599453094, log2e = 1.4426950408889634074;
-  const double bulk_rel = (double)bulk * exp2((double)R_max + 10.0 - (double)m * (rp.greedy ? log2e : log2e));
+  const double bulk_rel = (double)bulk * exp2((double)R_max + 10.0 - (double)m * log2e);
   const unsigned long long S0 = S_cand + (bulk_rel < 9.0e18 ? (unsigned long long)bulk_rel : 0ull);
   const double lnZ = log((double)S0) - (double)kFixShift * ln2;
 
   SIP_MARK(6);
-  // ---- (5) gather the bin of the k-th largest and everything at or above the bin of the n-th best
-  for (uint32_t i = tid; i < nlist; i += kFinalThreads) {
-    const uint32_t key = ck[i];
-    const float s = value_of(key);
-    const int bin = bin_of(s, key);
-    if (k_act && bin == bin_k) {
-      const uint32_t q = atomicAdd(&fs.n_memb, 1u);
-      if (q < (uint32_t)kMembers) { fs.m_key[q] = key; fs.m_E[q] = mass(s); }
+  // ---- (6) gather the bin of the k-th largest and everything at or above the bin of the n-th best
+  if (k_act || n_top > 0) {
+    for (uint32_t i = tid; i < nlist; i += NT) {
+      const uint32_t p = at(i);
+      const uint32_t key = ck[p];
+      const float s = value_of(key);
+      const int bin = bin_of(s, key);
+      if (k_act && bin == bin_k) {
+        const uint32_t q = atomicAdd(&fs.n_memb, 1u);
+        if (q < (uint32_t)kMembers) { fs.m_key[q] = key; fs.m_E[q] = mass(s); }
+      }
+      if (n_top > 0 && bin >= bin_n) {
+        const uint32_t q = atomicAdd(&fs.n_top, 1u);
+        if (q < (uint32_t)kTopList) { fs.t_key[q] = key; fs.t_idx[q] = ci[p]; fs.t_bin[q] = (uint32_t)bin; }
+      }
     }
-    if (n_top > 0 && bin >= bin_n) {
-      const uint32_t q = atomicAdd(&fs.n_top, 1u);
-      if (q < (uint32_t)kTopList) { fs.t_key[q] = key; fs.t_idx[q] = ci[i]; fs.t_bin[q] = (uint32_t)bin; }
-    }
+    __syncthreads();
+    if (fs.n_memb > (uint32_t)kMembers || fs.n_top > (uint32_t)kTopList) return 9;   // uniform
   }
-  __syncthreads();
-  if (fs.n_memb > (uint32_t)kMembers || fs.n_top > (uint32_t)kTopList) return 9;   // uniform
   uint32_t key_k = 0;
   unsigned long long S1 = S0;
   if (k_act) {
@@ -370,6 +442,7 @@ __device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigne
     if ((uint32_t)tid < nm) {
       const uint32_t key = fs.m_key[tid];
       uint32_t gt = 0, ge = 0;
+#pragma unroll 8
       for (uint32_t q = 0; q < nm; ++q) { const uint32_t kq = fs.m_key[q]; gt += kq > key; ge += kq >= key; }
       if (gt < k_rem && k_rem <= ge) fs.key_k = key;
     }
@@ -378,15 +451,13 @@ __device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigne
     if ((uint32_t)tid < nm && fs.m_key[tid] >= key_k) atomicAdd(&fs.s1_part, fs.m_E[tid]);
     __syncthreads();
     S1 = hm[bin_k] + fs.s1_part;
-    __syncthreads();
-    if (tid == 0) fs.n_memb = 0;
   }
 
   int token = best_i;
   uint32_t token_key = key_of(m);
   if (!rp.greedy) {
     SIP_MARK(7);
-    // ---- (6) top-p
+    // ---- (7) top-p
     const bool minp_on = rp.min_p > 0.0f;
     const float t_minp = minp_on ? (float)log((double)rp.min_p) : 0.0f;
     // every element missing from L fails min-p  <=>  the completeness threshold itself fails it
@@ -397,109 +468,124 @@ __device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigne
       const unsigned long long limit = lim > 0.0 ? (unsigned long long)lim : 0ull;
       const int lowbin = k_act ? bin_k : 1;
       {
-        const int bu = kBins - 1 - 2 * tid, bl = bu - 1;
-        if (bu >= lowbin && hc[bu] && hm[bu] < limit) atomicMin(&fs.bin_p, bu);
-        if (bl >= lowbin && hc[bl] && hm[bl] < limit) atomicMin(&fs.bin_p, bl);
+        const int b0 = kBins - 1 - kBinsPerThread * tid;
+        int mine = 1 << 30;
+#pragma unroll
+        for (int j = 0; j < kBinsPerThread; ++j) {
+          const int bin = b0 - j;
+          if (bin >= lowbin && hc[bin] && hm[bin] < limit) mine = bin;       // bins descend: the last one wins
+        }
+        const uint32_t wmin = last_lane_u32(dpp_scan_min_u32((uint32_t)mine));
+        if (lane == kWave - 1 && wmin < (1u << 30)) atomicMin(&fs.bin_p, (int)wmin);
       }
       __syncthreads();
       const int bin_p = fs.bin_p;
-      if (bin_p >= kBins) return 10;                                      // uniform (p <= 0)
-      for (uint32_t i = tid; i < nlist; i += kFinalThreads) {
-        const uint32_t key = ck[i];
+  SIP_MARK(14);
+      if (bin_p >= kBins) return 10;                                          // uniform (p <= 0)
+      for (uint32_t i = tid; i < nlist; i += NT) {
+        const uint32_t key = ck[at(i)];
         const float s = value_of(key);
         if (key >= key_k && bin_of(s, key) == bin_p) {
-          const uint32_t q = atomicAdd(&fs.n_memb, 1u);
+          const uint32_t q = atomicAdd(&fs.n_memb2, 1u);
           if (q < (uint32_t)kMembers) { fs.m_key[q] = key; fs.m_E[q] = mass(s); }
         }
       }
       __syncthreads();
-      const uint32_t nm = fs.n_memb;
-      if (nm > (uint32_t)kMembers) return 9;                                 // uniform
+      const uint32_t nm = fs.n_memb2;
+  SIP_MARK(15);
+      if (nm > (uint32_t)kMembers) return 9;                                  // uniform
       if ((uint32_t)tid < nm) {
         const uint32_t key = fs.m_key[tid];
         unsigned long long G = hm[bin_p];
+#pragma unroll 8
         for (uint32_t q = 0; q < nm; ++q)
           if (fs.m_key[q] > key) G += fs.m_E[q];
         if (G < limit) atomicMin(&fs.key_p, key); else fs.dropped = 1;
       }
       __syncthreads();
       const bool inside = k_act || bin_p > fs.bin_low || fs.dropped != 0;
-      if (!inside && !minp_bounds) return 11;                             // uniform: the cut may lie below L
+      if (!inside && !minp_bounds) return 11;                                 // uniform: the cut may lie below L
       key_cut = max(key_k, fs.key_p);
-      __syncthreads();
-      if (tid == 0) fs.n_memb = 0;
     } else if (!k_act && !minp_bounds) {
-      return 12;                                                             // uniform: nothing bounds the kept set inside L
+      return 12;                                                              // uniform: nothing bounds the kept set inside L
     }
 
     SIP_MARK(8);
-    // ---- (7) draw: kept mass per index bin, prefix, then resolve inside the crossing bin
+    // ---- (8) draw: kept mass per index bin, prefix, then resolve inside the crossing bin
     auto kept = [&](float s, uint32_t key) {
       return key >= key_cut && key > key_c && (!minp_on || __fsub_rn(s, m) >= t_minp);
     };
     int ishift = 0;
     while (((V - 1) >> ishift) >= kBins) ++ishift;
+    __syncthreads();                                       // every reader of the suffix masses is done
+    for (int i = tid; i < kBins; i += NT) hm[i] = 0;
     __syncthreads();
-    for (int i = tid; i < kBins; i += kFinalThreads) hm[i] = 0;
-    __syncthreads();
-    for (uint32_t i = tid; i < nlist; i += kFinalThreads) {
-      const uint32_t key = ck[i];
+    for (uint32_t i = tid; i < nlist; i += NT) {
+      const uint32_t p = at(i);
+      const uint32_t key = ck[p];
       const float s = value_of(key);
       if (kept(s, key)) {
         const unsigned long long E = mass(s);
-        if (E) atomicAdd(&hm[ci[i] >> ishift], E);
+        if (E) atomicAdd(&hm[ci[p] >> ishift], E);
       }
     }
     __syncthreads();
     unsigned long long target;
     {
-      const unsigned long long m0 = hm[2 * tid], m1 = hm[2 * tid + 1];
-      const unsigned long long m2 = m0 + m1;
-      const unsigned long long minc = wave_incl_scan_u64(m2);
+      const int b0 = kBinsPerThread * tid;                 // ascending index order
+      unsigned long long w[kBinsPerThread], msum = 0;
+#pragma unroll
+      for (int j = 0; j < kBinsPerThread; ++j) { w[j] = hm[b0 + j]; msum += w[j]; }
+      const unsigned long long minc = dpp_scan_add_u64(msum);
       if (lane == kWave - 1) fs.r64[wave] = minc;
       __syncthreads();
-      unsigned long long moff = 0, S3 = 0;
-      for (int w = 0; w < kFinalWaves; ++w) {
-        if (w < wave) moff += fs.r64[w];
-        S3 += fs.r64[w];
+      unsigned long long ex = minc - msum, S3 = 0;
+#pragma unroll
+      for (int ww = 0; ww < kFinalWaves; ++ww) {
+        if (ww < wave) ex += fs.r64[ww];
+        S3 += fs.r64[ww];
       }
-      const unsigned long long j = philox_word0(a.seed, rp.row_id, a.step) >> 8;
-      target = (__umul64hi(j, S3) << 40) | ((j * S3) >> 24);               // floor(j * S3 / 2^24)
-      const unsigned long long ex0 = moff + minc - m2, ex1 = ex0 + m0;
-      if (ex0 <= target && target < ex0 + m0) { fs.bin_d = 2 * tid; fs.before_d = ex0; }
-      if (ex1 <= target && target < ex1 + m1) { fs.bin_d = 2 * tid + 1; fs.before_d = ex1; }
+      const unsigned long long j24 = philox_word0(a.seed, rp.row_id, a.step) >> 8;
+      target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);             // floor(j * S3 / 2^24)
+#pragma unroll
+      for (int j = 0; j < kBinsPerThread; ++j) {
+        if (ex <= target && target < ex + w[j]) { fs.bin_d = b0 + j; fs.before_d = ex; }
+        ex += w[j];
+      }
     }
     __syncthreads();
     const int bin_d = fs.bin_d;
-    if (bin_d < 0) return 13;                                             // uniform (no kept mass)
-    for (uint32_t i = tid; i < nlist; i += kFinalThreads) {
-      const uint32_t key = ck[i];
+    if (bin_d < 0) return 13;                                                 // uniform (no kept mass)
+    for (uint32_t i = tid; i < nlist; i += NT) {
+      const uint32_t p = at(i);
+      const uint32_t key = ck[p];
       const float s = value_of(key);
-      if ((int)(ci[i] >> ishift) == bin_d && kept(s, key)) {
-        const uint32_t q = atomicAdd(&fs.n_memb, 1u);
-        if (q < (uint32_t)kMembers) { fs.m_key[q] = key; fs.m_idx[q] = ci[i]; fs.m_E[q] = mass(s); }
+      if ((int)(ci[p] >> ishift) == bin_d && kept(s, key)) {
+        const uint32_t q = atomicAdd(&fs.n_memb3, 1u);
+        if (q < (uint32_t)kMembers) { fs.m_key[q] = key; fs.m_idx[q] = ci[p]; fs.m_E[q] = mass(s); }
       }
     }
     __syncthreads();
-    const uint32_t nm = fs.n_memb;
-    if (nm > (uint32_t)kMembers) return 9;                                   // uniform
+    const uint32_t nm = fs.n_memb3;
+    if (nm > (uint32_t)kMembers) return 9;                                    // uniform
     if ((uint32_t)tid < nm) {
       const uint32_t v = fs.m_idx[tid];
       unsigned long long C = fs.before_d;
+#pragma unroll 8
       for (uint32_t q = 0; q < nm; ++q)
         if (fs.m_idx[q] <= v) C += fs.m_E[q];
       if (C > target) atomicMin(&fs.token, (int)v);
     }
     __syncthreads();
     token = fs.token;
-    if (token == 0x7FFFFFFF) return 13;                                   // uniform
+    if (token == 0x7FFFFFFF) return 13;                                       // uniform
     if ((uint32_t)tid < nm && fs.m_idx[tid] == (uint32_t)token) fs.token_key = fs.m_key[tid];
     __syncthreads();
     token_key = fs.token_key;
   }
 
   SIP_MARK(9);
-  // ---- (8) outputs.  Past this point nothing can fail.
+  // ---- (9) outputs.  Past this point nothing can fail.
   if (tid == 0) a.out_ids[b] = token;
   if (a.k_lp >= 0) {
     const int cols = 1 + a.k_lp;
@@ -516,6 +602,7 @@ __device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigne
         if ((int)fs.t_bin[tid] > bin_n) sel = true;
         else {
           uint32_t rank = 0;
+#pragma unroll 8
           for (uint32_t q = 0; q < nt; ++q)
             if ((int)fs.t_bin[q] == bin_n) {
               const uint32_t kq = fs.t_key[q];
@@ -529,6 +616,7 @@ __device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigne
       __syncthreads();
       if (sel) {
         uint32_t pos = 0;
+#pragma unroll 8
         for (uint32_t q = 0; q < nt; ++q)
           if (fs.t_bin[q]) {
             const uint32_t kq = fs.t_key[q];
@@ -543,6 +631,85 @@ __device__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigne
   return 1;
 }
 
+// Second attempt for a row whose candidate list turned out too short: this workgroup reads
+// the row again (it is still in the last-level cache) with a lower threshold `Tc` and leaves
+// the result where the first attempt's data was: one segment of S*4*cap_w entries and one
+// chunk summary.  Same arithmetic as stream_kernel.
+template <int DT>
+__device__ __attribute__((noinline)) void restream_row(const Args& a, const int b, const RowParams& rp, const float Tc,
+                                                       FastShared& fs) {
+  constexpr int NT = kFinalThreads;
+  constexpr int EPL = (DT == SIP_F32) ? 4 : 8;
+  constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
+  const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+  const int V = a.V;
+  const char* row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * ESZ;
+  uint2* region = a.cand + (size_t)b * (size_t)(a.S * kStreamWaves) * (size_t)a.cap_w;
+  const uint32_t cap = (uint32_t)(a.S * kStreamWaves * a.cap_w);
+  float chi, clo;
+  scale_pair(rp, chi, clo);
+  int R = 0;
+  {
+    const double tr = ceil((double)Tc * ((double)chi + (double)clo));
+    if (tr > -1048576.0 && tr < 1048576.0) R = (int)tr;
+  }
+  const float negR = -(float)R;
+  __syncthreads();
+  if (tid == 0) fs.rq_n = 0;
+  __syncthreads();
+  unsigned long long acc = 0;
+  for (int e0 = tid * EPL; e0 < V; e0 += NT * EPL) {
+    const uint4 q = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);
+    float z[EPL];
+    if (DT == SIP_F32) {
+      z[0] = __uint_as_float(q.x); z[1] = __uint_as_float(q.y);
+      z[2] = __uint_as_float(q.z); z[3] = __uint_as_float(q.w);
+    } else {
+      const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        z[2 * i] = __uint_as_float(w[i] << 16);
+        z[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+      }
+    }
+    float g = 0.0f;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      if (e0 + i >= V) z[i] = -INFINITY;
+      const bool hit = z[i] >= Tc;
+      if (hit) {
+        const uint32_t pos = atomicAdd(&fs.rq_n, 1u);
+        if (pos < cap) region[pos] = make_uint2(__float_as_uint(z[i]), (uint32_t)(e0 + i));
+      }
+      float y = __fmaf_rn(z[i], chi, negR);
+      y = __fmaf_rn(z[i], clo, y);
+      y = fmaxf(y, -200.0f);
+      float e = __builtin_amdgcn_exp2f(y);
+      e = hit ? 0.0f : e;
+      g += e;
+      if ((i & 3) == 3) {
+        acc += (unsigned long long)(uint32_t)(g * kBulkScale);
+        g = 0.0f;
+      }
+    }
+  }
+  const unsigned long long wsum = dpp_scan_add_u64(acc);
+  if (lane == kWave - 1) fs.r64[wave] = wsum;
+  __syncthreads();
+  if (tid == 0) {
+    ChunkOut o;
+    o.bulk = 0;
+    for (int w = 0; w < kFinalWaves; ++w) o.bulk += fs.r64[w];
+    o.Tc = Tc; o.R = R;
+    o.cnt[0] = fs.rq_n; o.cnt[1] = 0; o.cnt[2] = 0; o.cnt[3] = 0;
+    a.chunks[(size_t)b * a.S] = o;
+  }
+  // what this workgroup wrote to global memory is read back by other waves of it
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
 template <int DT>
 __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a) {
   extern __shared__ __align__(16) unsigned char dynraw[];
@@ -551,12 +718,36 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a) {
   const int b = blockIdx.x;
   const RowParams rp = load_row_params(a, b);
   int how = 2;                                   // 2: not eligible for the single-pass path
-  if (candidate_target(rp, a) != 0) how = fast_row<DT>(a, b, rp, dynraw, fs);
+  int code = 0;
+  if (candidate_target(rp, a) != 0) {
+    how = fast_row<DT>(a, b, rp, dynraw, fs, a.S, a.chunk_len, a.cap_w);
+    if (how == 8 || how == 11 || how == 12) {
+      // The list was complete but too short.  Where min-p is on, the threshold that bounds the
+      // kept set is known exactly now that the maximum is; otherwise lower the threshold by a
+      // quarter of its distance to the maximum.  One retry, then the exact path.
+      __syncthreads();
+      const float m = fs.m_out, zmax = fs.zmax_out, t_old = fs.trow_out;
+      float t_new = t_old - 0.25f * (zmax - t_old);
+      if (rp.min_p > 0.0f && !rp.greedy) {
+        const float zt = (m + (float)log((double)rp.min_p)) * rp.tau;
+        t_new = fminf(t_new, zt - 1.0e-5f * fabsf(zt) - 1.0e-30f);
+        if (how != 8) t_new = zt - 1.0e-5f * fabsf(zt) - 1.0e-30f;
+      }
+      if (t_new < t_old) {
+        const Args copy = a;
+        restream_row<DT>(copy, b, rp, t_new, fs);
+        const int again = fast_row<DT>(a, b, rp, dynraw, fs, 1, 0x40000000, a.S * kStreamWaves * a.cap_w);
+        how = again == 1 ? 1 : 16 + again;       // 17..29: failed again after the retry
+        if (again == 1) code = 15;               // 15: finished by the retry (still one HBM pass)
+      }
+    }
+  }
   if (how != 1) {
     __syncthreads();
-    exact_row<DT>(a, b, reinterpret_cast<uint32_t*>(dynraw), ex);
+    const Args copy = a;        // only this copy has to live in memory for the out-of-line call
+    exact_row<DT>(copy, b, reinterpret_cast<uint32_t*>(dynraw), ex);
   }
-  if (threadIdx.x == 0) a.row_path[b] = how;
+  if (threadIdx.x == 0) a.row_path[b] = code ? code : how;
 }
 
 }  // namespace sip
