@@ -59,7 +59,6 @@ struct FastShared {
   uint32_t n_top;
   uint32_t t_key[kTopList];
   uint32_t t_idx[kTopList];
-  uint32_t t_bin[kTopList];
 };
 
 // Bytes of dynamic LDS the finishing kernel needs for vocabulary V, before the candidates.
@@ -184,11 +183,28 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     }
     return segs + (size_t)s0 * cap_w + (i - fs.segoff[s0]);
   };
+  // thread t takes list positions 8t .. 8t+7: one segment search, then it walks along
   uint2 creg[kCandRegs];
+  {
+    const uint32_t i0 = (uint32_t)(tid * kCandRegs);
+    int sg = 0;
+    if (i0 < total_seg) {
+      int s1 = nseg;
+      while (s1 - sg > 1) {
+        const int mid = (sg + s1) >> 1;
+        if (fs.segoff[mid] <= i0) sg = mid; else s1 = mid;
+      }
+    }
+    uint32_t lo_off = fs.segoff[sg], hi_off = fs.segoff[sg + 1];
 #pragma unroll
-  for (int r = 0; r < kCandRegs; ++r) {
-    const uint32_t i = (uint32_t)(r * NT + tid);
-    creg[r] = i < total_seg ? *cand_addr(i) : make_uint2(0u, 0xFFFFFFFFu);
+    for (int r = 0; r < kCandRegs; ++r) {
+      const uint32_t i = i0 + (uint32_t)r;
+      creg[r] = make_uint2(0u, 0xFFFFFFFFu);
+      if (i < total_seg) {
+        while (i >= hi_off) { ++sg; lo_off = hi_off; hi_off = fs.segoff[sg + 1]; }   // skips empty segments too
+        creg[r] = segs[(size_t)sg * cap_w + (i - lo_off)];
+      }
+    }
   }
   // (2b) slots of the distinct history tokens, in token order: each thread owns a contiguous
   // run of bitmap words
@@ -244,8 +260,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     }
   };
 #pragma unroll
-  for (int r = 0; r < kCandRegs; ++r)
-    if ((uint32_t)(r * NT) < total_seg) append(creg[r], (uint32_t)(r * NT + tid) < total_seg);   // uniform condition
+  for (int r = 0; r < kCandRegs; ++r) append(creg[r], (uint32_t)(tid * kCandRegs + r) < total_seg);
   for (uint32_t base = (uint32_t)(kCandRegs * NT); base < total_seg; base += NT) {
     const uint32_t i = base + tid;
     uint2 e = make_uint2(0u, 0xFFFFFFFFu);
@@ -273,8 +288,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
 
   SIP_MARK(4);
   // ---- (4) penalised values of the side entries; maximum of the list (lowest index on ties)
-  float chi, clo;
-  scale_pair(rp, chi, clo);
   long long corr = 0;               // mass the streaming pass counted for elements that carry a penalty
   uint32_t bkey = 0, bidx = 0xFFFFFFFFu;
   bool anyc = false;
@@ -290,12 +303,9 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       // the bulk sum and has to come out again
       const int c = (int)v / chunk_len;
       if (!(rv >= fs.Tc[c])) {
-        const float zb = fmaxf(rv, -3.0e38f);
-        float y = __fmaf_rn(zb, chi, -(float)fs.R[c]);
-        y = __fmaf_rn(zb, clo, y);
-        y = fmaxf(y, -200.0f);
-        const unsigned long long u = (unsigned long long)(uint32_t)(__builtin_amdgcn_exp2f(y) * kBulkScale);
-        const int sh = R_max - fs.R[c];
+        const BulkRef ref = make_bulk_ref(fs.Tc[c], rp);
+        const unsigned long long u = bulk_units(bulk_term(rv, ref));
+        const int sh = R_max - ref.R;
         corr += (long long)(sh < 64 ? (u >> sh) : 0ull);
       }
       const uint32_t kz = key_of(zp);
@@ -429,7 +439,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       }
       if (n_top > 0 && bin >= bin_n) {
         const uint32_t q = atomicAdd(&fs.n_top, 1u);
-        if (q < (uint32_t)kTopList) { fs.t_key[q] = key; fs.t_idx[q] = ci[p]; fs.t_bin[q] = (uint32_t)bin; }
+        if (q < (uint32_t)kTopList) { fs.t_key[q] = key; fs.t_idx[q] = ci[p]; }
       }
     }
     __syncthreads();
@@ -594,36 +604,21 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       a.out_lp[(size_t)b * cols] = (float)((double)value_of(token_key) - (double)m - lnZ);
     }
     if (n_top > 0) {
-      const uint32_t nt = fs.n_top, need = n_top - fs.above_n;     // entries wanted from the n-th best's own bin
-      bool sel = false;
-      uint32_t key = 0, v = 0;
+      // The gathered list holds every element at or above the bin of the n-th best, so an
+      // entry's rank in this list is its rank in the row.
+      const uint32_t nt = fs.n_top;
       if ((uint32_t)tid < nt) {
-        key = fs.t_key[tid]; v = fs.t_idx[tid];
-        if ((int)fs.t_bin[tid] > bin_n) sel = true;
-        else {
-          uint32_t rank = 0;
+        const uint32_t key = fs.t_key[tid], v = fs.t_idx[tid];
+        uint32_t rank = 0;
 #pragma unroll 8
-          for (uint32_t q = 0; q < nt; ++q)
-            if ((int)fs.t_bin[q] == bin_n) {
-              const uint32_t kq = fs.t_key[q];
-              rank += (kq > key || (kq == key && fs.t_idx[q] < v)) ? 1u : 0u;
-            }
-          sel = rank < need;
+        for (uint32_t q = 0; q < nt; ++q) {
+          const uint32_t kq = fs.t_key[q];
+          rank += (kq > key || (kq == key && fs.t_idx[q] < v)) ? 1u : 0u;
         }
-      }
-      __syncthreads();
-      if ((uint32_t)tid < nt) fs.t_bin[tid] = sel ? 1u : 0u;
-      __syncthreads();
-      if (sel) {
-        uint32_t pos = 0;
-#pragma unroll 8
-        for (uint32_t q = 0; q < nt; ++q)
-          if (fs.t_bin[q]) {
-            const uint32_t kq = fs.t_key[q];
-            pos += (kq > key || (kq == key && fs.t_idx[q] < v)) ? 1u : 0u;
-          }
-        a.out_lp_ids[(size_t)b * cols + 1 + pos] = (int)v;
-        a.out_lp[(size_t)b * cols + 1 + pos] = (float)((double)value_of(key) - (double)m - lnZ);
+        if (rank < n_top) {
+          a.out_lp_ids[(size_t)b * cols + 1 + rank] = (int)v;
+          a.out_lp[(size_t)b * cols + 1 + rank] = (float)((double)value_of(key) - (double)m - lnZ);
+        }
       }
     }
   }
@@ -646,54 +641,52 @@ __device__ __attribute__((noinline)) void restream_row(const Args& a, const int 
   const char* row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * ESZ;
   uint2* region = a.cand + (size_t)b * (size_t)(a.S * kStreamWaves) * (size_t)a.cap_w;
   const uint32_t cap = (uint32_t)(a.S * kStreamWaves * a.cap_w);
-  float chi, clo;
-  scale_pair(rp, chi, clo);
-  int R = 0;
-  {
-    const double tr = ceil((double)Tc * ((double)chi + (double)clo));
-    if (tr > -1048576.0 && tr < 1048576.0) R = (int)tr;
-  }
-  const float negR = -(float)R;
+  const BulkRef ref = make_bulk_ref(Tc, rp);
+  const int R = ref.R;
   __syncthreads();
   if (tid == 0) fs.rq_n = 0;
   __syncthreads();
-  unsigned long long acc = 0;
-  for (int e0 = tid * EPL; e0 < V; e0 += NT * EPL) {
-    const uint4 q = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);
-    float z[EPL];
-    if (DT == SIP_F32) {
-      z[0] = __uint_as_float(q.x); z[1] = __uint_as_float(q.y);
-      z[2] = __uint_as_float(q.z); z[3] = __uint_as_float(q.w);
-    } else {
-      const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+  float acc = 0.0f;
+  constexpr int UNR = 4;                                    // loads in flight per thread
+  for (int t0 = 0; t0 < V; t0 += UNR * NT * EPL) {
+    uint4 q[UNR];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        z[2 * i] = __uint_as_float(w[i] << 16);
-        z[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-      }
+    for (int u = 0; u < UNR; ++u) {
+      const int e0 = t0 + (u * NT + tid) * EPL;
+      q[u] = e0 < V ? *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ) : make_uint4(0, 0, 0, 0);
     }
-    float g = 0.0f;
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) {
-      if (e0 + i >= V) z[i] = -INFINITY;
-      const bool hit = z[i] >= Tc;
-      if (hit) {
-        const uint32_t pos = atomicAdd(&fs.rq_n, 1u);
-        if (pos < cap) region[pos] = make_uint2(__float_as_uint(z[i]), (uint32_t)(e0 + i));
+    for (int u = 0; u < UNR; ++u) {
+      const int e0 = t0 + (u * NT + tid) * EPL;
+      float z[EPL];
+      if (DT == SIP_F32) {
+        z[0] = __uint_as_float(q[u].x); z[1] = __uint_as_float(q[u].y);
+        z[2] = __uint_as_float(q[u].z); z[3] = __uint_as_float(q[u].w);
+      } else {
+        const uint32_t w[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          z[2 * i] = __uint_as_float(w[i] << 16);
+          z[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
       }
-      float y = __fmaf_rn(z[i], chi, negR);
-      y = __fmaf_rn(z[i], clo, y);
-      y = fmaxf(y, -200.0f);
-      float e = __builtin_amdgcn_exp2f(y);
-      e = hit ? 0.0f : e;
-      g += e;
-      if ((i & 3) == 3) {
-        acc += (unsigned long long)(uint32_t)(g * kBulkScale);
-        g = 0.0f;
+      float g = 0.0f;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        if (e0 + i >= V) z[i] = -INFINITY;
+        const bool hit = z[i] >= Tc;
+        if (hit) {
+          const uint32_t pos = atomicAdd(&fs.rq_n, 1u);
+          if (pos < cap) region[pos] = make_uint2(__float_as_uint(z[i]), (uint32_t)(e0 + i));
+        }
+        float e = bulk_term(z[i], ref);
+        e = hit ? 0.0f : e;
+        g += e;
       }
+      acc += g;
     }
   }
-  const unsigned long long wsum = dpp_scan_add_u64(acc);
+  const unsigned long long wsum = dpp_scan_add_u64(bulk_units(acc));
   if (lane == kWave - 1) fs.r64[wave] = wsum;
   __syncthreads();
   if (tid == 0) {

@@ -11,9 +11,10 @@
 //     values (top-k, top-p, min-p, draw, best-n, maximum) is answered later from these few
 //     thousand entries per row;
 //   * all other elements only contribute their softmax mass 2^(z*c - R), c = log2(e)/tau,
-//     R = ceil(Tc*c), summed as integers in units of 2^-30 (so the sum does not depend on
-//     the order of accumulation).  Because z < Tc, every term is <= 1: no running maximum,
-//     no rescaling (Sec. 5.1 row-wise softmax, here fused with temperature scaling).
+//     R = ceil(Tc*c).  Because z < Tc, every term is <= 1: no running maximum, no rescaling
+//     (Sec. 5.1 row-wise softmax, here fused with temperature scaling).  Each thread adds its
+//     terms in fp32 in a fixed order; the per-thread sums are combined as integers in units
+//     of 2^-30.
 // History penalties (Sec. 5.1 ApplyPenalty) touch at most |history| elements of a row and
 // are applied afterwards as a sparse correction by the finishing kernel.
 #pragma once
@@ -71,6 +72,32 @@ __device__ __forceinline__ void scale_pair(const RowParams& r, float& hi, float&
   lo = (float)(c - (double)hi);
 }
 
+// Softmax mass of a non-candidate element relative to the threshold: 2^((z - Tc) * c + r0)
+// with c = log2(e)/tau and r0 = Tc*c - ceil(Tc*c) in (-1, 0], i.e. 2^(z*c - R).  Taking the
+// difference to Tc first keeps the product small where the term is not negligible, so one
+// fp32 multiplier is accurate enough; z = -inf gives exactly 0.
+struct BulkRef {
+  float Tc, c, r0;
+  int R;
+};
+__device__ __forceinline__ BulkRef make_bulk_ref(float Tc, const RowParams& rp) {
+  float chi, clo;
+  scale_pair(rp, chi, clo);
+  const double tc = (double)Tc * ((double)chi + (double)clo);
+  BulkRef r;
+  r.Tc = Tc; r.c = chi; r.R = 0; r.r0 = 0.0f;
+  const double tr = ceil(tc);
+  if (tr > -1048576.0 && tr < 1048576.0) { r.R = (int)tr; r.r0 = (float)(tc - tr); }
+  return r;
+}
+__device__ __forceinline__ float bulk_term(float z, const BulkRef& r) {
+  return __builtin_amdgcn_exp2f(__fmaf_rn(__fsub_rn(z, r.Tc), r.c, r.r0));
+}
+// per-thread fp32 partial sum -> integer units of 2^-30
+__device__ __forceinline__ unsigned long long bulk_units(float acc) {
+  return acc > 0.0f ? (unsigned long long)(acc * kBulkScale) : 0ull;
+}
+
 #ifdef SIP_TIMING
 #define SIP_SMARK(i) do { if (blockIdx.x == SIP_TIMING_BLOCK && threadIdx.x == 0) \
     reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1))[16 + i] = wall_clock64(); } while (0)
@@ -96,7 +123,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   __shared__ uint32_t key_thr;
 
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
-  const int b = blockIdx.x / a.S, ch = blockIdx.x - b * a.S;
+  // Workgroups are handed to the 8 XCDs round-robin by their id.  The chunks of one row read
+  // the same sample, so they are renumbered to land on the same XCD (and its L2): id i works
+  // on logical chunk (i % 8) * (n / 8) + i / 8 when n, the grid size, is a multiple of 8.
+  int wg = blockIdx.x;
+  if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  const int b = wg / a.S, ch = wg - b * a.S;
   const RowParams rp = load_row_params(a, b);
   const int target = candidate_target(rp, a);
   if (target == 0) return;
@@ -152,28 +184,47 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   for (int i = tid; i < kSampleBins / 2; i += kStreamThreads) hist[i] = 0;
   __syncthreads();
   SIP_SMARK(1);
+  long long want = ((long long)target * kSampleSize + V - 1) / V;
+  if (want < 2) want = 2;
+  if (want > kSampleSize) want = kSampleSize;
+  const uint32_t j = (uint32_t)want;
+  {
+    // Only the upper tail of the sample matters.  When j is small, a thread enters just the
+    // three largest of its 16 keys: far fewer LDS atomics, and hardly any on the same word.
+    // (Should one thread hold more than three of the j largest, the threshold comes out a
+    // little low, which only lengthens the candidate list.)
+    const bool tail_only = j <= 128;                 // workgroup-uniform
+    uint32_t t0 = 0, t1 = 0, t2 = 0;
 #pragma unroll
-  for (int j = 0; j < SLOADS; ++j) {
-    float z[EPL];
-    unpack(smp[j], z);
+    for (int l = 0; l < SLOADS; ++l) {
+      float z[EPL];
+      unpack(smp[l], z);
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) {
-      const uint32_t k13 = key_of(z[i]) >> 19;
-      atomicAdd(&hist[k13 >> 1], (k13 & 1u) ? 0x10000u : 1u);
+      for (int i = 0; i < EPL; ++i) {
+        const uint32_t k13 = key_of(z[i]) >> 19;
+        if (tail_only) {
+          const uint32_t a1 = min(t0, k13); t0 = max(t0, k13);
+          const uint32_t a2 = min(t1, a1); t1 = max(t1, a1);
+          t2 = max(t2, a2);
+        } else {
+          atomicAdd(&hist[k13 >> 1], (k13 & 1u) ? 0x10000u : 1u);
+        }
+      }
+    }
+    if (tail_only) {
+      atomicAdd(&hist[t0 >> 1], (t0 & 1u) ? 0x10000u : 1u);
+      atomicAdd(&hist[t1 >> 1], (t1 & 1u) ? 0x10000u : 1u);
+      atomicAdd(&hist[t2 >> 1], (t2 & 1u) ? 0x10000u : 1u);
     }
   }
   __syncthreads();
   {
-    long long want = ((long long)target * kSampleSize + V - 1) / V;
-    if (want < 2) want = 2;
-    if (want > kSampleSize) want = kSampleSize;
-    const uint32_t j = (uint32_t)want;
     constexpr int WPT = kSampleBins / 2 / kStreamThreads;      // words per thread (16)
     const int wtop = kSampleBins / 2 - tid * WPT;              // thread 0 owns the highest bins
     uint32_t local = 0;
 #pragma unroll
     for (int i = 1; i <= WPT; ++i) { const uint32_t w = hist[wtop - i]; local += (w & 0xFFFFu) + (w >> 16); }
-    const uint32_t incl_w = wave_incl_scan_u32(local);
+    const uint32_t incl_w = dpp_scan_add_u32(local);
     if (lane == kWave - 1) red32[wave] = incl_w;
     __syncthreads();
     uint32_t off = 0;
@@ -195,21 +246,15 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   SIP_SMARK(2);
   const uint32_t kb = key_thr << 19;
   const float Tc = value_of(kb);
-  float chi, clo;
-  scale_pair(rp, chi, clo);
-  int R = 0;
-  {
-    const double tr = ceil((double)Tc * ((double)chi + (double)clo));
-    if (tr > -1048576.0 && tr < 1048576.0) R = (int)tr;
-  }
-  const float negR = -(float)R;
+  const BulkRef ref = make_bulk_ref(Tc, rp);
+  const int R = ref.R;
 
   // ---- stream
   uint2* queue = reinterpret_cast<uint2*>(smem) + wave * kQueueCap;          // this wave's LDS queue
-  uint2* seg = a.cand + ((size_t)blockIdx.x * kStreamWaves + wave) * (size_t)a.cap_w;
+  uint2* seg = a.cand + ((size_t)wg * kStreamWaves + wave) * (size_t)a.cap_w;
   const uint32_t cap = (uint32_t)a.cap_w;
   uint32_t qn = 0;                          // wave-uniform: candidates seen (entries beyond the queue are dropped)
-  unsigned long long acc = 0;
+  float acc = 0.0f;                         // this thread's bulk mass, fixed order of additions
 
   auto process = [&](const uint4& q, int e0, bool guard) {
     float z[EPL];
@@ -230,17 +275,11 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
         if (hit && pos < (uint32_t)kQueueCap) queue[pos] = make_uint2(__float_as_uint(z[i]), (uint32_t)(e0 + i));
         qn += (uint32_t)__popcll(mask);
       }
-      float y = __fmaf_rn(z[i], chi, negR);
-      y = __fmaf_rn(z[i], clo, y);
-      y = fmaxf(y, -200.0f);                // also absorbs the NaN that -inf logits produce above
-      float e = __builtin_amdgcn_exp2f(y);
+      float e = bulk_term(z[i], ref);
       e = hit ? 0.0f : e;
       g += e;
-      if ((i & 3) == 3) {                   // one conversion per aligned group of four
-        acc += (unsigned long long)(uint32_t)(g * kBulkScale);
-        g = 0.0f;
-      }
     }
+    acc += g;
   };
   auto process_tile = [&](const uint4 (&buf)[kStreamLoads], int t0) {
     const bool partial = t0 + TILE > c1;
@@ -271,8 +310,8 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   for (uint32_t i = lane; i < min(qn, min(cap, (uint32_t)kQueueCap)); i += kWave) seg[i] = queue[i];
 
   // ---- chunk summary
-  acc = wave_sum_u64(acc);
-  if (lane == 0) { red64[wave] = acc; wave_cnt[wave] = qn; }
+  const unsigned long long wsum = dpp_scan_add_u64(bulk_units(acc));      // integer from here on
+  if (lane == kWave - 1) { red64[wave] = wsum; wave_cnt[wave] = qn; }
   __syncthreads();
   if (tid == 0) {
     ChunkOut o;
@@ -281,7 +320,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     for (int w = 0; w < kStreamWaves; ++w) { o.bulk += red64[w]; o.cnt[w] = wave_cnt[w]; }
     o.Tc = Tc;
     o.R = R;
-    a.chunks[blockIdx.x] = o;
+    a.chunks[wg] = o;
   }
   SIP_SMARK(5);
 }
