@@ -155,6 +155,19 @@ def main() -> int:
         ev1.record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        # what a HIP-event pair reads with nothing but a trivial kernel in between: the fixed cost
+        # of the event packets and of one dispatch, which the per-kernel figures below include
+        base = []
+        tiny = torch.zeros(64, device=dev)
+        for _ in range(20):
+            e_a, e_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            tiny.add_(1.0)
+            e_a.record(stream)
+            tiny.add_(1.0)
+            e_b.record(stream)
+            torch.cuda.synchronize()
+            base.append(e_a.elapsed_time(e_b))
+    event_floor_ms = float(np.median(base))
     gpu_ms = ev0.elapsed_time(ev1)
     ms_per_step = wall * 1e3 / args.steps
     launch_ms = gpu_ms / args.steps                 # HIP-event time per call on the launch stream
@@ -198,6 +211,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(w.name),
                      "kernel": dominant, "kernel_ms_hip_events": dom_ms,
+                     "hip_event_pair_around_trivial_kernel_ms": event_floor_ms,
                      "algorithmic_bytes_per_launch": alg,
                      "finishing_kernel_ms_hip_events": final_ms,
                      "whole_call_ms_hip_events": launch_ms, "whole_call_GBps": whole_call,

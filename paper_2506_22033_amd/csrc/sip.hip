@@ -36,7 +36,7 @@ Plan make_plan(int32_t B, int32_t V, int dtype) {
   // Chunks per row.  Small batches: as many workgroups as fit on the chip at once (5 per compute
   // unit), so that there is a single, full round.  Large batches: 8, which makes many rounds
   // and lets the per-wave candidate queues (kQueueCap each) add up to 16K entries per row.
-  constexpr int kResident = 256 * 5;
+  constexpr int kResident = 256 * 8;
   int want = B * 8 <= kResident ? kResident / B : (B * 4 <= kResident ? kResident / B : 8);
   want = std::max(1, std::min({want, sip::kMaxChunks, std::max(1, n_tiles / 2)}));
   const int chunk_tiles = (n_tiles + want - 1) / want;

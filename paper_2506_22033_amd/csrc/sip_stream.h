@@ -24,7 +24,7 @@ namespace sip {
 
 constexpr int kStreamThreads = 256;
 constexpr int kStreamWaves = kStreamThreads / kWave;
-constexpr int kStreamLoads = 4;             // 16-byte loads per thread per tile
+constexpr int kStreamLoads = 2;             // 16-byte loads per thread per tile
 constexpr int kSampleBins = 8192;           // 13-bit keys: sign, exponent, 4 mantissa bits
 constexpr int kSampleSize = 4096;           // elements of a row the threshold is estimated from
 constexpr int kQueueCap = 512;              // entries of one wave's LDS candidate queue

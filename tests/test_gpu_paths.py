@@ -1,0 +1,85 @@
+"""GPU parity on inputs built to drive every code path of the library at a vocabulary large
+enough for the single-pass kernels: the path taken is read back from the workspace
+(include/sip.h: 1 single pass, 15 second attempt, other = exact path and why) and the result is
+compared with the oracle under the rules of tests/sip_harness.py whichever path ran."""
+import numpy as np
+import pytest
+
+import workloads
+from tests import sip_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(w, steps=(0, 1), seed=2, k=None):
+    d = H.to_device(w)
+    st = H.ParityStats()
+    paths = []
+    for step in steps:
+        out = H.run_gpu(d, seed, step, k_logprobs=k)
+        paths.append(H.last_row_path.copy())
+        st.merge(H.compare(w, out, seed, step, k_logprobs=k))
+    return st, np.stack(paths)
+
+
+def test_every_kind_of_row_on_the_single_pass_path():
+    rng = np.random.default_rng(0)
+    V, B = 40000, 24
+    z = (rng.standard_normal((B, V)) * 2.5).astype(np.float32)
+    z[:, ::7] = -np.inf                                    # masked vocabulary entries
+    z[5, 123] = 30.0                                       # dominant token
+    z[6, :] = np.round(z[6, :], 1)                         # many exact ties
+    params = dict(temperature=rng.choice([0.0, 0.4, 0.8, 1.0, 1.4], B),
+                  top_k=rng.choice([0, 1, 2, 40, 1000, 3000], B),
+                  top_p=rng.choice([1.0, 0.95, 0.7, 0.2], B),
+                  min_p=rng.choice([0.0, 0.02, 0.1], B),
+                  repetition_penalty=rng.choice([1.0, 1.2], B),
+                  frequency_penalty=rng.choice([0.0, 0.3], B),
+                  presence_penalty=rng.choice([0.0, 0.4, -0.2], B))
+    hist = [rng.integers(0, V, int(rng.integers(0, 900))).tolist() for _ in range(B)]
+    hist[3] = np.argsort(-z[3])[:300].tolist() * 2          # the whole top of the row carries a penalty
+    st, paths = _check(H.custom("mix", z, params, hist, k_logprobs=20), steps=(0, 1, 2))
+    assert (paths == 1).mean() > 0.5, paths
+    zb = workloads.f32_to_bf16_bits(np.nan_to_num(z, neginf=-60.0))
+    st, paths = _check(H.custom("mix_bf16", zb, params, hist, k_logprobs=20), steps=(0, 1))
+    assert (paths == 1).mean() > 0.5, paths
+
+
+def test_second_attempt_with_a_lower_threshold():
+    # min-p with a high temperature keeps far more tokens than the first candidate list holds
+    rng = np.random.default_rng(1)
+    V, B = 120000, 32
+    z = (rng.standard_normal((B, V)) * 2.5).astype(np.float32)
+    params = dict(temperature=rng.uniform(1.4, 1.9, B), min_p=np.full(B, 0.05), top_p=rng.choice([1.0, 0.9], B))
+    st, paths = _check(H.custom("retry", z, params, k_logprobs=5), steps=(0, 1, 2))
+    assert (paths == 15).any(), paths                      # at least one row needed the retry ...
+    assert st.rows == 96                                   # ... and every row matched the oracle
+
+
+def test_rows_that_must_take_the_exact_path():
+    rng = np.random.default_rng(2)
+    V, B = 50000, 5
+    z = (rng.standard_normal((B, V)) * 2.0).astype(np.float32)
+    params = dict(temperature=[1.0, 0.9, 1.0, 0.7, 1.0], top_k=[0, 20000, 0, 0, 50],
+                  top_p=[1.0, 1.0, 0.999, 1.0, 1.0], min_p=[0.0, 0.0, 0.0, 0.0, 0.0])
+    hist = [[], [], [], rng.integers(0, V, 9000).tolist(), []]     # row 3: > 4096 distinct history tokens
+    params.update(repetition_penalty=[1.0, 1.0, 1.0, 1.3, 1.0])
+    params["min_p"][3] = 0.1
+    st, paths = _check(H.custom("exact", z, params, hist, k_logprobs=3), steps=(0, 1))
+    assert (paths[:, 0] == 2).all()                        # pure temperature sampling: nothing bounds the kept set
+    assert (paths[:, 1] == 2).all()                        # k far beyond the candidate list
+    assert (paths[:, 3] == 4).all()                        # too many distinct history tokens
+    assert (paths[:, 4] == 1).all()
+
+
+@pytest.mark.parametrize("B", [1, 3, 5, 9])
+def test_grid_sizes_that_are_not_a_multiple_of_eight(B):
+    w = workloads.make(2, B=B, V=70001, H=200)
+    st, paths = _check(w, steps=(0,))
+    assert st.rows == B
+
+
+def test_vocabulary_beyond_the_single_pass_kernels():
+    w = workloads.make(4, B=2, V=300000, H=64)
+    st, paths = _check(w, steps=(0,))
+    assert (paths == 14).all()
