@@ -59,9 +59,15 @@ __device__ __forceinline__ int candidate_target(const RowParams& r, const Args& 
   if (!(r.tau >= 0.0f)) return 0;
   if (r.greedy) return 512;
   const int k = (r.top_k >= 2 && r.top_k < a.V) ? r.top_k : 0;
-  if (k == 0 && !(r.top_p < 1.0f) && !(r.min_p > 0.0f)) return 0;
-  const int t = max(k + (k >> 1) + 512, 1536);
-  if (2 * t > a.nc_cap) return 0;
+  const bool p_on = r.top_p < 1.0f, minp_on = r.min_p > 0.0f;
+  if (k == 0 && !p_on && !minp_on) return 0;
+  // top-k needs its k largest in the list (plus head-room for the sampling noise of the
+  // threshold); a nucleus with nothing else to bound it tends to be longer than one cut by
+  // min-p, so it starts from a longer list
+  int t = max(k + (k >> 2) + 512, (k == 0 && !minp_on) ? 3072 : 1536);
+  // the 13-bit threshold rounds down (up to ~1.3x more entries) and up to kSideMax/2 history
+  // tokens typically join the list
+  if (t + (t >> 2) + 2048 > a.nc_cap) return 0;
   return t;
 }
 
