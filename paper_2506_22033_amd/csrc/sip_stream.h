@@ -65,6 +65,9 @@ __device__ __forceinline__ int candidate_target(const RowParams& r, const Args& 
   // threshold); a nucleus with nothing else to bound it tends to be longer than one cut by
   // min-p, so it starts from a longer list
   int t = max(k + (k >> 2) + 512, (k == 0 && !minp_on) ? 3072 : 1536);
+  // min-p keeps what lies within tau * ln(1/min_p) of the maximum: the list must reach that far
+  // down, and how many elements that is grows quickly with the temperature
+  if (minp_on && r.min_p < 1.0f) t = max(t, 1024 + (int)(341.0f * r.tau * -__logf(r.min_p)));
   // the 13-bit threshold rounds down (up to ~1.3x more entries) and up to kSideMax/2 history
   // tokens typically join the list
   if (t + (t >> 2) + 2048 > a.nc_cap) return 0;

@@ -46,14 +46,18 @@ def test_every_kind_of_row_on_the_single_pass_path():
 
 
 def test_second_attempt_with_a_lower_threshold():
-    # min-p with a high temperature keeps far more tokens than the first candidate list holds
     rng = np.random.default_rng(1)
-    V, B = 120000, 32
-    z = (rng.standard_normal((B, V)) * 2.5).astype(np.float32)
-    params = dict(temperature=rng.uniform(1.4, 1.9, B), min_p=np.full(B, 0.05), top_p=rng.choice([1.0, 0.9], B))
-    st, paths = _check(H.custom("retry", z, params, k_logprobs=5), steps=(0, 1, 2))
+    V, B = 33000, 12
+    z = (rng.standard_normal((B, V)) * 2.0).astype(np.float32)
+    # rows 0-5: a nucleus of several thousand tokens with nothing else to bound it;
+    # rows 6-11: min-p, but the whole top of the row carries a heavy penalty, so the maximum
+    # (and with it the min-p cut) ends up far below what the first candidate list covers
+    params = dict(temperature=[1.0] * 6 + [0.8] * 6, top_p=[0.9] * 6 + [1.0] * 6, min_p=[0.0] * 6 + [0.05] * 6,
+                  presence_penalty=[0.0] * 6 + [6.0] * 6)
+    hist = [[] for _ in range(6)] + [np.argsort(-z[b])[:400].tolist() for b in range(6, 12)]
+    st, paths = _check(H.custom("retry", z, params, hist, k_logprobs=5), steps=(0, 1, 2))
     assert (paths == 15).any(), paths                      # at least one row needed the retry ...
-    assert st.rows == 96                                   # ... and every row matched the oracle
+    assert st.rows == 36                                   # ... and every row matched the oracle
 
 
 def test_rows_that_must_take_the_exact_path():
