@@ -74,8 +74,8 @@ typedef struct {
  * code path finished each row: 1 = the single-pass path (logits read once), any other value
  * = finished after re-reading the row: 15 = the single-pass logic again on a longer candidate
  * list (one extra read of that row, normally from cache), anything else = the exact
- * multi-pass path, the value naming the reason (2 no filter bounds the kept set or k too
- * large, 3-13 the candidate list could not prove the answer, 17-29 nor could the longer one,
+ * multi-pass path, the value naming the reason (2 top_k too large for the candidate list,
+ * 3-13 the candidate list could not prove the answer, 17-29 nor could the longer one,
  * 14 vocabulary size outside the single-pass kernels).  Results mean the same either way.
  */
 size_t sip_workspace_bytes(int32_t B, int32_t V, sip_dtype dtype, int64_t hist_nnz, int32_t k_logprobs);

@@ -473,6 +473,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     // every element missing from L fails min-p  <=>  the completeness threshold itself fails it
     const bool minp_bounds = minp_on && !(__fsub_rn(s_c, m) >= t_minp);
     uint32_t key_cut = key_k;
+    bool whole_row = false;
     if (rp.top_p < 1.0f) {
       const double lim = ceil((double)rp.top_p * (double)S1);
       const unsigned long long limit = lim > 0.0 ? (unsigned long long)lim : 0ull;
@@ -517,10 +518,109 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       if (!inside && !minp_bounds) return 11;                                 // uniform: the cut may lie below L
       key_cut = max(key_k, fs.key_p);
     } else if (!k_act && !minp_bounds) {
-      return 12;                                                              // uniform: nothing bounds the kept set inside L
+      if (minp_on) return 12;                                                 // uniform: min-p reaches below L
+      whole_row = true;                                                       // no filter at all: every token is kept
     }
 
     SIP_MARK(8);
+    if (whole_row) {
+      // ---- (8') draw over the whole row (plain temperature sampling).  Maximum, total mass
+      // and best-n came from the list; the draw itself needs every element's mass in
+      // vocabulary order, so the row is read again here, twice: per-wave totals of contiguous
+      // ranges, then the one wave that holds the crossing walks its range with lane prefixes.
+      constexpr int EPL = (DT == SIP_F32) ? 4 : 8;
+      constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
+      const int range = ((((V + kFinalWaves - 1) / kFinalWaves) + kWave * EPL - 1) / (kWave * EPL)) * (kWave * EPL);
+      const int wbase = wave * range, wend = min(V, wbase + range);
+      auto masses = [&](int e0, unsigned long long (&E)[EPL], uint32_t (&keys)[EPL]) {
+        // e0 < V, multiple of EPL
+        const uint4 q = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);
+        float z[EPL];
+        if (DT == SIP_F32) {
+          z[0] = __uint_as_float(q.x); z[1] = __uint_as_float(q.y);
+          z[2] = __uint_as_float(q.z); z[3] = __uint_as_float(q.w);
+        } else {
+          const uint32_t w4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            z[2 * i] = __uint_as_float(w4[i] << 16);
+            z[2 * i + 1] = __uint_as_float(w4[i] & 0xFFFF0000u);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+          const int v = e0 + i;
+          E[i] = 0; keys[i] = 0;
+          if (v < V) {
+            float sv;
+            const uint32_t word = has_pen ? bm[v >> 5] : 0u;
+            if ((word >> (v & 31)) & 1u)                                       // carries a penalty: value from the list
+              sv = value_of(ck[top - (pre[v >> 5] + __popc(word & ((1u << (v & 31)) - 1u)))]);
+            else
+              sv = scaled_s(z[i]);
+            keys[i] = key_of(sv);
+            E[i] = mass(sv);
+          }
+        }
+      };
+      unsigned long long mine = 0;
+      for (int e0 = wbase + lane * EPL; e0 < wend; e0 += kWave * EPL) {
+        unsigned long long E[EPL];
+        uint32_t keys[EPL];
+        masses(e0, E, keys);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) mine += E[i];
+      }
+      mine = last_lane_u64(dpp_scan_add_u64(mine));
+      __syncthreads();
+      if (lane == 0) fs.r64[wave] = mine;
+      __syncthreads();
+      unsigned long long before = 0, S3 = 0;
+#pragma unroll
+      for (int ww = 0; ww < kFinalWaves; ++ww) {
+        if (ww < wave) before += fs.r64[ww];
+        S3 += fs.r64[ww];
+      }
+      const unsigned long long j24 = philox_word0(a.seed, rp.row_id, a.step) >> 8;
+      const unsigned long long target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);
+      if (before <= target && target < before + mine) {                       // at most one wave
+        unsigned long long running = before;
+        int found = -1;
+        uint32_t found_key = 0;
+        for (int base = wbase; base < wend && found < 0; base += kWave * EPL) {
+          const int e0 = base + lane * EPL;
+          unsigned long long E[EPL];
+          uint32_t keys[EPL];
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) { E[i] = 0; keys[i] = 0; }
+          if (e0 < wend) masses(e0, E, keys);
+          unsigned long long lane_tot = 0;
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) lane_tot += E[i];
+          const unsigned long long incl = dpp_scan_add_u64(lane_tot);
+          unsigned long long c = running + incl - lane_tot;
+          int hit = -1;
+          uint32_t hit_key = 0;
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) {
+            c += E[i];
+            if (hit < 0 && c > target) { hit = e0 + i; hit_key = keys[i]; }
+          }
+          const unsigned long long ball = __ballot(hit >= 0);
+          if (ball) {
+            const int src = __ffsll((long long)ball) - 1;
+            found = __builtin_amdgcn_readlane(hit, src);
+            found_key = (uint32_t)__builtin_amdgcn_readlane((int)hit_key, src);
+          }
+          running += last_lane_u64(incl);
+        }
+        if (lane == 0) { fs.token = found; fs.token_key = found_key; }
+      }
+      __syncthreads();
+      token = fs.token;
+      if (token == 0x7FFFFFFF || token < 0) return 13;                        // uniform
+      token_key = fs.token_key;
+    } else {
     // ---- (8) draw: kept mass per index bin, prefix, then resolve inside the crossing bin
     auto kept = [&](float s, uint32_t key) {
       return key >= key_cut && key > key_c && (!minp_on || __fsub_rn(s, m) >= t_minp);
@@ -592,6 +692,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     if ((uint32_t)tid < nm && fs.m_idx[tid] == (uint32_t)token) fs.token_key = fs.m_key[tid];
     __syncthreads();
     token_key = fs.token_key;
+    }
   }
 
   SIP_MARK(9);

@@ -53,14 +53,15 @@ __device__ __forceinline__ RowParams load_row_params(const Args& a, int b) {
 }
 
 // How many of the row's largest elements the candidate list should hold; 0 = this row
-// cannot be finished from a candidate list (nothing bounds its kept set, or k is too large)
-// and takes the exact multi-pass path instead.
+// cannot be finished from a candidate list (k is too large) and takes the exact multi-pass
+// path instead.
 __device__ __forceinline__ int candidate_target(const RowParams& r, const Args& a) {
   if (!(r.tau >= 0.0f)) return 0;
   if (r.greedy) return 512;
   const int k = (r.top_k >= 2 && r.top_k < a.V) ? r.top_k : 0;
   const bool p_on = r.top_p < 1.0f, minp_on = r.min_p > 0.0f;
-  if (k == 0 && !p_on && !minp_on) return 0;
+  if (k == 0 && !p_on && !minp_on) return 1024;       // plain temperature sampling: the list serves the maximum
+                                                      // and best-n, the draw re-reads the row
   // top-k needs its k largest in the list (plus head-room for the sampling noise of the
   // threshold); a nucleus with nothing else to bound it tends to be longer than one cut by
   // min-p, so it starts from a longer list

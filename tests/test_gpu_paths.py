@@ -70,7 +70,7 @@ def test_rows_that_must_take_the_exact_path():
     params.update(repetition_penalty=[1.0, 1.0, 1.0, 1.3, 1.0])
     params["min_p"][3] = 0.1
     st, paths = _check(H.custom("exact", z, params, hist, k_logprobs=3), steps=(0, 1))
-    assert (paths[:, 0] == 2).all()                        # pure temperature sampling: nothing bounds the kept set
+    assert (paths[:, 0] == 1).all()                        # plain temperature sampling: single pass + whole-row draw
     assert (paths[:, 1] == 2).all()                        # k far beyond the candidate list
     assert (paths[:, 3] == 4).all()                        # too many distinct history tokens
     assert (paths[:, 4] == 1).all()
@@ -87,3 +87,19 @@ def test_vocabulary_beyond_the_single_pass_kernels():
     w = workloads.make(4, B=2, V=300000, H=64)
     st, paths = _check(w, steps=(0,))
     assert (paths == 14).all()
+
+
+def test_plain_temperature_sampling_draws_over_the_whole_row():
+    rng = np.random.default_rng(7)
+    V, B = 50001, 10
+    z = (rng.standard_normal((B, V)) * 2.0).astype(np.float32)
+    z[2, 100:40000] = -np.inf
+    params = dict(temperature=[1.0, 0.6, 1.7, 0.9, 1.0, 1.3, 0.5, 1.0, 2.0, 0.8],
+                  repetition_penalty=[1.0, 1.3, 1.0, 1.0, 1.1, 1.0, 1.0, 1.2, 1.0, 1.0],
+                  frequency_penalty=[0.0, 0.2, 0.0, 0.0, 0.0, 0.4, 0.0, 0.0, 0.0, 0.0])
+    hist = [rng.integers(0, V, 700).tolist() for _ in range(B)]
+    st, paths = _check(H.custom("plain", z, params, hist, k_logprobs=8), steps=(0, 1, 2, 3))
+    assert (paths == 1).all(), paths
+    zb = workloads.f32_to_bf16_bits(np.nan_to_num(z, neginf=-80.0))
+    st, paths = _check(H.custom("plain_bf16", zb, params, hist, k_logprobs=8), steps=(0, 1))
+    assert (paths == 1).all(), paths
