@@ -526,15 +526,18 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     if (whole_row) {
       // ---- (8') draw over the whole row (plain temperature sampling).  Maximum, total mass
       // and best-n came from the list; the draw itself needs every element's mass in
-      // vocabulary order, so the row is read again here, twice: per-wave totals of contiguous
-      // ranges, then the one wave that holds the crossing walks its range with lane prefixes.
+      // vocabulary order, so the row is read once more here (it is still in the last-level
+      // cache), plus the one block in which the running mass crosses the target.
       constexpr int EPL = (DT == SIP_F32) ? 4 : 8;
       constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
-      const int range = ((((V + kFinalWaves - 1) / kFinalWaves) + kWave * EPL - 1) / (kWave * EPL)) * (kWave * EPL);
-      const int wbase = wave * range, wend = min(V, wbase + range);
-      auto masses = [&](int e0, unsigned long long (&E)[EPL], uint32_t (&keys)[EPL]) {
-        // e0 < V, multiple of EPL
-        const uint4 q = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);
+      const float zmax = value_of(bkey);
+      float c_row, c_lo;
+      scale_pair(rp, c_row, c_lo);
+      const int e_last = ((V - 1) / EPL) * EPL;
+      auto ldrow = [&](int e0) {                            // clamped: always a valid address
+        return *reinterpret_cast<const uint4*>(row + (size_t)min(e0, e_last) * ESZ);
+      };
+      auto masses = [&](const uint4& q, int e0, unsigned long long (&E)[EPL], uint32_t (&keys)[EPL]) {
         float z[EPL];
         if (DT == SIP_F32) {
           z[0] = __uint_as_float(q.x); z[1] = __uint_as_float(q.y);
@@ -552,48 +555,89 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
           const int v = e0 + i;
           E[i] = 0; keys[i] = 0;
           if (v < V) {
-            float sv;
             const uint32_t word = has_pen ? bm[v >> 5] : 0u;
-            if ((word >> (v & 31)) & 1u)                                       // carries a penalty: value from the list
-              sv = value_of(ck[top - (pre[v >> 5] + __popc(word & ((1u << (v & 31)) - 1u)))]);
-            else
-              sv = scaled_s(z[i]);
-            keys[i] = key_of(sv);
-            E[i] = mass(sv);
+            if ((word >> (v & 31)) & 1u) {                                     // carries a penalty: value from the list
+              const float sv = value_of(ck[top - (pre[v >> 5] + __popc(word & ((1u << (v & 31)) - 1u)))]);
+              keys[i] = key_of(sv);
+              E[i] = mass(sv);
+            } else {
+              // exp(z/tau - max) as 2^((z - zmax) * c): no division, hardware exp2; the two passes
+              // below use the same expression, which is all the draw needs
+              keys[i] = __float_as_uint(z[i]);                                 // raw bits, turned into a key on a hit
+              E[i] = fix_of(__builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(z[i], zmax), c_row)));
+            }
           }
         }
       };
-      unsigned long long mine = 0;
-      for (int e0 = wbase + lane * EPL; e0 < wend; e0 += kWave * EPL) {
-        unsigned long long E[EPL];
-        uint32_t keys[EPL];
-        masses(e0, E, keys);
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) mine += E[i];
-      }
-      mine = last_lane_u64(dpp_scan_add_u64(mine));
+      // first read: mass of every block of BLK consecutive elements (one block = UNR loads per
+      // lane of one wave) into hm[]; waves take contiguous runs of blocks
+      constexpr int UNR = 4;
+      constexpr int BLK = UNR * kWave * EPL;
+      const int nblk = (V + BLK - 1) / BLK;                 // <= kBins because V <= 262144
+      const int per_wave = (nblk + kFinalWaves - 1) / kFinalWaves;
+      __syncthreads();                                      // the suffix masses in hm[] are no longer needed
+      for (int i = tid; i < kBins; i += NT) hm[i] = 0;
       __syncthreads();
-      if (lane == 0) fs.r64[wave] = mine;
-      __syncthreads();
-      unsigned long long before = 0, S3 = 0;
+      for (int blk = wave * per_wave; blk < min(nblk, (wave + 1) * per_wave); ++blk) {
+        const int base = blk * BLK;
+        uint4 q[UNR];
 #pragma unroll
-      for (int ww = 0; ww < kFinalWaves; ++ww) {
-        if (ww < wave) before += fs.r64[ww];
-        S3 += fs.r64[ww];
-      }
-      const unsigned long long j24 = philox_word0(a.seed, rp.row_id, a.step) >> 8;
-      const unsigned long long target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);
-      if (before <= target && target < before + mine) {                       // at most one wave
-        unsigned long long running = before;
-        int found = -1;
-        uint32_t found_key = 0;
-        for (int base = wbase; base < wend && found < 0; base += kWave * EPL) {
-          const int e0 = base + lane * EPL;
+        for (int u = 0; u < UNR; ++u) q[u] = ldrow(base + (u * kWave + lane) * EPL);
+        unsigned long long mine = 0;
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
           unsigned long long E[EPL];
           uint32_t keys[EPL];
+          masses(q[u], base + (u * kWave + lane) * EPL, E, keys);        // zero past the end of the row
 #pragma unroll
-          for (int i = 0; i < EPL; ++i) { E[i] = 0; keys[i] = 0; }
-          if (e0 < wend) masses(e0, E, keys);
+          for (int i = 0; i < EPL; ++i) mine += E[i];
+        }
+        mine = dpp_scan_add_u64(mine);
+        if (lane == kWave - 1) hm[blk] = mine;
+      }
+      __syncthreads();
+      // prefix over the blocks, find the block that holds the crossing
+      unsigned long long target;
+      {
+        const int b0 = kBinsPerThread * tid;
+        unsigned long long w[kBinsPerThread], msum = 0;
+#pragma unroll
+        for (int j = 0; j < kBinsPerThread; ++j) { w[j] = hm[b0 + j]; msum += w[j]; }
+        const unsigned long long minc = dpp_scan_add_u64(msum);
+        if (lane == kWave - 1) fs.r64[wave] = minc;
+        __syncthreads();
+        unsigned long long ex = minc - msum, S3 = 0;
+#pragma unroll
+        for (int ww = 0; ww < kFinalWaves; ++ww) {
+          if (ww < wave) ex += fs.r64[ww];
+          S3 += fs.r64[ww];
+        }
+        const unsigned long long j24 = philox_word0(a.seed, rp.row_id, a.step) >> 8;
+        target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);           // floor(j * S3 / 2^24)
+#pragma unroll
+        for (int j = 0; j < kBinsPerThread; ++j) {
+          if (ex <= target && target < ex + w[j]) { fs.bin_d = b0 + j; fs.before_d = ex; }
+          ex += w[j];
+        }
+      }
+      __syncthreads();
+      const int blk_d = fs.bin_d;
+      if (blk_d < 0) return 13;                                               // uniform (no mass at all)
+      // second read, one block, one wave: lane prefixes in vocabulary order
+      if (wave == 0) {
+        const int base = blk_d * BLK;
+        unsigned long long running = fs.before_d;
+        int found = -1;
+        uint32_t found_key = 0;
+        uint4 q[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) q[u] = ldrow(base + (u * kWave + lane) * EPL);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+          const int e0 = base + (u * kWave + lane) * EPL;
+          unsigned long long E[EPL];
+          uint32_t keys[EPL];
+          masses(q[u], e0, E, keys);
           unsigned long long lane_tot = 0;
 #pragma unroll
           for (int i = 0; i < EPL; ++i) lane_tot += E[i];
@@ -604,17 +648,21 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
 #pragma unroll
           for (int i = 0; i < EPL; ++i) {
             c += E[i];
-            if (hit < 0 && c > target) { hit = e0 + i; hit_key = keys[i]; }
+            if (hit < 0 && c > target) { hit = e0 + i; hit_key = keys[i]; }   // key, or raw bits if unpenalised
           }
           const unsigned long long ball = __ballot(hit >= 0);
-          if (ball) {
+          if (ball && found < 0) {
             const int src = __ffsll((long long)ball) - 1;
             found = __builtin_amdgcn_readlane(hit, src);
             found_key = (uint32_t)__builtin_amdgcn_readlane((int)hit_key, src);
           }
           running += last_lane_u64(incl);
         }
-        if (lane == 0) { fs.token = found; fs.token_key = found_key; }
+        if (lane == 0) {
+          if (found >= 0 && !(has_pen && ((bm[found >> 5] >> (found & 31)) & 1u)))
+            found_key = key_of(scaled_s(__uint_as_float(found_key)));
+          fs.token = found; fs.token_key = found_key;
+        }
       }
       __syncthreads();
       token = fs.token;
