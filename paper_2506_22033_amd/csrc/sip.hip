@@ -25,7 +25,6 @@ struct Plan {
 
 constexpr int kFastMinV = 16384;
 constexpr int kFastMaxV = 262144;
-constexpr size_t kFinalLdsBudget = 144 * 1024;
 
 Plan make_plan(int32_t B, int32_t V, int dtype) {
   Plan p{};
@@ -43,11 +42,8 @@ Plan make_plan(int32_t B, int32_t V, int dtype) {
   p.S = (n_tiles + chunk_tiles - 1) / chunk_tiles;     // every chunk non-empty
   p.chunk_len = chunk_tiles * tile;
   p.cap_w = sip::kQueueCap;
-  const size_t fixed = sip::final_lds_fixed(V);
-  size_t nc = (kFinalLdsBudget - fixed) / 8;
-  nc = std::min<size_t>(nc, 12288) / 64 * 64;
-  p.nc_cap = (int)nc;
-  p.final_lds = fixed + nc * 8;
+  p.nc_cap = sip::kFinalThreads * sip::kCandLong;     // the finishing kernel holds the list in registers
+  p.final_lds = sip::final_lds_fixed(V);
   return p;
 }
 

@@ -4,17 +4,19 @@
 // logprob and the best-n list, without reading the logits again (except for the at most
 // |history| elements that carry a penalty).
 //
-// The candidate list L is held in LDS.  Every sum is an integer sum (masses in units of 2^-40
-// of the maximum's mass), so no result depends on the order in which threads add.
-// Selection works on 2048 linear value bins between the completeness threshold and the
-// maximum: one histogram pass locates the bin that holds the k-th largest value, the nucleus
-// cut or the n-th best, and the handful of entries in that bin are then resolved by
-// all-pairs comparison.  The draw does the same over 2048 bins of the vocabulary index.
+// The candidate list lives in registers: every thread keeps its share of the entries (key,
+// index, mass, value bin) from the moment they are read until the end.  Every sum is an
+// integer sum (masses in units of 2^-40 of the maximum's mass), so no result depends on the
+// order in which threads add.  Selection works on 2048 linear value bins between the
+// completeness threshold and the maximum: one histogram locates the bin that holds the k-th
+// largest value, the nucleus cut or the n-th best, and the handful of entries in that bin are
+// then resolved by all-pairs comparison.  The draw does the same over 2048 bins of the
+// vocabulary index.
 //
 // Whenever the list cannot prove the answer (a cut falls below the completeness threshold,
 // a bin or a segment overflows, too many distinct history tokens, ...) the function returns a
-// reason code > 1 before writing any output and the caller runs the exact multi-pass path on
-// the row; 1 means the row is finished.
+// reason code > 1 and the caller tries again with a longer list or runs the exact multi-pass
+// path on the row; 1 means the row is finished.
 #pragma once
 #include "sip_device.h"
 #include "sip_exact.h"
@@ -29,14 +31,17 @@ constexpr int kBinsPerThread = kBins / kFinalThreads;
 constexpr int kMembers = 256;        // entries of one bin that can be resolved by all-pairs comparison
 constexpr int kSideMax = 4096;       // distinct history tokens per row the fast path handles
 constexpr int kMaxChunks = 32;
-constexpr int kTopList = 320;        // entries at or above the bin of the n-th best
+constexpr int kTopList = 256;        // entries at or above the bin of the n-th best (half a workgroup ranks them)
 constexpr int kTokRegs = 8;          // history tokens a thread keeps in registers between phases
-constexpr int kCandRegs = 8;         // candidate entries a thread requests ahead of time
+constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
+constexpr int kNeedLong = 30;        // internal: the list needs the variant with more registers per thread
+constexpr int kCandShort = 8, kCandLong = 24;   // candidate entries per thread of the two variants
 constexpr int kSideRegs = kSideMax / kFinalThreads;   // raw logits of side entries, likewise
 
 struct FastShared {
   float Tc[kMaxChunks];
   int R[kMaxChunks];
+  float r0[kMaxChunks];                 // fractional part of the chunk's reference exponent
   unsigned long long bulk[kMaxChunks];
   uint32_t segoff[kMaxChunks * kStreamWaves + 1];
   unsigned long long r64[kFinalWaves];
@@ -44,7 +49,7 @@ struct FastShared {
   uint32_t r32[kFinalWaves];
   uint32_t rkey[kFinalWaves];
   uint32_t ridx[kFinalWaves];
-  uint32_t fail_seg, ndist, nlist, anyc, dropped;
+  uint32_t fail_seg, anyc, dropped;
   float m_out, zmax_out, trow_out;      // for a second attempt: max of s, max of z', threshold used
   uint32_t rq_n;                         // candidates found by the second pass
   int bin_k, bin_n, bin_p, bin_low, bin_d;
@@ -64,7 +69,7 @@ struct FastShared {
 // Bytes of dynamic LDS the finishing kernel needs for vocabulary V, before the candidates.
 __host__ __device__ inline size_t final_lds_fixed(int V) {
   const size_t W = ((size_t)V + 31) / 32;
-  return ((W * 4 + W * 2 + 15) / 16) * 16 + (size_t)kBins * 12;
+  return ((W * 4 + W * 2 + 15) / 16) * 16 + (size_t)kBins * 20 + (size_t)kSideMax * 8;
 }
 
 template <int DT>
@@ -77,15 +82,30 @@ __device__ __forceinline__ float load_elem(const char* row, int v) {
 // behind the per-row path codes in the workspace.
 #ifdef SIP_TIMING
 #define SIP_MARK(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) \
-    reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1))[i] = wall_clock64(); } while (0)
+    { reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1))[i] = wall_clock64(); \
+      reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1))[32 + i] = clock64(); } } while (0)
+#define SIP_MARK_T(i, t) do { if (blockIdx.x == 0 && threadIdx.x == (t)) \
+    { reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1))[i] = wall_clock64(); } } while (0)
 #else
 #define SIP_MARK(i) do { } while (0)
+#define SIP_MARK_T(i, t) do { } while (0)
 #endif
 
-template <int DT>
+// One attempt at finishing row b from its candidate list.  CR = candidate entries a thread can
+// hold in registers: the list, once read, never goes to memory again -- each thread keeps its
+// share (CR candidates and kSideRegs history tokens) with key, index, mass and value bin in
+// registers, and the phases below talk to each other only through the LDS histograms and a few
+// small gathered lists.  Returns 1 (finished), kNeedLong (the list does not fit CR entries per
+// thread) or a reason code > 1; outputs written before a failure are overwritten by the path
+// that takes the row over.
+template <int DT, int CR>
 __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
                                         FastShared& fs, const int S, const int chunk_len, const int cap_w) {
   constexpr int NT = kFinalThreads;
+  constexpr int SR = kSideRegs;
+  constexpr int NE = CR + SR;                               // register entries per thread
+  constexpr bool STORE = CR <= 8;                           // keep mass and bin in registers too
+  constexpr int NS = STORE ? NE : 1;
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
   const int V = a.V;
   const int W = (V + 31) >> 5;
@@ -93,18 +113,16 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   uint32_t* bm = reinterpret_cast<uint32_t*>(dyn);
   unsigned short* pre = reinterpret_cast<unsigned short*>(dyn + (size_t)W * 4);
   unsigned char* p2 = dyn + (((size_t)W * 6 + 15) / 16) * 16;
-  unsigned long long* hm = reinterpret_cast<unsigned long long*>(p2);
-  uint32_t* hc = reinterpret_cast<uint32_t*>(p2 + (size_t)kBins * 8);
-  uint32_t* ck = reinterpret_cast<uint32_t*>(p2 + (size_t)kBins * 12);
-  uint32_t* ci = ck + a.nc_cap;
-  uint32_t* cnt = reinterpret_cast<uint32_t*>(hm);         // kSideMax counters, before the bins are needed
-  const uint32_t nc_cap = (uint32_t)a.nc_cap;
-  const uint32_t top = nc_cap - 1;                         // side entries grow downwards from here
+  unsigned long long* hm = reinterpret_cast<unsigned long long*>(p2);      // value bins: mass
+  unsigned long long* hd = hm + kBins;                                      // index bins: kept mass
+  uint32_t* hc = reinterpret_cast<uint32_t*>(hd + kBins);                   // value bins: count
+  uint32_t* cnt = hc + kBins;                                               // multiplicity per history slot
+  uint32_t* stok = cnt + kSideMax;                                          // token per history slot
   const char* row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * (DT == SIP_F32 ? 4 : 2);
   auto scaled_s = [&](float z) { return rp.greedy ? z : __fdiv_rn(z, rp.tau); };
 
   SIP_MARK(0);
-  // ---- (0) chunk summaries, history extent; clear the bitmap and the counters meanwhile
+  // ---- (0) chunk summaries, history extent; clear the LDS tables meanwhile
   long long lo = 0, hi = 0;
   if (a.indptr && a.tokens && a.nnz > 0) {
     lo = a.indptr[b]; hi = a.indptr[b + 1];
@@ -114,14 +132,15 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   const bool has_pen = (hi > lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
   const int nseg = S * kStreamWaves;
   if (tid == 0) {
-    fs.fail_seg = 0; fs.ndist = 0; fs.nlist = 0; fs.anyc = 0; fs.dropped = 0;
+    fs.fail_seg = 0; fs.anyc = 0; fs.dropped = 0;
     fs.bin_k = -1; fs.bin_n = -1; fs.bin_p = 1 << 30; fs.bin_low = 1 << 30; fs.bin_d = -1;
-    fs.key_p = 0xFFFFFFFFu; fs.s1_part = 0; fs.n_memb = 0; fs.n_memb2 = 0; fs.n_memb3 = 0; fs.n_top = 0;
-    fs.token = 0x7FFFFFFF;
+    fs.key_p = 0xFFFFFFFFu; fs.n_memb = 0; fs.n_memb2 = 0; fs.n_memb3 = 0; fs.n_top = 0;
+    fs.token = 0x7FFFFFFF; fs.key_k = 0; fs.s1_part = 0;
   }
   if (tid < S) {
     const ChunkOut co = a.chunks[(size_t)b * a.S + tid];
     fs.Tc[tid] = co.Tc; fs.R[tid] = co.R; fs.bulk[tid] = co.bulk;
+    fs.r0[tid] = make_bulk_ref(co.Tc, rp).r0;
 #pragma unroll
     for (int w = 0; w < kStreamWaves; ++w) fs.segoff[tid * kStreamWaves + w] = co.cnt[w];
   }
@@ -132,10 +151,20 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     const long long i = lo + tid + (long long)j * NT;
     tok[j] = (has_pen && i < hi) ? a.tokens[i] : -1;
   }
+  {
+    uint4* z4 = reinterpret_cast<uint4*>(p2);               // hm, hd, hc: kBins * 20 bytes
+    for (int i = tid; i < kBins * 20 / 16; i += NT) z4[i] = make_uint4(0, 0, 0, 0);
+  }
   if (has_pen) {
     for (int w = tid; w < W; w += NT) bm[w] = 0;
     for (int i = tid; i < kSideMax; i += NT) cnt[i] = 0;
   }
+  // row constants that take long arithmetic, worked out while the loads above travel
+  const bool minp_on = !rp.greedy && rp.min_p > 0.0f;
+  const float t_minp = minp_on ? (float)log((double)rp.min_p) : 0.0f;
+  const unsigned long long j24 = rp.greedy ? 0ull : (unsigned long long)(philox_word0(a.seed, rp.row_id, a.step) >> 8);
+  float c_row, c_lo;
+  scale_pair(rp, c_row, c_lo);
   __syncthreads();
 
   SIP_MARK(1);
@@ -167,26 +196,19 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   __syncthreads();
   if (fs.fail_seg || !(T_row == T_row)) return 3;                             // uniform
   const uint32_t total_seg = fs.segoff[nseg];
-  if (total_seg > nc_cap) return 5;                                           // uniform
+  if (total_seg > (uint32_t)a.nc_cap) return 5;                               // uniform
+  if (total_seg > (uint32_t)(NT * CR)) return kNeedLong;                      // uniform
 
   SIP_MARK(2);
   // ---- (2) The two dependent global reads of this kernel -- the candidate segments and the raw
   // logits of the history tokens -- are issued as early as their addresses are known and
   // consumed as late as possible, with the LDS work in between.
-  // (2a) request this thread's share of the candidates (kCandRegs rounds live in registers)
+  // (2a) thread t takes list positions per*t .. per*t + per-1: one segment search, then it walks along
   const uint2* segs = a.cand + (size_t)b * (size_t)(a.S * kStreamWaves) * (size_t)a.cap_w;
-  auto cand_addr = [&](uint32_t i) -> const uint2* {       // i < total_seg
-    int s0 = 0, s1 = nseg;                                  // segoff[s0] <= i < segoff[s1]
-    while (s1 - s0 > 1) {
-      const int mid = (s0 + s1) >> 1;
-      if (fs.segoff[mid] <= i) s0 = mid; else s1 = mid;
-    }
-    return segs + (size_t)s0 * cap_w + (i - fs.segoff[s0]);
-  };
-  // thread t takes list positions 8t .. 8t+7: one segment search, then it walks along
-  uint2 creg[kCandRegs];
+  const int per = (int)((total_seg + NT - 1) / NT);                           // uniform, <= CR
+  uint2 creg[CR];
   {
-    const uint32_t i0 = (uint32_t)(tid * kCandRegs);
+    const uint32_t i0 = (uint32_t)(tid * per);
     int sg = 0;
     if (i0 < total_seg) {
       int s1 = nseg;
@@ -197,12 +219,14 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     }
     uint32_t lo_off = fs.segoff[sg], hi_off = fs.segoff[sg + 1];
 #pragma unroll
-    for (int r = 0; r < kCandRegs; ++r) {
-      const uint32_t i = i0 + (uint32_t)r;
-      creg[r] = make_uint2(0u, 0xFFFFFFFFu);
-      if (i < total_seg) {
-        while (i >= hi_off) { ++sg; lo_off = hi_off; hi_off = fs.segoff[sg + 1]; }   // skips empty segments too
-        creg[r] = segs[(size_t)sg * cap_w + (i - lo_off)];
+    for (int r = 0; r < CR; ++r) {
+      creg[r] = make_uint2(0u, kNoIdx);
+      if (r < per) {
+        const uint32_t i = i0 + (uint32_t)r;
+        if (i < total_seg) {
+          while (i >= hi_off) { ++sg; lo_off = hi_off; hi_off = fs.segoff[sg + 1]; }   // skips empty segments too
+          creg[r] = segs[(size_t)sg * cap_w + (i - lo_off)];
+        }
       }
     }
   }
@@ -210,8 +234,8 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   // run of bitmap words
   uint32_t ndist = 0;
   if (has_pen) {
-    const int per = (W + NT - 1) / NT;
-    const int w0 = tid * per, w1 = min(W, w0 + per);
+    const int perw = (W + NT - 1) / NT;
+    const int w0 = tid * perw, w1 = min(W, w0 + perw);
     uint32_t local = 0;
     for (int w = w0; w < w1; ++w) local += (uint32_t)__popc(bm[w]);
     const uint32_t incl = dpp_scan_add_u32(local);
@@ -224,12 +248,12 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       if (ww < wave) slot += t;
       ndist += t;
     }
-    if (ndist > (uint32_t)kSideMax || ndist > nc_cap) return 4;               // uniform
+    if (ndist > (uint32_t)kSideMax) return 4;                                 // uniform
     for (int w = w0; w < w1; ++w) {
       uint32_t bits = bm[w];
       if (bits) pre[w] = (unsigned short)slot;
       while (bits) {                                                          // token of each slot
-        ci[top - slot] = (uint32_t)((w << 5) + __ffs((int)bits) - 1);
+        stok[slot] = (uint32_t)((w << 5) + __ffs((int)bits) - 1);
         bits &= bits - 1;
         ++slot;
       }
@@ -237,35 +261,18 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     __syncthreads();
   }
   SIP_MARK(11);
-  // (2c) request the raw logits of this thread's side entries
-  float raw[kSideRegs];
+  // Register entries: 0..CR-1 candidates, CR..NE-1 history tokens.  idx == kNoIdx: no entry.
+  uint32_t idx[NE], key[NE];                 // key[] holds the bits of z' until (5) turns them into keys
+  // (2c) request the raw logits of this thread's history tokens
+  float raw[SR];
 #pragma unroll
-  for (int r = 0; r < kSideRegs; ++r) {
+  for (int r = 0; r < SR; ++r) {
     const uint32_t i = (uint32_t)(r * NT + tid);
-    raw[r] = i < ndist ? load_elem<DT>(row, (int)ci[top - i]) : 0.0f;
-  }
-  // (2d) candidates -> LDS; entries that carry a penalty are dropped here and come back with
-  // their penalised value in (4)
-  auto append = [&](const uint2& e, bool valid) {
-    bool keep = valid && e.y < (uint32_t)V;
-    if (keep && has_pen) keep = ((bm[e.y >> 5] >> (e.y & 31)) & 1u) == 0;
-    const unsigned long long mask = __ballot(keep);
-    uint32_t wbase = 0;
-    if (lane == 0 && mask) wbase = atomicAdd(&fs.nlist, (uint32_t)__popcll(mask));
-    wbase = (uint32_t)__builtin_amdgcn_readfirstlane((int)wbase);
-    if (keep) {
-      const uint32_t pos = wbase + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                       __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-      ck[pos] = e.x; ci[pos] = e.y;                // pos < total_seg <= nc_cap
+    idx[CR + r] = kNoIdx; raw[r] = 0.0f;
+    if ((uint32_t)(r * NT) < ndist && i < ndist) {
+      idx[CR + r] = stok[i];
+      raw[r] = load_elem<DT>(row, (int)idx[CR + r]);
     }
-  };
-#pragma unroll
-  for (int r = 0; r < kCandRegs; ++r) append(creg[r], (uint32_t)(tid * kCandRegs + r) < total_seg);
-  for (uint32_t base = (uint32_t)(kCandRegs * NT); base < total_seg; base += NT) {
-    const uint32_t i = base + tid;
-    uint2 e = make_uint2(0u, 0xFFFFFFFFu);
-    if (i < total_seg) e = *cand_addr(i);
-    append(e, i < total_seg);
   }
   // ---- (3) multiplicities of the history tokens
   if (has_pen && rp.phi != 0.0f) {
@@ -279,56 +286,60 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     for (int j = 0; j < kTokRegs; ++j) count(tok[j]);
     for (long long i = lo + tid + (long long)kTokRegs * NT; i < hi; i += NT) count(a.tokens[i]);
   }
-  __syncthreads();
-  const uint32_t n_unpen = fs.nlist;
-  const uint32_t nlist = n_unpen + ndist;
-  if (nlist > nc_cap || nlist == 0) return 5;                                 // uniform
-  // list position i -> LDS index: unpenalised candidates first, side entries from the top
-  auto at = [&](uint32_t i) { return i < n_unpen ? i : top - (i - n_unpen); };
-
-  SIP_MARK(4);
-  // ---- (4) penalised values of the side entries; maximum of the list (lowest index on ties)
-  long long corr = 0;               // mass the streaming pass counted for elements that carry a penalty
-  uint32_t bkey = 0, bidx = 0xFFFFFFFFu;
+  // (2d) candidates that carry a penalty are dropped: they come back with their penalised value
+  // as history entries
   bool anyc = false;
 #pragma unroll
-  for (int r = 0; r < kSideRegs; ++r) {
-    const uint32_t i = (uint32_t)(r * NT + tid);
-    if (i < ndist) {
-      const uint32_t v = ci[top - i];
+  for (int r = 0; r < CR; ++r) {
+    const uint2 e = creg[r];
+    bool keep = r < per && e.y < (uint32_t)V;
+    if (keep && has_pen) keep = ((bm[e.y >> 5] >> (e.y & 31)) & 1u) == 0;
+    idx[r] = keep ? e.y : kNoIdx;
+    key[r] = e.x;
+    anyc |= keep && __uint_as_float(e.x) >= T_row;
+  }
+  __syncthreads();
+
+  SIP_MARK(4);
+  // ---- (4) penalised values of the history entries; maximum of the list (lowest index on ties)
+  long long corr = 0;               // mass the streaming pass counted for elements that carry a penalty
+  uint32_t bkey = 0, bidx = kNoIdx;
+#pragma unroll
+  for (int r = 0; r < SR; ++r) {
+    if ((uint32_t)(r * NT) < ndist && idx[CR + r] != kNoIdx) {
+      const uint32_t v = idx[CR + r];
       const float rv = raw[r];
-      const float zp = penalise(rv, cnt[i], rp.theta, rp.phi, rp.psi);
-      ck[top - i] = __float_as_uint(zp);
+      const float zp = penalise(rv, cnt[r * NT + tid], rp.theta, rp.phi, rp.psi);
+      key[CR + r] = __float_as_uint(zp);
       // the streaming pass saw the raw value: if it was below its chunk's threshold it went into
       // the bulk sum and has to come out again
       const int c = (int)v / chunk_len;
       if (!(rv >= fs.Tc[c])) {
-        const BulkRef ref = make_bulk_ref(fs.Tc[c], rp);
+        BulkRef ref;
+        ref.Tc = fs.Tc[c]; ref.c = c_row; ref.r0 = fs.r0[c]; ref.R = fs.R[c];
         const unsigned long long u = bulk_units(bulk_term(rv, ref));
         const int sh = R_max - ref.R;
         corr += (long long)(sh < 64 ? (u >> sh) : 0ull);
       }
-      const uint32_t kz = key_of(zp);
-      if (kz > bkey || (kz == bkey && v < bidx)) { bkey = kz; bidx = v; }
     }
   }
-  for (uint32_t i = tid; i < n_unpen; i += NT) {
-    const float z = __uint_as_float(ck[i]);
-    const uint32_t v = ci[i];
-    const uint32_t kz = key_of(z);
-    if (kz > bkey || (kz == bkey && v < bidx)) { bkey = kz; bidx = v; }
-    anyc |= z >= T_row;
+#pragma unroll
+  for (int r = 0; r < NE; ++r) {
+    if (idx[r] != kNoIdx) {
+      const uint32_t kz = key_of(__uint_as_float(key[r]));
+      if (kz > bkey || (kz == bkey && idx[r] < bidx)) { bkey = kz; bidx = idx[r]; }
+    }
   }
   {
     const uint32_t wk = last_lane_u32(dpp_scan_max_u32(bkey));
-    const uint32_t wi = last_lane_u32(dpp_scan_min_u32(bkey == wk ? bidx : 0xFFFFFFFFu));
+    const uint32_t wi = last_lane_u32(dpp_scan_min_u32(bkey == wk ? bidx : kNoIdx));
     const unsigned long long uc = dpp_scan_add_u64((unsigned long long)corr);
     if (lane == kWave - 1) { fs.rkey[wave] = wk; fs.ridx[wave] = wi; fs.rcorr[wave] = (long long)uc; }
     if (__any(anyc) && lane == 0) fs.anyc = 1;
   }
   __syncthreads();
   long long corr_total = 0;
-  bkey = 0; bidx = 0xFFFFFFFFu;
+  bkey = 0; bidx = kNoIdx;
 #pragma unroll
   for (int w = 0; w < kFinalWaves; ++w) {
     const uint32_t ok = fs.rkey[w], oi = fs.ridx[w];
@@ -336,37 +347,56 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     corr_total += fs.rcorr[w];
   }
   // an unpenalised candidate at or above T_row proves that nothing outside the list is larger
-  if (!fs.anyc || bidx == 0xFFFFFFFFu) return 6;                              // uniform
+  if (!fs.anyc || bidx == kNoIdx) return 6;                                   // uniform
   const int best_i = (int)bidx;
   const float m = scaled_s(value_of(bkey));
-  const float s_c = scaled_s(T_row);            // entries with s > s_c: every such element of the row is in L
+  const float s_c = scaled_s(T_row);            // entries with s > s_c: every such element of the row is in the list
   const uint32_t key_c = key_of(s_c);
   if (tid == 0) { fs.m_out = m; fs.zmax_out = value_of(bkey); fs.trow_out = T_row; }
   const float span = __fsub_rn(m, s_c);
   if (!(span >= 0.0f) || !(span < 3.0e38f)) return 7;                         // uniform
   const float binscale = span > 0.0f ? (float)(kBins - 2) / span : 0.0f;
-  auto bin_of = [&](float s, uint32_t key) -> int {
-    if (key <= key_c) return 0;
+  auto bin_of = [&](float s, uint32_t k) -> int {
+    if (k <= key_c) return 0;
     const int q = (int)(__fsub_rn(s, s_c) * binscale);
     return 1 + min(kBins - 2, max(q, 0));
   };
   auto mass = [&](float s) { return fix_of(expf(__fsub_rn(s, m))); };
+  // which register rounds hold anything at all (workgroup-uniform)
+  auto live = [&](int r) { return r < CR ? r < per : (uint32_t)((r - CR) * NT) < ndist; };
 
   SIP_MARK(5);
-  // ---- (5) keys, value histogram (count and mass per bin), suffix sums
-  for (int i = tid; i < kBins; i += NT) { hc[i] = 0; hm[i] = 0; }            // counters are dead since (4)
-  __syncthreads();
-  SIP_MARK(12);
-  for (uint32_t i = tid; i < nlist; i += NT) {
-    const uint32_t p = at(i);
-    const float s = scaled_s(__uint_as_float(ck[p]));
-    const uint32_t key = key_of(s);
-    ck[p] = key;
-    const int bin = bin_of(s, key);
-    atomicAdd(&hc[bin], 1u);
-    const unsigned long long E = mass(s);
-    if (E) atomicAdd(&hm[bin], E);
+  // ---- (5) keys, masses, value histogram (count and mass per bin)
+  unsigned long long Ereg[NS];
+  short breg[NS];
+#pragma unroll
+  for (int r = 0; r < NE; ++r) {
+    if (live(r)) {
+      unsigned long long E = 0;
+      int bin = -1;
+      uint32_t k = 0;
+      if (idx[r] != kNoIdx) {
+        const float s = scaled_s(__uint_as_float(key[r]));
+        k = key_of(s);
+        bin = bin_of(s, k);
+        E = mass(s);
+        atomicAdd(&hc[bin], 1u);
+        if (E) atomicAdd(&hm[bin], E);
+      }
+      key[r] = k;
+      if (r >= CR) cnt[(r - CR) * NT + tid] = k;      // slot -> key, for the whole-row draw (this thread's own slot)
+      if constexpr (STORE) { Ereg[r] = E; breg[r] = (short)bin; }
+    } else {
+      key[r] = 0;
+      if constexpr (STORE) { Ereg[r] = 0; breg[r] = -1; }
+    }
   }
+  auto E_of = [&](int r) -> unsigned long long {
+    if constexpr (STORE) return Ereg[r]; else return mass(value_of(key[r]));
+  };
+  auto b_of = [&](int r) -> int {
+    if constexpr (STORE) return (int)breg[r]; else return bin_of(value_of(key[r]), key[r]);
+  };
   __syncthreads();
   SIP_MARK(13);
   const bool k_act = !rp.greedy && rp.top_k >= 2 && rp.top_k < V;
@@ -410,7 +440,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     if (lane == kWave - 1 && wlow < (1u << 30)) atomicMin(&fs.bin_low, (int)wlow);
   }
   __syncthreads();
-  if ((k_act && fs.bin_k < 0) || (n_top > 0 && fs.bin_n < 0)) return 8;      // uniform: k-th / n-th not provably in L
+  if ((k_act && fs.bin_k < 0) || (n_top > 0 && fs.bin_n < 0)) return 8;      // uniform: k-th / n-th not provably in the list
   const int bin_k = k_act ? fs.bin_k : 0, bin_n = fs.bin_n;
 
   // bulk mass -> units of 2^-40 relative to the maximum
@@ -420,46 +450,81 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     bulk += sh < 64 ? (fs.bulk[c] >> sh) : 0ull;
   }
   bulk = (long long)bulk > corr_total ? bulk - (unsigned long long)corr_total : 0ull;
+  // 2^x with x split into integer and fraction: the fraction goes through the hardware exp2 (1 ulp,
+  // far inside the accuracy of the fp32 bulk sums), the integer part is an exponent shift
   const double ln2 = 0.6931471805599453094, log2e = 1.4426950408889634074;
-  const double bulk_rel = (double)bulk * exp2((double)R_max + 10.0 - (double)m * log2e);
+  const double x = fmin(fmax((double)R_max + 10.0 - (double)m * log2e, -2000.0), 2000.0);
+  const double xi = floor(x);
+  const double bulk_rel = ldexp((double)bulk * (double)__builtin_amdgcn_exp2f((float)(x - xi)), (int)xi);
   const unsigned long long S0 = S_cand + (bulk_rel < 9.0e18 ? (unsigned long long)bulk_rel : 0ull);
-  const double lnZ = log((double)S0) - (double)kFixShift * ln2;
+  // ln S0 from exponent and mantissa: S0 = f * 2^e, f in [0.5, 1)
+  int e2;
+  const float f2 = (float)frexp((double)S0, &e2);
+  const double lnZ = ((double)__builtin_amdgcn_logf(f2) + (double)(e2 - kFixShift)) * ln2;
 
   SIP_MARK(6);
   // ---- (6) gather the bin of the k-th largest and everything at or above the bin of the n-th best
   if (k_act || n_top > 0) {
-    for (uint32_t i = tid; i < nlist; i += NT) {
-      const uint32_t p = at(i);
-      const uint32_t key = ck[p];
-      const float s = value_of(key);
-      const int bin = bin_of(s, key);
-      if (k_act && bin == bin_k) {
-        const uint32_t q = atomicAdd(&fs.n_memb, 1u);
-        if (q < (uint32_t)kMembers) { fs.m_key[q] = key; fs.m_E[q] = mass(s); }
-      }
-      if (n_top > 0 && bin >= bin_n) {
-        const uint32_t q = atomicAdd(&fs.n_top, 1u);
-        if (q < (uint32_t)kTopList) { fs.t_key[q] = key; fs.t_idx[q] = ci[p]; }
+#pragma unroll
+    for (int r = 0; r < NE; ++r) {
+      if (live(r) && idx[r] != kNoIdx) {
+        const int bin = b_of(r);
+        if (k_act && bin == bin_k) {
+          const uint32_t q = atomicAdd(&fs.n_memb, 1u);
+          if (q < (uint32_t)kMembers) { fs.m_key[q] = key[r]; fs.m_E[q] = E_of(r); }
+        }
+        if (n_top > 0 && bin >= bin_n) {
+          const uint32_t q = atomicAdd(&fs.n_top, 1u);
+          if (q < (uint32_t)kTopList) { fs.t_key[q] = key[r]; fs.t_idx[q] = idx[r]; }
+        }
       }
     }
     __syncthreads();
     if (fs.n_memb > (uint32_t)kMembers || fs.n_top > (uint32_t)kTopList) return 9;   // uniform
   }
+  SIP_MARK(24);
+  // best-n (upper half of the workgroup) and the k-th largest (lower half) side by side
+  SIP_MARK_T(29, 256);
+  if (a.k_lp >= 0 && n_top > 0 && tid >= NT / 2) {
+    // The gathered list holds every element at or above the bin of the n-th best, so an
+    // entry's rank in this list is its rank in the row.
+    const int cols = 1 + a.k_lp;
+    const uint32_t nt = fs.n_top;
+    const uint32_t t = (uint32_t)(tid - NT / 2);
+    if (t < nt) {
+      const uint32_t kt = fs.t_key[t], v = fs.t_idx[t];
+      uint32_t rank = 0;
+#pragma unroll 8
+      for (uint32_t q = 0; q < nt; ++q) {
+        const uint32_t kq = fs.t_key[q];
+        rank += (kq > kt || (kq == kt && fs.t_idx[q] < v)) ? 1u : 0u;
+      }
+      if (rank < n_top) {
+        a.out_lp_ids[(size_t)b * cols + 1 + rank] = (int)v;
+        a.out_lp[(size_t)b * cols + 1 + rank] = (float)((double)value_of(kt) - (double)m - lnZ);
+      }
+    }
+  }
+  SIP_MARK_T(30, 256);
   uint32_t key_k = 0;
   unsigned long long S1 = S0;
   if (k_act) {
     const uint32_t nm = fs.n_memb, k_rem = (uint32_t)rp.top_k - fs.above_k;
     if ((uint32_t)tid < nm) {
-      const uint32_t key = fs.m_key[tid];
+      const uint32_t kt = fs.m_key[tid];
       uint32_t gt = 0, ge = 0;
+      unsigned long long sum_ge = 0;
 #pragma unroll 8
-      for (uint32_t q = 0; q < nm; ++q) { const uint32_t kq = fs.m_key[q]; gt += kq > key; ge += kq >= key; }
-      if (gt < k_rem && k_rem <= ge) fs.key_k = key;
+      for (uint32_t q = 0; q < nm; ++q) {
+        const uint32_t kq = fs.m_key[q];
+        gt += kq > kt; ge += kq >= kt;
+        sum_ge += kq >= kt ? fs.m_E[q] : 0ull;
+      }
+      // the k-th largest of the row: ties write the same two values
+      if (gt < k_rem && k_rem <= ge) { fs.key_k = kt; fs.s1_part = sum_ge; }
     }
     __syncthreads();
     key_k = fs.key_k;
-    if ((uint32_t)tid < nm && fs.m_key[tid] >= key_k) atomicAdd(&fs.s1_part, fs.m_E[tid]);
-    __syncthreads();
     S1 = hm[bin_k] + fs.s1_part;
   }
 
@@ -468,9 +533,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   if (!rp.greedy) {
     SIP_MARK(7);
     // ---- (7) top-p
-    const bool minp_on = rp.min_p > 0.0f;
-    const float t_minp = minp_on ? (float)log((double)rp.min_p) : 0.0f;
-    // every element missing from L fails min-p  <=>  the completeness threshold itself fails it
+    // every element missing from the list fails min-p  <=>  the completeness threshold itself fails it
     const bool minp_bounds = minp_on && !(__fsub_rn(s_c, m) >= t_minp);
     uint32_t key_cut = key_k;
     bool whole_row = false;
@@ -491,34 +554,33 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       }
       __syncthreads();
       const int bin_p = fs.bin_p;
-  SIP_MARK(14);
+      SIP_MARK(14);
       if (bin_p >= kBins) return 10;                                          // uniform (p <= 0)
-      for (uint32_t i = tid; i < nlist; i += NT) {
-        const uint32_t key = ck[at(i)];
-        const float s = value_of(key);
-        if (key >= key_k && bin_of(s, key) == bin_p) {
+#pragma unroll
+      for (int r = 0; r < NE; ++r) {
+        if (live(r) && idx[r] != kNoIdx && key[r] >= key_k && b_of(r) == bin_p) {
           const uint32_t q = atomicAdd(&fs.n_memb2, 1u);
-          if (q < (uint32_t)kMembers) { fs.m_key[q] = key; fs.m_E[q] = mass(s); }
+          if (q < (uint32_t)kMembers) { fs.m_key[q] = key[r]; fs.m_E[q] = E_of(r); }
         }
       }
       __syncthreads();
       const uint32_t nm = fs.n_memb2;
-  SIP_MARK(15);
+      SIP_MARK(15);
       if (nm > (uint32_t)kMembers) return 9;                                  // uniform
       if ((uint32_t)tid < nm) {
-        const uint32_t key = fs.m_key[tid];
+        const uint32_t kt = fs.m_key[tid];
         unsigned long long G = hm[bin_p];
 #pragma unroll 8
         for (uint32_t q = 0; q < nm; ++q)
-          if (fs.m_key[q] > key) G += fs.m_E[q];
-        if (G < limit) atomicMin(&fs.key_p, key); else fs.dropped = 1;
+          if (fs.m_key[q] > kt) G += fs.m_E[q];
+        if (G < limit) atomicMin(&fs.key_p, kt); else fs.dropped = 1;
       }
       __syncthreads();
       const bool inside = k_act || bin_p > fs.bin_low || fs.dropped != 0;
-      if (!inside && !minp_bounds) return 11;                                 // uniform: the cut may lie below L
+      if (!inside && !minp_bounds) return 11;                                 // uniform: the cut may lie below the list
       key_cut = max(key_k, fs.key_p);
     } else if (!k_act && !minp_bounds) {
-      if (minp_on) return 12;                                                 // uniform: min-p reaches below L
+      if (minp_on) return 12;                                                 // uniform: min-p reaches below the list
       whole_row = true;                                                       // no filter at all: every token is kept
     }
 
@@ -531,8 +593,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       constexpr int EPL = (DT == SIP_F32) ? 4 : 8;
       constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
       const float zmax = value_of(bkey);
-      float c_row, c_lo;
-      scale_pair(rp, c_row, c_lo);
       const int e_last = ((V - 1) / EPL) * EPL;
       auto ldrow = [&](int e0) {                            // clamped: always a valid address
         return *reinterpret_cast<const uint4*>(row + (size_t)min(e0, e_last) * ESZ);
@@ -557,7 +617,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
           if (v < V) {
             const uint32_t word = has_pen ? bm[v >> 5] : 0u;
             if ((word >> (v & 31)) & 1u) {                                     // carries a penalty: value from the list
-              const float sv = value_of(ck[top - (pre[v >> 5] + __popc(word & ((1u << (v & 31)) - 1u)))]);
+              const float sv = value_of(cnt[pre[v >> 5] + __popc(word & ((1u << (v & 31)) - 1u))]);
               keys[i] = key_of(sv);
               E[i] = mass(sv);
             } else {
@@ -570,14 +630,11 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
         }
       };
       // first read: mass of every block of BLK consecutive elements (one block = UNR loads per
-      // lane of one wave) into hm[]; waves take contiguous runs of blocks
+      // lane of one wave) into hd[] (still all zero); waves take contiguous runs of blocks
       constexpr int UNR = 4;
       constexpr int BLK = UNR * kWave * EPL;
       const int nblk = (V + BLK - 1) / BLK;                 // <= kBins because V <= 262144
       const int per_wave = (nblk + kFinalWaves - 1) / kFinalWaves;
-      __syncthreads();                                      // the suffix masses in hm[] are no longer needed
-      for (int i = tid; i < kBins; i += NT) hm[i] = 0;
-      __syncthreads();
       for (int blk = wave * per_wave; blk < min(nblk, (wave + 1) * per_wave); ++blk) {
         const int base = blk * BLK;
         uint4 q[UNR];
@@ -593,7 +650,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
           for (int i = 0; i < EPL; ++i) mine += E[i];
         }
         mine = dpp_scan_add_u64(mine);
-        if (lane == kWave - 1) hm[blk] = mine;
+        if (lane == kWave - 1) hd[blk] = mine;
       }
       __syncthreads();
       // prefix over the blocks, find the block that holds the crossing
@@ -602,7 +659,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
         const int b0 = kBinsPerThread * tid;
         unsigned long long w[kBinsPerThread], msum = 0;
 #pragma unroll
-        for (int j = 0; j < kBinsPerThread; ++j) { w[j] = hm[b0 + j]; msum += w[j]; }
+        for (int j = 0; j < kBinsPerThread; ++j) { w[j] = hd[b0 + j]; msum += w[j]; }
         const unsigned long long minc = dpp_scan_add_u64(msum);
         if (lane == kWave - 1) fs.r64[wave] = minc;
         __syncthreads();
@@ -612,7 +669,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
           if (ww < wave) ex += fs.r64[ww];
           S3 += fs.r64[ww];
         }
-        const unsigned long long j24 = philox_word0(a.seed, rp.row_id, a.step) >> 8;
         target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);           // floor(j * S3 / 2^24)
 #pragma unroll
         for (int j = 0; j < kBinsPerThread; ++j) {
@@ -669,109 +725,92 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       if (token == 0x7FFFFFFF || token < 0) return 13;                        // uniform
       token_key = fs.token_key;
     } else {
-    // ---- (8) draw: kept mass per index bin, prefix, then resolve inside the crossing bin
-    auto kept = [&](float s, uint32_t key) {
-      return key >= key_cut && key > key_c && (!minp_on || __fsub_rn(s, m) >= t_minp);
-    };
-    int ishift = 0;
-    while (((V - 1) >> ishift) >= kBins) ++ishift;
-    __syncthreads();                                       // every reader of the suffix masses is done
-    for (int i = tid; i < kBins; i += NT) hm[i] = 0;
-    __syncthreads();
-    for (uint32_t i = tid; i < nlist; i += NT) {
-      const uint32_t p = at(i);
-      const uint32_t key = ck[p];
-      const float s = value_of(key);
-      if (kept(s, key)) {
-        const unsigned long long E = mass(s);
-        if (E) atomicAdd(&hm[ci[p] >> ishift], E);
-      }
-    }
-    __syncthreads();
-    unsigned long long target;
-    {
-      const int b0 = kBinsPerThread * tid;                 // ascending index order
-      unsigned long long w[kBinsPerThread], msum = 0;
+      // ---- (8) draw: kept mass per index bin, prefix, then resolve inside the crossing bin
+      auto kept = [&](uint32_t k) {
+        return k >= key_cut && k > key_c && (!minp_on || __fsub_rn(value_of(k), m) >= t_minp);
+      };
+      int ishift = 0;
+      while (((V - 1) >> ishift) >= kBins) ++ishift;
+      unsigned long long keptmask = 0;                      // bit r: register entry r is in the kept set
 #pragma unroll
-      for (int j = 0; j < kBinsPerThread; ++j) { w[j] = hm[b0 + j]; msum += w[j]; }
-      const unsigned long long minc = dpp_scan_add_u64(msum);
-      if (lane == kWave - 1) fs.r64[wave] = minc;
+      for (int r = 0; r < NE; ++r) {
+        if (live(r) && idx[r] != kNoIdx && kept(key[r])) {
+          const unsigned long long E = E_of(r);
+          if (E) { atomicAdd(&hd[idx[r] >> ishift], E); keptmask |= 1ull << r; }
+        }
+      }
       __syncthreads();
-      unsigned long long ex = minc - msum, S3 = 0;
+      SIP_MARK(25);
+      unsigned long long target;
+      {
+        const int b0 = kBinsPerThread * tid;                 // ascending index order
+        unsigned long long w[kBinsPerThread], msum = 0;
 #pragma unroll
-      for (int ww = 0; ww < kFinalWaves; ++ww) {
-        if (ww < wave) ex += fs.r64[ww];
-        S3 += fs.r64[ww];
-      }
-      const unsigned long long j24 = philox_word0(a.seed, rp.row_id, a.step) >> 8;
-      target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);             // floor(j * S3 / 2^24)
+        for (int j = 0; j < kBinsPerThread; ++j) { w[j] = hd[b0 + j]; msum += w[j]; }
+        const unsigned long long minc = dpp_scan_add_u64(msum);
+        if (lane == kWave - 1) fs.r64[wave] = minc;
+        __syncthreads();
+        unsigned long long ex = minc - msum, S3 = 0;
 #pragma unroll
-      for (int j = 0; j < kBinsPerThread; ++j) {
-        if (ex <= target && target < ex + w[j]) { fs.bin_d = b0 + j; fs.before_d = ex; }
-        ex += w[j];
+        for (int ww = 0; ww < kFinalWaves; ++ww) {
+          if (ww < wave) ex += fs.r64[ww];
+          S3 += fs.r64[ww];
+        }
+        target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);             // floor(j * S3 / 2^24)
+#pragma unroll
+        for (int j = 0; j < kBinsPerThread; ++j) {
+          if (ex <= target && target < ex + w[j]) { fs.bin_d = b0 + j; fs.before_d = ex; }
+          ex += w[j];
+        }
       }
-    }
-    __syncthreads();
-    const int bin_d = fs.bin_d;
-    if (bin_d < 0) return 13;                                                 // uniform (no kept mass)
-    for (uint32_t i = tid; i < nlist; i += NT) {
-      const uint32_t p = at(i);
-      const uint32_t key = ck[p];
-      const float s = value_of(key);
-      if ((int)(ci[p] >> ishift) == bin_d && kept(s, key)) {
-        const uint32_t q = atomicAdd(&fs.n_memb3, 1u);
-        if (q < (uint32_t)kMembers) { fs.m_key[q] = key; fs.m_idx[q] = ci[p]; fs.m_E[q] = mass(s); }
+      __syncthreads();
+      const int bin_d = fs.bin_d;
+      SIP_MARK(26);
+      if (bin_d < 0) return 13;                                               // uniform (no kept mass)
+#pragma unroll
+      for (int r = 0; r < NE; ++r) {
+        if (((keptmask >> r) & 1ull) && (int)(idx[r] >> ishift) == bin_d) {
+          const uint32_t q = atomicAdd(&fs.n_memb3, 1u);
+          if (q < (uint32_t)kMembers) { fs.m_key[q] = key[r]; fs.m_idx[q] = idx[r]; fs.m_E[q] = E_of(r); }
+        }
       }
-    }
-    __syncthreads();
-    const uint32_t nm = fs.n_memb3;
-    if (nm > (uint32_t)kMembers) return 9;                                    // uniform
-    if ((uint32_t)tid < nm) {
-      const uint32_t v = fs.m_idx[tid];
-      unsigned long long C = fs.before_d;
+      __syncthreads();
+      const uint32_t nm = fs.n_memb3;
+      SIP_MARK(27);
+      if (nm > (uint32_t)kMembers) return 9;                                  // uniform
+      if ((uint32_t)tid < nm) {
+        const uint32_t v = fs.m_idx[tid];
+        unsigned long long C = fs.before_d;
 #pragma unroll 8
-      for (uint32_t q = 0; q < nm; ++q)
-        if (fs.m_idx[q] <= v) C += fs.m_E[q];
-      if (C > target) atomicMin(&fs.token, (int)v);
-    }
-    __syncthreads();
-    token = fs.token;
-    if (token == 0x7FFFFFFF) return 13;                                       // uniform
-    if ((uint32_t)tid < nm && fs.m_idx[tid] == (uint32_t)token) fs.token_key = fs.m_key[tid];
-    __syncthreads();
-    token_key = fs.token_key;
+        for (uint32_t q = 0; q < nm; ++q)
+          if (fs.m_idx[q] <= v) C += fs.m_E[q];
+        // members have mass > 0 and distinct indices: exactly one of them is the first crossing
+        if (C > target && C - fs.m_E[tid] <= target) { fs.token = (int)v; fs.token_key = fs.m_key[tid]; }
+      }
+      __syncthreads();
+      token = fs.token;
+      if (token == 0x7FFFFFFF) return 13;                                     // uniform
+      token_key = fs.token_key;
     }
   }
 
   SIP_MARK(9);
-  // ---- (9) outputs.  Past this point nothing can fail.
-  if (tid == 0) a.out_ids[b] = token;
-  if (a.k_lp >= 0) {
-    const int cols = 1 + a.k_lp;
-    if (tid == 0) {
+  // ---- (9) the token and its logprob.  Past this point nothing can fail.
+  if (tid == 0) {
+    a.out_ids[b] = token;
+    if (a.k_lp >= 0) {
+      const int cols = 1 + a.k_lp;
       a.out_lp_ids[(size_t)b * cols] = token;
       a.out_lp[(size_t)b * cols] = (float)((double)value_of(token_key) - (double)m - lnZ);
     }
-    if (n_top > 0) {
-      // The gathered list holds every element at or above the bin of the n-th best, so an
-      // entry's rank in this list is its rank in the row.
-      const uint32_t nt = fs.n_top;
-      if ((uint32_t)tid < nt) {
-        const uint32_t key = fs.t_key[tid], v = fs.t_idx[tid];
-        uint32_t rank = 0;
-#pragma unroll 8
-        for (uint32_t q = 0; q < nt; ++q) {
-          const uint32_t kq = fs.t_key[q];
-          rank += (kq > key || (kq == key && fs.t_idx[q] < v)) ? 1u : 0u;
-        }
-        if (rank < n_top) {
-          a.out_lp_ids[(size_t)b * cols + 1 + rank] = (int)v;
-          a.out_lp[(size_t)b * cols + 1 + rank] = (float)((double)value_of(key) - (double)m - lnZ);
-        }
-      }
-    }
   }
   SIP_MARK(10);
+#ifdef SIP_TIMING
+  if (blockIdx.x == 0 && tid == 0) {
+    long long* dbg = reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1));
+    dbg[24] = fs.n_top; dbg[25] = fs.n_memb; dbg[26] = fs.n_memb2; dbg[27] = fs.n_memb3; dbg[28] = total_seg; dbg[31] = ndist;
+  }
+#endif
   return 1;
 }
 
@@ -862,8 +901,19 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a) {
   int how = 2;                                   // 2: not eligible for the single-pass path
   int code = 0;
   if (candidate_target(rp, a) != 0) {
-    how = fast_row<DT>(a, b, rp, dynraw, fs, a.S, a.chunk_len, a.cap_w);
-    if (how == 8 || how == 11 || how == 12) {
+    // At most two attempts, written as a loop so that the kernel holds one copy of fast_row.
+    int S = a.S, chunk_len = a.chunk_len, cap_w = a.cap_w;
+#pragma nounroll
+    for (int attempt = 0; attempt < 2; ++attempt) {
+      int r = fast_row<DT, kCandShort>(a, b, rp, dynraw, fs, S, chunk_len, cap_w);
+      if (r == kNeedLong) r = fast_row<DT, kCandLong>(a, b, rp, dynraw, fs, S, chunk_len, cap_w);
+      if (attempt == 1) {
+        how = r == 1 ? 1 : 16 + r;               // 17..29: failed again after the retry
+        if (r == 1) code = 15;                   // 15: finished by the retry (still one HBM pass)
+        break;
+      }
+      how = r;
+      if (r != 8 && r != 11 && r != 12) break;
       // The list was complete but too short.  Where min-p is on, the threshold that bounds the
       // kept set is known exactly now that the maximum is; otherwise lower the threshold by a
       // quarter of its distance to the maximum.  One retry, then the exact path.
@@ -873,15 +923,12 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a) {
       if (rp.min_p > 0.0f && !rp.greedy) {
         const float zt = (m + (float)log((double)rp.min_p)) * rp.tau;
         t_new = fminf(t_new, zt - 1.0e-5f * fabsf(zt) - 1.0e-30f);
-        if (how != 8) t_new = zt - 1.0e-5f * fabsf(zt) - 1.0e-30f;
+        if (r != 8) t_new = zt - 1.0e-5f * fabsf(zt) - 1.0e-30f;
       }
-      if (t_new < t_old) {
-        const Args copy = a;
-        restream_row<DT>(copy, b, rp, t_new, fs);
-        const int again = fast_row<DT>(a, b, rp, dynraw, fs, 1, 0x40000000, a.S * kStreamWaves * a.cap_w);
-        how = again == 1 ? 1 : 16 + again;       // 17..29: failed again after the retry
-        if (again == 1) code = 15;               // 15: finished by the retry (still one HBM pass)
-      }
+      if (!(t_new < t_old)) break;
+      const Args copy = a;
+      restream_row<DT>(copy, b, rp, t_new, fs);
+      S = 1; chunk_len = 0x40000000; cap_w = a.S * kStreamWaves * a.cap_w;
     }
   }
   if (how != 1) {

@@ -69,9 +69,8 @@ __device__ __forceinline__ int candidate_target(const RowParams& r, const Args& 
   // min-p keeps what lies within tau * ln(1/min_p) of the maximum: the list must reach that far
   // down, and how many elements that is grows quickly with the temperature
   if (minp_on && r.min_p < 1.0f) t = max(t, 1024 + (int)(341.0f * r.tau * -__logf(r.min_p)));
-  // the 13-bit threshold rounds down (up to ~1.3x more entries) and up to kSideMax/2 history
-  // tokens typically join the list
-  if (t + (t >> 2) + 2048 > a.nc_cap) return 0;
+  // the 13-bit threshold rounds down: up to ~1.3x more entries than asked for
+  if (t + (t >> 2) + (t >> 3) > a.nc_cap) return 0;
   return t;
 }
 
