@@ -168,6 +168,11 @@ __device__ __forceinline__ unsigned long long last_lane_u64(unsigned long long v
   return ((unsigned long long)last_lane_u32((uint32_t)(v >> 32)) << 32) | last_lane_u32((uint32_t)v);
 }
 
+__device__ __forceinline__ unsigned long long readlane_u64(unsigned long long v, int l) {
+  return ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), l) << 32) |
+         (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
+}
+
 // fp32 mass in (0, 1] -> integer units of 2^-40 (truncating); exact above 2^-16
 __device__ __forceinline__ unsigned long long fix_of(float e) {
   return (unsigned long long)(e * kFixScale);

@@ -18,6 +18,8 @@
 // reason code > 1 and the caller tries again with a longer list or runs the exact multi-pass
 // path on the row; 1 means the row is finished.
 #pragma once
+#include <type_traits>
+
 #include "sip_device.h"
 #include "sip_exact.h"
 #include "sip_stream.h"
@@ -31,8 +33,9 @@ constexpr int kBinsPerThread = kBins / kFinalThreads;
 constexpr int kMembers = 256;        // entries of one bin that can be resolved by all-pairs comparison
 constexpr int kSideMax = 4096;       // distinct history tokens per row the fast path handles
 constexpr int kMaxChunks = 32;
-constexpr int kTopList = 256;        // entries at or above the bin of the n-th best (half a workgroup ranks them)
+constexpr int kTopList = kFinalThreads / 2 < 256 ? kFinalThreads / 2 : 256;        // entries at or above the bin of the n-th best (half a workgroup ranks them)
 constexpr int kTokRegs = 8;          // history tokens a thread keeps in registers between phases
+constexpr int kWordRegs = 16;        // bitmap words a thread owns (2^18 / 32 / kFinalThreads)
 constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
 constexpr int kNeedLong = 30;        // internal: the list needs the variant with more registers per thread
 constexpr int kCandShort = 8, kCandLong = 24;   // candidate entries per thread of the two variants
@@ -104,7 +107,8 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   constexpr int NT = kFinalThreads;
   constexpr int SR = kSideRegs;
   constexpr int NE = CR + SR;                               // register entries per thread
-  constexpr bool STORE = CR <= 8;                           // keep mass and bin in registers too
+  constexpr bool STORE = CR <= kCandShort;
+  typedef typename std::conditional<(NE <= 32), uint32_t, unsigned long long>::type mask_t;                           // keep mass and bin in registers too
   constexpr int NS = STORE ? NE : 1;
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
   const int V = a.V;
@@ -190,10 +194,17 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       if (t >= 0 && t < V) atomicOr(&bm[t >> 5], 1u << (t & 31));
     }
   }
-  float T_row = -INFINITY;
-  int R_max = -(1 << 30);
-  for (int c = 0; c < S; ++c) { T_row = fmaxf(T_row, fs.Tc[c]); R_max = max(R_max, fs.R[c]); }
   __syncthreads();
+  // largest chunk threshold and reference exponent: lane c reads chunk c (S <= 32), then a wave maximum
+  float T_row;
+  int R_max;
+  {
+    const int c = min(lane, S - 1);
+    const uint32_t kt = key_of(fs.Tc[c]);
+    const uint32_t kr = (uint32_t)fs.R[c] ^ 0x80000000u;
+    T_row = value_of(last_lane_u32(dpp_scan_max_u32(kt)));
+    R_max = (int)(last_lane_u32(dpp_scan_max_u32(kr)) ^ 0x80000000u);
+  }
   if (fs.fail_seg || !(T_row == T_row)) return 3;                             // uniform
   const uint32_t total_seg = fs.segoff[nseg];
   if (total_seg > (uint32_t)a.nc_cap) return 5;                               // uniform
@@ -234,10 +245,17 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   // run of bitmap words
   uint32_t ndist = 0;
   if (has_pen) {
-    const int perw = (W + NT - 1) / NT;
-    const int w0 = tid * perw, w1 = min(W, w0 + perw);
+    const int perw = (W + NT - 1) / NT;                   // <= kWordRegs because V <= 262144
+    const int w0 = tid * perw;
+    uint32_t wd[kWordRegs];                                // all reads go out together
+#pragma unroll
+    for (int j = 0; j < kWordRegs; ++j) wd[j] = bm[min(w0 + j, W - 1)];
     uint32_t local = 0;
-    for (int w = w0; w < w1; ++w) local += (uint32_t)__popc(bm[w]);
+#pragma unroll
+    for (int j = 0; j < kWordRegs; ++j) {
+      if (!(j < perw && w0 + j < W)) wd[j] = 0;
+      local += (uint32_t)__popc(wd[j]);
+    }
     const uint32_t incl = dpp_scan_add_u32(local);
     if (lane == kWave - 1) fs.r32[wave] = incl;
     __syncthreads();
@@ -249,11 +267,12 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       ndist += t;
     }
     if (ndist > (uint32_t)kSideMax) return 4;                                 // uniform
-    for (int w = w0; w < w1; ++w) {
-      uint32_t bits = bm[w];
-      if (bits) pre[w] = (unsigned short)slot;
+#pragma unroll
+    for (int j = 0; j < kWordRegs; ++j) {
+      uint32_t bits = wd[j];
+      if (bits) pre[w0 + j] = (unsigned short)slot;
       while (bits) {                                                          // token of each slot
-        stok[slot] = (uint32_t)((w << 5) + __ffs((int)bits) - 1);
+        stok[slot] = (uint32_t)(((w0 + j) << 5) + __ffs((int)bits) - 1);
         bits &= bits - 1;
         ++slot;
       }
@@ -267,13 +286,16 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   float raw[SR];
 #pragma unroll
   for (int r = 0; r < SR; ++r) {
-    const uint32_t i = (uint32_t)(r * NT + tid);
     idx[CR + r] = kNoIdx; raw[r] = 0.0f;
-    if ((uint32_t)(r * NT) < ndist && i < ndist) {
-      idx[CR + r] = stok[i];
-      raw[r] = load_elem<DT>(row, (int)idx[CR + r]);
+    if ((uint32_t)(r * NT) < ndist) {                                        // uniform
+      const uint32_t i = (uint32_t)(r * NT + tid);
+      const uint32_t t = stok[min(i, (uint32_t)kSideMax - 1)];
+      if (i < ndist) idx[CR + r] = t;
     }
   }
+#pragma unroll
+  for (int r = 0; r < SR; ++r)
+    if (idx[CR + r] != kNoIdx) raw[r] = load_elem<DT>(row, (int)idx[CR + r]);
   // ---- (3) multiplicities of the history tokens
   if (has_pen && rp.phi != 0.0f) {
     auto count = [&](int t) {
@@ -282,21 +304,38 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
         atomicAdd(&cnt[pre[t >> 5] + __popc(word & ((1u << (t & 31)) - 1u))], 1u);
       }
     };
+    const int rounds = (int)min((long long)kTokRegs, (hi - lo + NT - 1) / NT);   // uniform
+    uint32_t cw[kTokRegs], cp[kTokRegs];
 #pragma unroll
-    for (int j = 0; j < kTokRegs; ++j) count(tok[j]);
+    for (int j = 0; j < kTokRegs; ++j) {
+      if (j < rounds) {
+        const int t = min(max(tok[j], 0), V - 1);
+        cw[j] = bm[t >> 5]; cp[j] = pre[t >> 5];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < kTokRegs; ++j) {
+      const int t = tok[j];
+      if (j < rounds && t >= 0 && t < V) atomicAdd(&cnt[cp[j] + __popc(cw[j] & ((1u << (t & 31)) - 1u))], 1u);
+    }
     for (long long i = lo + tid + (long long)kTokRegs * NT; i < hi; i += NT) count(a.tokens[i]);
   }
   // (2d) candidates that carry a penalty are dropped: they come back with their penalised value
   // as history entries
   bool anyc = false;
+  uint32_t fw[CR];
+#pragma unroll
+  for (int r = 0; r < CR; ++r) {
+    fw[r] = 0;
+    if (r < per && has_pen) fw[r] = bm[min(creg[r].y, (uint32_t)V - 1) >> 5];   // uniform condition
+  }
 #pragma unroll
   for (int r = 0; r < CR; ++r) {
     const uint2 e = creg[r];
-    bool keep = r < per && e.y < (uint32_t)V;
-    if (keep && has_pen) keep = ((bm[e.y >> 5] >> (e.y & 31)) & 1u) == 0;
+    const bool keep = (r < per) & (e.y < (uint32_t)V) & (((fw[r] >> (e.y & 31)) & 1u) == 0);
     idx[r] = keep ? e.y : kNoIdx;
     key[r] = e.x;
-    anyc |= keep && __uint_as_float(e.x) >= T_row;
+    anyc |= keep & (__uint_as_float(e.x) >= T_row);
   }
   __syncthreads();
 
@@ -304,22 +343,37 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   // ---- (4) penalised values of the history entries; maximum of the list (lowest index on ties)
   long long corr = 0;               // mass the streaming pass counted for elements that carry a penalty
   uint32_t bkey = 0, bidx = kNoIdx;
+  {
+    // everything these rounds read from LDS is requested first, then used
+    uint32_t mult[SR];
+    BulkRef ref[SR];
+    const float inv_len = 1.0f / (float)chunk_len;
 #pragma unroll
-  for (int r = 0; r < SR; ++r) {
-    if ((uint32_t)(r * NT) < ndist && idx[CR + r] != kNoIdx) {
-      const uint32_t v = idx[CR + r];
-      const float rv = raw[r];
-      const float zp = penalise(rv, cnt[r * NT + tid], rp.theta, rp.phi, rp.psi);
-      key[CR + r] = __float_as_uint(zp);
-      // the streaming pass saw the raw value: if it was below its chunk's threshold it went into
-      // the bulk sum and has to come out again
-      const int c = (int)v / chunk_len;
-      if (!(rv >= fs.Tc[c])) {
-        BulkRef ref;
-        ref.Tc = fs.Tc[c]; ref.c = c_row; ref.r0 = fs.r0[c]; ref.R = fs.R[c];
-        const unsigned long long u = bulk_units(bulk_term(rv, ref));
-        const int sh = R_max - ref.R;
-        corr += (long long)(sh < 64 ? (u >> sh) : 0ull);
+    for (int r = 0; r < SR; ++r) {
+      if ((uint32_t)(r * NT) < ndist) {                                      // uniform
+        const uint32_t v = min(idx[CR + r], (uint32_t)V - 1);
+        // chunk of v: quotient by a float reciprocal, put right by one step either way
+        int c = (int)((float)v * inv_len);
+        c = min(c, S - 1);
+        c -= (long long)c * chunk_len > (long long)v;
+        c += c + 1 < S && (long long)(c + 1) * chunk_len <= (long long)v;
+        mult[r] = cnt[r * NT + tid];
+        ref[r].Tc = fs.Tc[c]; ref[r].c = c_row; ref[r].r0 = fs.r0[c]; ref[r].R = fs.R[c];
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < SR; ++r) {
+      if ((uint32_t)(r * NT) < ndist && idx[CR + r] != kNoIdx) {
+        const float rv = raw[r];
+        const float zp = penalise(rv, mult[r], rp.theta, rp.phi, rp.psi);
+        key[CR + r] = __float_as_uint(zp);
+        // the streaming pass saw the raw value: if it was below its chunk's threshold it went into
+        // the bulk sum and has to come out again
+        if (!(rv >= ref[r].Tc)) {
+          const unsigned long long u = bulk_units(bulk_term(rv, ref[r]));
+          const int sh = R_max - ref[r].R;
+          corr += (long long)(sh < 64 ? (u >> sh) : 0ull);
+        }
       }
     }
   }
@@ -444,10 +498,12 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   const int bin_k = k_act ? fs.bin_k : 0, bin_n = fs.bin_n;
 
   // bulk mass -> units of 2^-40 relative to the maximum
-  unsigned long long bulk = 0;
-  for (int c = 0; c < S; ++c) {
+  unsigned long long bulk;
+  {
+    const int c = min(lane, S - 1);
     const int sh = R_max - fs.R[c];
-    bulk += sh < 64 ? (fs.bulk[c] >> sh) : 0ull;
+    const unsigned long long bc = fs.bulk[c];
+    bulk = last_lane_u64(dpp_scan_add_u64((lane < S && sh < 64) ? (bc >> sh) : 0ull));
   }
   bulk = (long long)bulk > corr_total ? bulk - (unsigned long long)corr_total : 0ull;
   // 2^x with x split into integer and fraction: the fraction goes through the hardware exp2 (1 ulp,
@@ -465,17 +521,28 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   SIP_MARK(6);
   // ---- (6) gather the bin of the k-th largest and everything at or above the bin of the n-th best
   if (k_act || n_top > 0) {
+    mask_t mk = 0, mt = 0;            // bit r: register entry r lies in the bin of the k-th / belongs to the top list
 #pragma unroll
     for (int r = 0; r < NE; ++r) {
       if (live(r) && idx[r] != kNoIdx) {
         const int bin = b_of(r);
-        if (k_act && bin == bin_k) {
-          const uint32_t q = atomicAdd(&fs.n_memb, 1u);
-          if (q < (uint32_t)kMembers) { fs.m_key[q] = key[r]; fs.m_E[q] = E_of(r); }
+        mk |= (mask_t)(k_act & (bin == bin_k)) << r;
+        mt |= (mask_t)((n_top > 0) & (bin >= bin_n)) << r;
+      }
+    }
+    uint32_t qk = 0, qt = 0;            // one reservation per thread and list
+    if (mk) qk = atomicAdd(&fs.n_memb, (uint32_t)__popcll((unsigned long long)mk));
+    if (mt) qt = atomicAdd(&fs.n_top, (uint32_t)__popcll((unsigned long long)mt));
+    if (mk | mt) {
+#pragma unroll
+      for (int r = 0; r < NE; ++r) {
+        if ((mk >> r) & 1u) {
+          if (qk < (uint32_t)kMembers) { fs.m_key[qk] = key[r]; fs.m_E[qk] = E_of(r); }
+          ++qk;
         }
-        if (n_top > 0 && bin >= bin_n) {
-          const uint32_t q = atomicAdd(&fs.n_top, 1u);
-          if (q < (uint32_t)kTopList) { fs.t_key[q] = key[r]; fs.t_idx[q] = idx[r]; }
+        if ((mt >> r) & 1u) {
+          if (qt < (uint32_t)kTopList) { fs.t_key[qt] = key[r]; fs.t_idx[qt] = idx[r]; }
+          ++qt;
         }
       }
     }
@@ -485,11 +552,28 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   SIP_MARK(24);
   // best-n (upper half of the workgroup) and the k-th largest (lower half) side by side
   SIP_MARK_T(29, 256);
-  if (a.k_lp >= 0 && n_top > 0 && tid >= NT / 2) {
-    // The gathered list holds every element at or above the bin of the n-th best, so an
-    // entry's rank in this list is its rank in the row.
+  // The gathered list holds every element at or above the bin of the n-th best, so an entry's
+  // rank in this list is its rank in the row.  Up to 64 entries are ranked by one wave out of
+  // its own registers; longer lists by half the workgroup out of LDS.
+  const uint32_t nt_all = (a.k_lp >= 0 && n_top > 0) ? (uint32_t)__builtin_amdgcn_readfirstlane((int)fs.n_top) : 0u;
+  if (nt_all > 0 && nt_all <= (uint32_t)kWave) {
+    if (wave == 1) {
+      const int cols = 1 + a.k_lp;
+      const uint32_t kt = fs.t_key[lane], v = fs.t_idx[lane];
+      uint32_t rank = 0;
+      for (uint32_t q = 0; q < nt_all; ++q) {
+        const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
+        const uint32_t iq = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q);
+        rank += (uint32_t)((kq > kt) | ((kq == kt) & (iq < v)));
+      }
+      if ((uint32_t)lane < nt_all && rank < n_top) {
+        a.out_lp_ids[(size_t)b * cols + 1 + rank] = (int)v;
+        a.out_lp[(size_t)b * cols + 1 + rank] = (float)((double)value_of(kt) - (double)m - lnZ);
+      }
+    }
+  } else if (nt_all > 0 && tid >= NT / 2) {
     const int cols = 1 + a.k_lp;
-    const uint32_t nt = fs.n_top;
+    const uint32_t nt = nt_all;
     const uint32_t t = (uint32_t)(tid - NT / 2);
     if (t < nt) {
       const uint32_t kt = fs.t_key[t], v = fs.t_idx[t];
@@ -509,8 +593,22 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   uint32_t key_k = 0;
   unsigned long long S1 = S0;
   if (k_act) {
-    const uint32_t nm = fs.n_memb, k_rem = (uint32_t)rp.top_k - fs.above_k;
-    if ((uint32_t)tid < nm) {
+    const uint32_t nm = (uint32_t)__builtin_amdgcn_readfirstlane((int)fs.n_memb), k_rem = (uint32_t)rp.top_k - fs.above_k;
+    if (nm <= (uint32_t)kWave) {
+      if (wave == 0) {                    // members in the lanes of one wave, compared through readlane
+        const uint32_t kt = fs.m_key[lane];
+        const unsigned long long Et = fs.m_E[lane];
+        uint32_t gt = 0, ge = 0;
+        unsigned long long sum_ge = 0;
+        for (uint32_t q = 0; q < nm; ++q) {
+          const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
+          const unsigned long long Eq = readlane_u64(Et, (int)q);
+          gt += kq > kt; ge += kq >= kt;
+          sum_ge += kq >= kt ? Eq : 0ull;
+        }
+        if ((uint32_t)lane < nm && gt < k_rem && k_rem <= ge) { fs.key_k = kt; fs.s1_part = sum_ge; }
+      }
+    } else if ((uint32_t)tid < nm) {
       const uint32_t kt = fs.m_key[tid];
       uint32_t gt = 0, ge = 0;
       unsigned long long sum_ge = 0;
@@ -556,18 +654,42 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       const int bin_p = fs.bin_p;
       SIP_MARK(14);
       if (bin_p >= kBins) return 10;                                          // uniform (p <= 0)
+      {
+        mask_t mp = 0;
 #pragma unroll
-      for (int r = 0; r < NE; ++r) {
-        if (live(r) && idx[r] != kNoIdx && key[r] >= key_k && b_of(r) == bin_p) {
-          const uint32_t q = atomicAdd(&fs.n_memb2, 1u);
-          if (q < (uint32_t)kMembers) { fs.m_key[q] = key[r]; fs.m_E[q] = E_of(r); }
+        for (int r = 0; r < NE; ++r)
+          if (live(r) && idx[r] != kNoIdx) mp |= (mask_t)((key[r] >= key_k) & (b_of(r) == bin_p)) << r;
+        if (mp) {
+          uint32_t q = atomicAdd(&fs.n_memb2, (uint32_t)__popcll((unsigned long long)mp));
+#pragma unroll
+          for (int r = 0; r < NE; ++r) {
+            if ((mp >> r) & 1u) {
+              if (q < (uint32_t)kMembers) { fs.m_key[q] = key[r]; fs.m_E[q] = E_of(r); }
+              ++q;
+            }
+          }
         }
       }
       __syncthreads();
-      const uint32_t nm = fs.n_memb2;
+      const uint32_t nm = (uint32_t)__builtin_amdgcn_readfirstlane((int)fs.n_memb2);
       SIP_MARK(15);
       if (nm > (uint32_t)kMembers) return 9;                                  // uniform
-      if ((uint32_t)tid < nm) {
+      if (nm <= (uint32_t)kWave) {
+        if (wave == 0) {
+          const uint32_t kt = fs.m_key[lane];
+          const unsigned long long Et = fs.m_E[lane];
+          unsigned long long G = hm[bin_p];
+          for (uint32_t q = 0; q < nm; ++q) {
+            const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
+            const unsigned long long Eq = readlane_u64(Et, (int)q);
+            G += kq > kt ? Eq : 0ull;
+          }
+          const bool member = (uint32_t)lane < nm;
+          const uint32_t kp = last_lane_u32(dpp_scan_min_u32((member && G < limit) ? kt : 0xFFFFFFFFu));
+          const bool drop = __any(member && !(G < limit));
+          if (lane == 0) { fs.key_p = kp; if (drop) fs.dropped = 1; }
+        }
+      } else if ((uint32_t)tid < nm) {
         const uint32_t kt = fs.m_key[tid];
         unsigned long long G = hm[bin_p];
 #pragma unroll 8
@@ -731,12 +853,12 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       };
       int ishift = 0;
       while (((V - 1) >> ishift) >= kBins) ++ishift;
-      unsigned long long keptmask = 0;                      // bit r: register entry r is in the kept set
+      mask_t keptmask = 0;                                // bit r: register entry r is in the kept set
 #pragma unroll
       for (int r = 0; r < NE; ++r) {
         if (live(r) && idx[r] != kNoIdx && kept(key[r])) {
           const unsigned long long E = E_of(r);
-          if (E) { atomicAdd(&hd[idx[r] >> ishift], E); keptmask |= 1ull << r; }
+          if (E) { atomicAdd(&hd[idx[r] >> ishift], E); keptmask |= (mask_t)1 << r; }
         }
       }
       __syncthreads();
@@ -767,18 +889,39 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       const int bin_d = fs.bin_d;
       SIP_MARK(26);
       if (bin_d < 0) return 13;                                               // uniform (no kept mass)
+      {
+        mask_t md = 0;
 #pragma unroll
-      for (int r = 0; r < NE; ++r) {
-        if (((keptmask >> r) & 1ull) && (int)(idx[r] >> ishift) == bin_d) {
-          const uint32_t q = atomicAdd(&fs.n_memb3, 1u);
-          if (q < (uint32_t)kMembers) { fs.m_key[q] = key[r]; fs.m_idx[q] = idx[r]; fs.m_E[q] = E_of(r); }
+        for (int r = 0; r < NE; ++r) md |= (mask_t)(((keptmask >> r) & 1u) & (mask_t)((int)(idx[r] >> ishift) == bin_d)) << r;
+        if (md) {
+          uint32_t q = atomicAdd(&fs.n_memb3, (uint32_t)__popcll((unsigned long long)md));
+#pragma unroll
+          for (int r = 0; r < NE; ++r) {
+            if ((md >> r) & 1u) {
+              if (q < (uint32_t)kMembers) { fs.m_key[q] = key[r]; fs.m_idx[q] = idx[r]; fs.m_E[q] = E_of(r); }
+              ++q;
+            }
+          }
         }
       }
       __syncthreads();
-      const uint32_t nm = fs.n_memb3;
+      const uint32_t nm = (uint32_t)__builtin_amdgcn_readfirstlane((int)fs.n_memb3);
       SIP_MARK(27);
       if (nm > (uint32_t)kMembers) return 9;                                  // uniform
-      if ((uint32_t)tid < nm) {
+      if (nm <= (uint32_t)kWave) {
+        if (wave == 0) {
+          const uint32_t v = fs.m_idx[lane], kt = fs.m_key[lane];
+          const unsigned long long Et = fs.m_E[lane];
+          unsigned long long C = fs.before_d;
+          for (uint32_t q = 0; q < nm; ++q) {
+            const uint32_t iq = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q);
+            const unsigned long long Eq = readlane_u64(Et, (int)q);
+            C += iq <= v ? Eq : 0ull;
+          }
+          // members have mass > 0 and distinct indices: exactly one of them is the first crossing
+          if ((uint32_t)lane < nm && C > target && C - Et <= target) { fs.token = (int)v; fs.token_key = kt; }
+        }
+      } else if ((uint32_t)tid < nm) {
         const uint32_t v = fs.m_idx[tid];
         unsigned long long C = fs.before_d;
 #pragma unroll 8
@@ -892,11 +1035,19 @@ __device__ __attribute__((noinline)) void restream_row(const Args& a, const int 
 }
 
 template <int DT>
-__global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a) {
+__global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
+  // The arguments are read where they are used, straight from the kernel-argument segment
+  // (the struct is the only parameter, so it starts at offset 0), instead of being held in
+  // scalar registers from the first instruction on: there are more of them than registers.
+  (void)a_by_value;
+  const Args& a = *(const Args*)__builtin_amdgcn_kernarg_segment_ptr();
   extern __shared__ __align__(16) unsigned char dynraw[];
   __shared__ ExactShared ex;
   __shared__ FastShared fs;
   const int b = blockIdx.x;
+#ifdef SIP_TIMING
+  const long long t_begin = wall_clock64();
+#endif
   const RowParams rp = load_row_params(a, b);
   int how = 2;                                   // 2: not eligible for the single-pass path
   int code = 0;
@@ -926,17 +1077,20 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a) {
         if (r != 8) t_new = zt - 1.0e-5f * fabsf(zt) - 1.0e-30f;
       }
       if (!(t_new < t_old)) break;
-      const Args copy = a;
-      restream_row<DT>(copy, b, rp, t_new, fs);
+      restream_row<DT>(a, b, rp, t_new, fs);
       S = 1; chunk_len = 0x40000000; cap_w = a.S * kStreamWaves * a.cap_w;
     }
   }
   if (how != 1) {
     __syncthreads();
-    const Args copy = a;        // only this copy has to live in memory for the out-of-line call
-    exact_row<DT>(copy, b, reinterpret_cast<uint32_t*>(dynraw), ex);
+    exact_row<DT>(a, b, reinterpret_cast<uint32_t*>(dynraw), ex);
   }
+#ifdef SIP_TIMING
+  // development aid: the row's time in this kernel, in 10 ns ticks, above the path code
+  if (threadIdx.x == 0) a.row_path[b] = (code ? code : how) | ((int)(wall_clock64() - t_begin) << 8);
+#else
   if (threadIdx.x == 0) a.row_path[b] = code ? code : how;
+#endif
 }
 
 }  // namespace sip
