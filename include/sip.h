@@ -114,12 +114,15 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
 
 /*
  * Profiling aid.  Arms a one-shot hook on the calling host thread: the next sip_sample() call
- * made by this thread that takes the single-pass path records `hip_event` (a hipEvent_t
- * created by the caller) on its stream between the streaming kernel -- the one pass over the
- * logits, Sec. 5.1's dense row-wise work -- and the finishing kernel, so that a caller can
- * time the two separately with hipEventElapsedTime.  NULL disarms.  No effect on results.
+ * made by this thread that takes the single-pass path launches its two kernels with the given
+ * hipEvent_t handles (created by the caller with timing enabled) attached to the kernel
+ * dispatches themselves: `stream_start` / `stream_stop` take the begin and end time stamps of
+ * the streaming kernel -- the one pass over the logits, Sec. 5.1's dense row-wise work --
+ * and `final_start` / `final_stop` those of the finishing kernel, so that a caller reads each
+ * kernel's duration with hipEventElapsedTime without any extra packet between them.  Either
+ * pair may be NULL; all NULL disarms.  No effect on results.
  */
-void sip_profile_stage_event(void* hip_event);
+void sip_profile_kernel_events(void* stream_start, void* stream_stop, void* final_start, void* final_stop);
 
 /* Host string for a status code (static storage, never NULL). */
 const char* sip_status_string(sip_status status);

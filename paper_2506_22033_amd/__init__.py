@@ -2,8 +2,8 @@
 
 The product is the C library ``libsip.so`` (sources in ``csrc/``, boundary in
 ``include/sip.h``); this package is its thin Python binding."""
-from .binding import (SIP_BF16, SIP_F32, SIP_MAX_K_LOGPROBS, SIP_MAX_V, SipError, load, sip_profile_stage_event, sip_sample,
+from .binding import (SIP_BF16, SIP_F32, SIP_MAX_K_LOGPROBS, SIP_MAX_V, SipError, load, sip_profile_kernel_events, sip_sample,
                       sip_status_string, sip_version, sip_workspace_bytes)
 
-__all__ = ["SIP_BF16", "SIP_F32", "SIP_MAX_K_LOGPROBS", "SIP_MAX_V", "SipError", "load", "sip_profile_stage_event", "sip_sample",
+__all__ = ["SIP_BF16", "SIP_F32", "SIP_MAX_K_LOGPROBS", "SIP_MAX_V", "SipError", "load", "sip_profile_kernel_events", "sip_sample",
            "sip_status_string", "sip_version", "sip_workspace_bytes"]

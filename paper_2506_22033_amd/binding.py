@@ -58,8 +58,8 @@ def load() -> ctypes.CDLL:
             ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         lib.sip_status_string.restype = ctypes.c_char_p
         lib.sip_status_string.argtypes = [ctypes.c_int]
-        lib.sip_profile_stage_event.restype = None
-        lib.sip_profile_stage_event.argtypes = [ctypes.c_void_p]
+        lib.sip_profile_kernel_events.restype = None
+        lib.sip_profile_kernel_events.argtypes = [ctypes.c_void_p] * 4
         lib.sip_version.restype = ctypes.c_int
         lib.sip_version.argtypes = []
         _lib = lib
@@ -70,9 +70,10 @@ def sip_version() -> int:
     return int(load().sip_version())
 
 
-def sip_profile_stage_event(hip_event: Optional[int]) -> None:
-    """Arm the one-shot stage hook with a raw hipEvent_t handle (None disarms)."""
-    load().sip_profile_stage_event(hip_event)
+def sip_profile_kernel_events(stream_start: Optional[int], stream_stop: Optional[int],
+                              final_start: Optional[int] = None, final_stop: Optional[int] = None) -> None:
+    """Arm the one-shot profiling hook with raw hipEvent_t handles (all None disarms)."""
+    load().sip_profile_kernel_events(stream_start, stream_stop, final_start, final_stop)
 
 
 def sip_status_string(status: int) -> str:

@@ -1,6 +1,7 @@
 // Host side of the C boundary declared in include/sip.h: argument checks, workspace
 // carving and kernel launches.  No allocation, no synchronisation.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <atomic>
@@ -51,7 +52,7 @@ struct Layout {
   size_t row_path, side_z, side_c, chunks, cand, total;
 };
 
-thread_local hipEvent_t g_stage_event = nullptr;
+thread_local hipEvent_t g_prof[4] = {nullptr, nullptr, nullptr, nullptr};   // one-shot, see sip_profile_kernel_events()
 
 // Kernels that use more than the default 64 KB of dynamic LDS have to be told so once.
 constexpr int kMaxDynLds = 144 * 1024;
@@ -145,13 +146,17 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
   auto k_final = dtype == SIP_F32 ? sip::final_kernel<SIP_F32> : sip::final_kernel<SIP_BF16>;
   const size_t dyn = std::max(plan.final_lds, 2 * words * sizeof(uint32_t));
   if (!allow_big_lds(reinterpret_cast<const void*>(k_final), dtype == SIP_F32 ? 2 : 3)) return SIP_ERR_HIP;
-  hipLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, a);
+  hipEvent_t ev[4];
+  for (int i = 0; i < 4; ++i) { ev[i] = g_prof[i]; g_prof[i] = nullptr; }
+  if (ev[0] || ev[1])       // the events take the dispatch's own begin / end time stamps
+    hipExtLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, ev[0], ev[1], 0, a);
+  else
+    hipLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, a);
   if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
-  if (g_stage_event) {                       // one-shot profiling hook, see sip_profile_stage_event()
-    (void)hipEventRecord(g_stage_event, stream);
-    g_stage_event = nullptr;
-  }
-  hipLaunchKernelGGL(k_final, dim3(B), dim3(sip::kFinalThreads), dyn, stream, a);
+  if (ev[2] || ev[3])
+    hipExtLaunchKernelGGL(k_final, dim3(B), dim3(sip::kFinalThreads), dyn, stream, ev[2], ev[3], 0, a);
+  else
+    hipLaunchKernelGGL(k_final, dim3(B), dim3(sip::kFinalThreads), dyn, stream, a);
   if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
   return SIP_OK;
 }
@@ -167,7 +172,12 @@ const char* sip_status_string(sip_status status) {
   return "unknown status";
 }
 
-void sip_profile_stage_event(void* hip_event) { g_stage_event = static_cast<hipEvent_t>(hip_event); }
+void sip_profile_kernel_events(void* stream_start, void* stream_stop, void* final_start, void* final_stop) {
+  g_prof[0] = static_cast<hipEvent_t>(stream_start);
+  g_prof[1] = static_cast<hipEvent_t>(stream_stop);
+  g_prof[2] = static_cast<hipEvent_t>(final_start);
+  g_prof[3] = static_cast<hipEvent_t>(final_stop);
+}
 
 int sip_version(void) { return 100; }
 

@@ -25,6 +25,7 @@ namespace sip {
 constexpr int kStreamThreads = 256;
 constexpr int kStreamWaves = kStreamThreads / kWave;
 constexpr int kStreamLoads = 2;             // 16-byte loads per thread per tile
+constexpr int kStreamBufs = 2;              // tiles held in registers: one being processed, the others in flight
 constexpr int kSampleBins = 8192;           // 13-bit keys: sign, exponent, 4 mantissa bits
 constexpr int kSampleSize = 4096;           // elements of a row the threshold is estimated from
 constexpr int kQueueCap = 512;              // entries of one wave's LDS candidate queue
@@ -62,13 +63,19 @@ __device__ __forceinline__ int candidate_target(const RowParams& r, const Args& 
   const bool p_on = r.top_p < 1.0f, minp_on = r.min_p > 0.0f;
   if (k == 0 && !p_on && !minp_on) return 1024;       // plain temperature sampling: the list serves the maximum
                                                       // and best-n, the draw re-reads the row
-  // top-k needs its k largest in the list (plus head-room for the sampling noise of the
-  // threshold); a nucleus with nothing else to bound it tends to be longer than one cut by
-  // min-p, so it starts from a longer list
-  int t = max(k + (k >> 2) + 512, (k == 0 && !minp_on) ? 3072 : 1536);
-  // min-p keeps what lies within tau * ln(1/min_p) of the maximum: the list must reach that far
-  // down, and how many elements that is grows quickly with the temperature
-  if (minp_on && r.min_p < 1.0f) t = max(t, 1024 + (int)(341.0f * r.tau * -__logf(r.min_p)));
+  int t;
+  if (k > 0) {
+    // top-k needs its k largest in the list, plus head-room for the sampling noise of the
+    // threshold; whatever top-p and min-p do afterwards happens inside those k
+    t = k + (k >> 2) + 512;
+  } else {
+    // a nucleus with nothing else to bound it tends to be longer than one cut by min-p, so it
+    // starts from a longer list
+    t = minp_on ? 1536 : 3072;
+    // min-p keeps what lies within tau * ln(1/min_p) of the maximum: the list must reach that
+    // far down, and how many elements that is grows quickly with the temperature
+    if (minp_on && r.min_p < 1.0f) t = max(t, 1024 + (int)(341.0f * r.tau * -__logf(r.min_p)));
+  }
   // the 13-bit threshold rounds down: up to ~1.3x more entries than asked for
   if (t + (t >> 2) + (t >> 3) > a.nc_cap) return 0;
   return t;
@@ -172,13 +179,16 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     }
   };
 
-  // the first two tiles of the chunk are requested before anything else so that they travel
+  // the first tiles of the chunk are requested before anything else so that they travel
   // while the threshold is being worked out
   SIP_SMARK(0);
-  uint4 bufA[kStreamLoads], bufB[kStreamLoads];
-  int tA = c0, tB = c0 + TILE;
-  load_tile(tA, bufA);
-  if (tB < c1) load_tile(tB, bufB);
+  uint4 buf[kStreamBufs][kStreamLoads];
+  int tnext = c0;                                    // first element of the next tile to request
+#pragma unroll
+  for (int k = 0; k < kStreamBufs; ++k) {
+    if (tnext < c1) load_tile(tnext, buf[k]);
+    tnext += TILE;
+  }
 
   // ---- threshold: the same 4096-element sample (1 KB blocks spread evenly over the row) is
   // read by every chunk of the row, so all chunks agree on Tc = the j-th largest sample value
@@ -301,17 +311,24 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   };
 
   SIP_SMARK(3);
-  // two register buffers in ping-pong: while one tile is processed the other one's loads are
-  // in flight
-  while (true) {
-    process_tile(bufA, tA);
-    tA += 2 * TILE;
-    if (tA < c1) load_tile(tA, bufA);
-    if (tB >= c1) break;
-    process_tile(bufB, tB);
-    tB += 2 * TILE;
-    if (tB < c1) load_tile(tB, bufB);
-    if (tA >= c1) break;
+  // kStreamBufs register buffers in rotation: while one tile is processed the loads of the
+  // others are in flight
+  {
+    int tcur = c0;
+    bool more = true;
+    while (more) {
+#pragma unroll
+      for (int k = 0; k < kStreamBufs; ++k) {
+        if (tcur < c1) {
+          process_tile(buf[k], tcur);
+          if (tnext < c1) load_tile(tnext, buf[k]);
+          tnext += TILE;
+          tcur += TILE;
+        } else {
+          more = false;
+        }
+      }
+    }
   }
   SIP_SMARK(4);
   // the queue goes out to the wave's segment in one burst (no global stores inside the loop:
