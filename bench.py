@@ -83,7 +83,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="0..4 = C1..C5 (default 2 = C3, the headline)")
-    ap.add_argument("--cpu-rows", type=int, default=1024, help="row-samples the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=16384, help="row-samples the oracle is timed on (0 = skip)")
     ap.add_argument("--check", action="store_true", help="also compare step 0 with the oracle on 16 rows")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run a plain 256 MiB device copy 4 times (reference for the "
