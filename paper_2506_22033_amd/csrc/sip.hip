@@ -20,7 +20,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // Launch shape of the single-pass path; a function of (B, V, dtype) only.
 struct Plan {
   bool fast;       // false: vocabulary outside what the single-pass kernels are built for
-  int S, chunk_len, cap_w, nc_cap;
+  int S, cap_w, nc_cap;
   size_t final_lds;
 };
 
@@ -39,9 +39,7 @@ Plan make_plan(int32_t B, int32_t V, int dtype) {
   constexpr int kResident = 256 * 8;
   int want = B * 8 <= kResident ? kResident / B : (B * 4 <= kResident ? kResident / B : 8);
   want = std::max(1, std::min({want, sip::kMaxChunks, std::max(1, n_tiles / 2)}));
-  const int chunk_tiles = (n_tiles + want - 1) / want;
-  p.S = (n_tiles + chunk_tiles - 1) / chunk_tiles;     // every chunk non-empty
-  p.chunk_len = chunk_tiles * tile;
+  p.S = want;                                          // <= n_tiles / 2: every chunk holds at least two tiles
   p.cap_w = sip::kQueueCap;
   p.nc_cap = sip::kFinalThreads * sip::kCandLong;     // the finishing kernel holds the list in registers
   p.final_lds = sip::final_lds_fixed(V);
@@ -129,7 +127,7 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
   a.side_c = reinterpret_cast<unsigned int*>(ws + lay.side_c);
   a.chunks = reinterpret_cast<sip::ChunkOut*>(ws + lay.chunks);
   a.cand = reinterpret_cast<uint2*>(ws + lay.cand);
-  a.S = plan.S; a.chunk_len = plan.chunk_len; a.cap_w = plan.cap_w; a.nc_cap = plan.nc_cap;
+  a.S = plan.S; a.cap_w = plan.cap_w; a.nc_cap = plan.nc_cap;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t words = ((size_t)V + 31) / 32;

@@ -40,11 +40,19 @@ struct Args {
   ChunkOut* chunks;         // [B * S]
   uint2* cand;              // [B * S * 4 * cap_w]  (value bits, index)
   int S;                    // chunks per row
-  int chunk_len;            // elements per chunk (multiple of the tile)
   int cap_w;                // candidate slots per wave segment
   int nc_cap;               // candidates the finishing kernel can hold in LDS
   int* row_path;            // [B] diagnostic: 1 = finished by the single-pass path, >1 = exact path (reason)
 };
+
+// A row is cut into S chunks of whole units of `unit` elements (what one wave reads with one
+// 16-byte load per lane), the chunk sizes differing by at most one unit.  First element of
+// chunk ch; chunk_begin(S) is V.
+__host__ __device__ inline int chunk_begin(int ch, int V, int S, int unit) {
+  const long long n = ((long long)V + unit - 1) / unit;
+  const long long e = (long long)ch * n / S * unit;
+  return (int)(e < V ? e : V);
+}
 
 // ApplyPenalty for one seen token: repetition, then frequency, then presence, one fp32
 // rounding per operation (Sec. 2.1 step 3 (1); Sec. 5.1).

@@ -45,6 +45,7 @@ struct FastShared {
   float Tc[kMaxChunks];
   int R[kMaxChunks];
   float r0[kMaxChunks];                 // fractional part of the chunk's reference exponent
+  int cbeg[kMaxChunks + 1];             // first element of each chunk
   unsigned long long bulk[kMaxChunks];
   uint32_t segoff[kMaxChunks * kStreamWaves + 1];
   unsigned long long r64[kFinalWaves];
@@ -103,7 +104,7 @@ __device__ __forceinline__ float load_elem(const char* row, int v) {
 // that takes the row over.
 template <int DT, int CR>
 __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
-                                        FastShared& fs, const int S, const int chunk_len, const int cap_w) {
+                                        FastShared& fs, const int S, const int cap_w) {
   constexpr int NT = kFinalThreads;
   constexpr int SR = kSideRegs;
   constexpr int NE = CR + SR;                               // register entries per thread
@@ -141,6 +142,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     fs.key_p = 0xFFFFFFFFu; fs.n_memb = 0; fs.n_memb2 = 0; fs.n_memb3 = 0; fs.n_top = 0;
     fs.token = 0x7FFFFFFF; fs.key_k = 0; fs.s1_part = 0;
   }
+  if (tid <= S) fs.cbeg[tid] = chunk_begin(tid, V, S, kWave * (DT == SIP_F32 ? 4 : 8));
   if (tid < S) {
     const ChunkOut co = a.chunks[(size_t)b * a.S + tid];
     fs.Tc[tid] = co.Tc; fs.R[tid] = co.R; fs.bulk[tid] = co.bulk;
@@ -347,16 +349,15 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     // everything these rounds read from LDS is requested first, then used
     uint32_t mult[SR];
     BulkRef ref[SR];
-    const float inv_len = 1.0f / (float)chunk_len;
+    const float per_elem = (float)S / (float)V;
 #pragma unroll
     for (int r = 0; r < SR; ++r) {
       if ((uint32_t)(r * NT) < ndist) {                                      // uniform
-        const uint32_t v = min(idx[CR + r], (uint32_t)V - 1);
-        // chunk of v: quotient by a float reciprocal, put right by one step either way
-        int c = (int)((float)v * inv_len);
-        c = min(c, S - 1);
-        c -= (long long)c * chunk_len > (long long)v;
-        c += c + 1 < S && (long long)(c + 1) * chunk_len <= (long long)v;
+        const int v = (int)min(idx[CR + r], (uint32_t)V - 1);
+        // chunk of v: an estimate from the proportion, put right by one step either way
+        int c = min((int)((float)v * per_elem), S - 1);
+        const int lo_c = fs.cbeg[c], hi_c = fs.cbeg[c + 1];
+        c += (v >= hi_c) - (v < lo_c);
         mult[r] = cnt[r * NT + tid];
         ref[r].Tc = fs.Tc[c]; ref[r].c = c_row; ref[r].r0 = fs.r0[c]; ref[r].R = fs.R[c];
       }
@@ -1053,11 +1054,11 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   int code = 0;
   if (candidate_target(rp, a) != 0) {
     // At most two attempts, written as a loop so that the kernel holds one copy of fast_row.
-    int S = a.S, chunk_len = a.chunk_len, cap_w = a.cap_w;
+    int S = a.S, cap_w = a.cap_w;
 #pragma nounroll
     for (int attempt = 0; attempt < 2; ++attempt) {
-      int r = fast_row<DT, kCandShort>(a, b, rp, dynraw, fs, S, chunk_len, cap_w);
-      if (r == kNeedLong) r = fast_row<DT, kCandLong>(a, b, rp, dynraw, fs, S, chunk_len, cap_w);
+      int r = fast_row<DT, kCandShort>(a, b, rp, dynraw, fs, S, cap_w);
+      if (r == kNeedLong) r = fast_row<DT, kCandLong>(a, b, rp, dynraw, fs, S, cap_w);
       if (attempt == 1) {
         how = r == 1 ? 1 : 16 + r;               // 17..29: failed again after the retry
         if (r == 1) code = 15;                   // 15: finished by the retry (still one HBM pass)
@@ -1078,7 +1079,7 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
       }
       if (!(t_new < t_old)) break;
       restream_row<DT>(a, b, rp, t_new, fs);
-      S = 1; chunk_len = 0x40000000; cap_w = a.S * kStreamWaves * a.cap_w;
+      S = 1; cap_w = a.S * kStreamWaves * a.cap_w;
     }
   }
   if (how != 1) {

@@ -139,6 +139,9 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   __shared__ uint32_t key_thr;
 
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+#ifdef SIP_TIMING
+  const long long t_wg_begin = wall_clock64();
+#endif
   // Workgroups are handed to the 8 XCDs round-robin by their id.  The chunks of one row read
   // the same sample, so they are renumbered to land on the same XCD (and its L2): id i works
   // on logical chunk (i % 8) * (n / 8) + i / 8 when n, the grid size, is a multiple of 8.
@@ -149,8 +152,8 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   const int target = candidate_target(rp, a);
   if (target == 0) return;
   const int V = a.V;
-  const int c0 = ch * a.chunk_len;
-  const int c1 = min(V, c0 + a.chunk_len);
+  const int c0 = chunk_begin(ch, V, a.S, kWave * EPL);
+  const int c1 = chunk_begin(ch + 1, V, a.S, kWave * EPL);
   if (c0 >= c1) return;                              // host guarantees every chunk is non-empty
   const char* row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * ESZ;
 
@@ -349,6 +352,13 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     a.chunks[wg] = o;
   }
   SIP_SMARK(5);
+#ifdef SIP_TIMING
+  // development aid: begin and end time of this workgroup in the last slot of its first segment
+  if (tid == 0) {
+    uint2* slot = a.cand + ((size_t)wg * kStreamWaves) * (size_t)a.cap_w + (a.cap_w - 1);
+    *slot = make_uint2((uint32_t)t_wg_begin, (uint32_t)wall_clock64());
+  }
+#endif
 }
 
 }  // namespace sip
