@@ -33,11 +33,11 @@ Plan make_plan(int32_t B, int32_t V, int dtype) {
   if (!p.fast) return p;
   const int tile = sip::kStreamThreads * sip::kStreamLoads * (dtype == SIP_F32 ? 4 : 8);
   const int n_tiles = (V + tile - 1) / tile;
-  // Chunks per row.  Small batches: as many workgroups as fit on the chip at once (5 per compute
-  // unit), so that there is a single, full round.  Large batches: 8, which makes many rounds
+  // Chunks per row.  Small batches: as many workgroups as fit on the chip at once (4 per compute
+  // unit), so that there is a single, full round.  Large batches: 4, which makes many rounds
   // and lets the per-wave candidate queues (kQueueCap each) add up to 16K entries per row.
-  constexpr int kResident = 256 * 8;
-  int want = B * 8 <= kResident ? kResident / B : (B * 4 <= kResident ? kResident / B : 8);
+  constexpr int kResident = 256 * 4;
+  int want = B * 4 <= kResident ? kResident / B : (B * 2 <= kResident ? kResident / B : 4);
   want = std::max(1, std::min({want, sip::kMaxChunks, std::max(1, n_tiles / 2)}));
   p.S = want;                                          // <= n_tiles / 2: every chunk holds at least two tiles
   p.cap_w = sip::kQueueCap;

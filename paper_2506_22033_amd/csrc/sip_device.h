@@ -16,7 +16,7 @@ struct ChunkOut {
   unsigned long long bulk;  // sum over non-candidates of 2^(z*c - R), in units of 2^-30
   float Tc;                 // every element of the chunk with z >= Tc is in a segment
   int R;                    // integer reference exponent of `bulk`
-  unsigned int cnt[4];      // candidates found by each wave (may exceed cap_w: overflow)
+  unsigned int cnt[8];      // candidates found by each of the chunk's 8 waves (may exceed cap_w: overflow)
 };
 
 // Everything one call needs, passed by value to the kernels.

@@ -32,7 +32,7 @@ constexpr int kBins = 2048;
 constexpr int kBinsPerThread = kBins / kFinalThreads;
 constexpr int kMembers = 256;        // entries of one bin that can be resolved by all-pairs comparison
 constexpr int kSideMax = 4096;       // distinct history tokens per row the fast path handles
-constexpr int kMaxChunks = 32;
+constexpr int kMaxChunks = 128 / kStreamWaves;   // one wave takes the prefix of all segment sizes, two per lane
 constexpr int kTopList = kFinalThreads / 2 < 256 ? kFinalThreads / 2 : 256;        // entries at or above the bin of the n-th best (half a workgroup ranks them)
 constexpr int kTokRegs = 8;          // history tokens a thread keeps in registers between phases
 constexpr int kWordRegs = 16;        // bitmap words a thread owns (2^18 / 32 / kFinalThreads)
@@ -1026,7 +1026,9 @@ __device__ __attribute__((noinline)) void restream_row(const Args& a, const int 
     o.bulk = 0;
     for (int w = 0; w < kFinalWaves; ++w) o.bulk += fs.r64[w];
     o.Tc = Tc; o.R = R;
-    o.cnt[0] = fs.rq_n; o.cnt[1] = 0; o.cnt[2] = 0; o.cnt[3] = 0;
+    o.cnt[0] = fs.rq_n;
+#pragma unroll
+    for (int w = 1; w < 8; ++w) o.cnt[w] = 0;
     a.chunks[(size_t)b * a.S] = o;
   }
   // what this workgroup wrote to global memory is read back by other waves of it

@@ -1,6 +1,6 @@
 // Single pass over the logits: the only kernel that touches all B*V elements.
 //
-// A row is cut into S chunks, one 256-thread workgroup each.  The workgroup never learns the
+// A row is cut into S chunks, one 512-thread workgroup each.  The workgroup never learns the
 // row's maximum; instead it picks, from a 4096-element sample spread over the row, a value
 // threshold Tc such that only the top ~1-3 % of the row lies at or above it, and then streams
 // its chunk once:
@@ -22,8 +22,9 @@
 
 namespace sip {
 
-constexpr int kStreamThreads = 256;
+constexpr int kStreamThreads = 512;
 constexpr int kStreamWaves = kStreamThreads / kWave;
+static_assert(kStreamWaves == 8, "ChunkOut::cnt holds one count per wave");
 constexpr int kStreamLoads = 2;             // 16-byte loads per thread per tile
 constexpr int kStreamBufs = 2;              // tiles held in registers: one being processed, the others in flight
 constexpr int kSampleBins = 8192;           // 13-bit keys: sign, exponent, 4 mantissa bits
@@ -129,9 +130,9 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   constexpr int TILE = SUB * kStreamLoads;
   constexpr int SLOADS = kSampleSize / SUB;         // sample loads per thread (4 fp32, 2 bf16)
   constexpr int NSB = SLOADS * kStreamWaves;        // 1 KB sample blocks spread over the row
-  // 16 KB of LDS, used first as the sample histogram (two 16-bit counters per word), then as
-  // four per-wave candidate queues
-  __shared__ __align__(16) unsigned char smem[kSampleBins * 2];
+  // 32 KB of LDS: first the sample histogram (two 16-bit counters per word, 16 KB), then the
+  // per-wave candidate queues
+  __shared__ __align__(16) unsigned char smem[(kSampleBins * 2 > kStreamWaves * kQueueCap * 8) ? kSampleBins * 2 : kStreamWaves * kQueueCap * 8];
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
   __shared__ uint32_t red32[kStreamWaves];
   __shared__ unsigned long long red64[kStreamWaves];

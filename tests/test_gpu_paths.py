@@ -83,6 +83,16 @@ def test_grid_sizes_that_are_not_a_multiple_of_eight(B):
     assert st.rows == B
 
 
+@pytest.mark.parametrize("B,V,dtype_index", [(8, 152064, 2), (2, 262144, 2), (16, 129280, 3)])
+def test_small_batches_cut_rows_into_the_largest_number_of_chunks(B, V, dtype_index):
+    """Few rows of a large vocabulary: the launch plan uses as many chunks per row as the
+    finishing kernel's segment table holds (fp32 and bf16)."""
+    w = workloads.make(dtype_index, B=B, V=V, H=300)
+    st, paths = _check(w, steps=(0,))
+    assert st.rows == B
+    assert np.isin(paths, (1, 15)).all()
+
+
 def test_vocabulary_beyond_the_single_pass_kernels():
     w = workloads.make(4, B=2, V=300000, H=64)
     st, paths = _check(w, steps=(0,))
