@@ -71,8 +71,9 @@ __device__ __forceinline__ int candidate_target(const RowParams& r, const Args& 
     t = k + (k >> 2) + 512;
   } else {
     // a nucleus with nothing else to bound it tends to be longer than one cut by min-p, so it
-    // starts from a longer list
-    t = minp_on ? 1536 : 3072;
+    // starts from a longer list -- as long as still fits, after the threshold's rounding, the 8
+    // entries per thread of the finishing kernel's faster variant
+    t = minp_on ? 1536 : 2560;
     // min-p keeps what lies within tau * ln(1/min_p) of the maximum: the list must reach that
     // far down, and how many elements that is grows quickly with the temperature
     if (minp_on && r.min_p < 1.0f) t = max(t, 1024 + (int)(341.0f * r.tau * -__logf(r.min_p)));
