@@ -38,8 +38,7 @@ constexpr int kTokRegs = 8;          // history tokens a thread keeps in registe
 constexpr int kWordRegs = 16;        // bitmap words a thread owns (2^18 / 32 / kFinalThreads)
 constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
 constexpr int kNeedLong = 30;        // internal: the list needs the variant with more registers per thread
-constexpr int kCandShort = 8, kCandLong = 24;   // candidate entries per thread of the two variants
-constexpr int kSideRegs = kSideMax / kFinalThreads;   // raw logits of side entries, likewise
+constexpr int kCandLong = 24;        // candidate entries per thread of the largest variant
 
 struct FastShared {
   float Tc[kMaxChunks];
@@ -95,20 +94,21 @@ __device__ __forceinline__ float load_elem(const char* row, int v) {
 #define SIP_MARK_T(i, t) do { } while (0)
 #endif
 
-// One attempt at finishing row b from its candidate list.  CR = candidate entries a thread can
-// hold in registers: the list, once read, never goes to memory again -- each thread keeps its
-// share (CR candidates and kSideRegs history tokens) with key, index, mass and value bin in
+// One attempt at finishing row b from its candidate list.  CR / SR = candidate entries /
+// distinct history tokens a thread can hold in registers: the list, once read, never goes to
+// memory again -- each thread keeps its share with key, index, mass and value bin in
 // registers, and the phases below talk to each other only through the LDS histograms and a few
-// small gathered lists.  Returns 1 (finished), kNeedLong (the list does not fit CR entries per
-// thread) or a reason code > 1; outputs written before a failure are overwritten by the path
-// that takes the row over.
-template <int DT, int CR>
+// small gathered lists.  Every register round is unrolled code that costs time even when it
+// holds nothing (0.5-0.7 us each), hence several instantiations and a caller that picks the
+// smallest one that fits.  Returns 1 (finished), kNeedLong (the row does not fit CR or SR
+// entries per thread) or a reason code > 1; outputs written before a failure are overwritten
+// by the path that takes the row over.
+template <int DT, int CR, int SR>
 __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
                                         FastShared& fs, const int S, const int cap_w) {
   constexpr int NT = kFinalThreads;
-  constexpr int SR = kSideRegs;
   constexpr int NE = CR + SR;                               // register entries per thread
-  constexpr bool STORE = CR <= kCandShort;
+  constexpr bool STORE = CR <= 8;
   typedef typename std::conditional<(NE <= 32), uint32_t, unsigned long long>::type mask_t;                           // keep mass and bin in registers too
   constexpr int NS = STORE ? NE : 1;
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
@@ -269,6 +269,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       ndist += t;
     }
     if (ndist > (uint32_t)kSideMax) return 4;                                 // uniform
+    if (ndist > (uint32_t)(NT * SR)) return kNeedLong;                        // uniform
 #pragma unroll
     for (int j = 0; j < kWordRegs; ++j) {
       uint32_t bits = wd[j];
@@ -1037,6 +1038,21 @@ __device__ __attribute__((noinline)) void restream_row(const Args& a, const int 
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 
+// Runs the smallest instantiation of fast_row that can hold the row: the history length bounds
+// the number of distinct tokens; a variant that turns out too small says so early and the next
+// one starts over.  Three variants, one after the other: every further instantiation in this
+// kernel was measured to slow all of them down (0.6-1 us each).
+template <int DT>
+__device__ __forceinline__ int fast_any(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
+                                        FastShared& fs, const int S, const int cap_w, const long long hist_len) {
+  constexpr int NT = kFinalThreads;
+  int r = kNeedLong;
+  if (hist_len <= 2 * NT) r = fast_row<DT, 8, 2>(a, b, rp, dyn, fs, S, cap_w);
+  if (r == kNeedLong) r = fast_row<DT, 8, 8>(a, b, rp, dyn, fs, S, cap_w);
+  if (r == kNeedLong) r = fast_row<DT, kCandLong, 8>(a, b, rp, dyn, fs, S, cap_w);
+  return r == kNeedLong ? 5 : r;
+}
+
 template <int DT>
 __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   // The arguments are read where they are used, straight from the kernel-argument segment
@@ -1054,13 +1070,16 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   const RowParams rp = load_row_params(a, b);
   int how = 2;                                   // 2: not eligible for the single-pass path
   int code = 0;
-  if (candidate_target(rp, a) != 0) {
-    // At most two attempts, written as a loop so that the kernel holds one copy of fast_row.
+  const int target = candidate_target(rp, a);
+  if (target != 0) {
+    long long hist_len = 0;
+    if (a.indptr && a.tokens && a.nnz > 0) hist_len = a.indptr[b + 1] - a.indptr[b];
+    if (hist_len < 0 || hist_len > a.nnz) hist_len = a.nnz;
+    // At most two attempts, written as a loop so that the kernel holds one copy of the code.
     int S = a.S, cap_w = a.cap_w;
 #pragma nounroll
     for (int attempt = 0; attempt < 2; ++attempt) {
-      int r = fast_row<DT, kCandShort>(a, b, rp, dynraw, fs, S, cap_w);
-      if (r == kNeedLong) r = fast_row<DT, kCandLong>(a, b, rp, dynraw, fs, S, cap_w);
+      const int r = fast_any<DT>(a, b, rp, dynraw, fs, S, cap_w, hist_len);
       if (attempt == 1) {
         how = r == 1 ? 1 : 16 + r;               // 17..29: failed again after the retry
         if (r == 1) code = 15;                   // 15: finished by the retry (still one HBM pass)
