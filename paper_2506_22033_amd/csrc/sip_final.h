@@ -37,7 +37,8 @@ constexpr int kTopList = kFinalThreads / 2 < 256 ? kFinalThreads / 2 : 256;     
 constexpr int kTokRegs = 8;          // history tokens a thread keeps in registers between phases
 constexpr int kWordRegs = 16;        // bitmap words a thread owns (2^18 / 32 / kFinalThreads)
 constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
-constexpr int kNeedLong = 30;        // internal: the list needs the variant with more registers per thread
+constexpr int kNeedLong = 30;        // internal: more history tokens than this variant holds per thread
+constexpr int kNeedLongList = 31;    // internal: more candidates than this variant holds per thread
 constexpr int kCandLong = 24;        // candidate entries per thread of the largest variant
 
 struct FastShared {
@@ -100,8 +101,8 @@ __device__ __forceinline__ float load_elem(const char* row, int v) {
 // registers, and the phases below talk to each other only through the LDS histograms and a few
 // small gathered lists.  Every register round is unrolled code that costs time even when it
 // holds nothing (0.5-0.7 us each), hence several instantiations and a caller that picks the
-// smallest one that fits.  Returns 1 (finished), kNeedLong (the row does not fit CR or SR
-// entries per thread) or a reason code > 1; outputs written before a failure are overwritten
+// smallest one that fits.  Returns 1 (finished), kNeedLong / kNeedLongList (the row does not fit
+// SR / CR entries per thread) or a reason code > 1; outputs written before a failure are overwritten
 // by the path that takes the row over.
 template <int DT, int CR, int SR>
 __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
@@ -210,7 +211,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   if (fs.fail_seg || !(T_row == T_row)) return 3;                             // uniform
   const uint32_t total_seg = fs.segoff[nseg];
   if (total_seg > (uint32_t)a.nc_cap) return 5;                               // uniform
-  if (total_seg > (uint32_t)(NT * CR)) return kNeedLong;                      // uniform
+  if (total_seg > (uint32_t)(NT * CR)) return kNeedLongList;                  // uniform
 
   SIP_MARK(2);
   // ---- (2) The two dependent global reads of this kernel -- the candidate segments and the raw
@@ -951,9 +952,12 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   }
   SIP_MARK(10);
 #ifdef SIP_TIMING
-  if (blockIdx.x == 0 && tid == 0) {
+#ifndef SIP_DBG_ROW
+#define SIP_DBG_ROW 0
+#endif
+  if (blockIdx.x == SIP_DBG_ROW && tid == 0) {
     long long* dbg = reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1));
-    dbg[24] = fs.n_top; dbg[25] = fs.n_memb; dbg[26] = fs.n_memb2; dbg[27] = fs.n_memb3; dbg[28] = total_seg; dbg[31] = ndist;
+    dbg[24] = fs.n_top; dbg[25] = fs.n_memb; dbg[26] = fs.n_memb2; dbg[27] = fs.n_memb3; dbg[28] = total_seg; dbg[31] = ndist; dbg[29] = CR; dbg[30] = SR;
   }
 #endif
   return 1;
@@ -1049,8 +1053,8 @@ __device__ __forceinline__ int fast_any(const Args& a, const int b, const RowPar
   int r = kNeedLong;
   if (hist_len <= 2 * NT) r = fast_row<DT, 8, 2>(a, b, rp, dyn, fs, S, cap_w);
   if (r == kNeedLong) r = fast_row<DT, 8, 8>(a, b, rp, dyn, fs, S, cap_w);
-  if (r == kNeedLong) r = fast_row<DT, kCandLong, 8>(a, b, rp, dyn, fs, S, cap_w);
-  return r == kNeedLong ? 5 : r;
+  if (r == kNeedLong || r == kNeedLongList) r = fast_row<DT, kCandLong, 8>(a, b, rp, dyn, fs, S, cap_w);
+  return (r == kNeedLong || r == kNeedLongList) ? 5 : r;
 }
 
 template <int DT>
