@@ -1092,11 +1092,11 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
       how = r;
       if (r != 8 && r != 11 && r != 12) break;
       // The list was complete but too short.  Where min-p is on, the threshold that bounds the
-      // kept set is known exactly now that the maximum is; otherwise lower the threshold by a
-      // quarter of its distance to the maximum.  One retry, then the exact path.
+      // kept set is known exactly now that the maximum is; otherwise lower the threshold by
+      // three tenths of its distance to the maximum.  One retry, then the exact path.
       __syncthreads();
       const float m = fs.m_out, zmax = fs.zmax_out, t_old = fs.trow_out;
-      float t_new = t_old - 0.25f * (zmax - t_old);
+      float t_new = t_old - 0.3f * (zmax - t_old);
       if (rp.min_p > 0.0f && !rp.greedy) {
         const float zt = (m + (float)log((double)rp.min_p)) * rp.tau;
         t_new = fminf(t_new, zt - 1.0e-5f * fabsf(zt) - 1.0e-30f);

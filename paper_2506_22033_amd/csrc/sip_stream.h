@@ -66,20 +66,22 @@ __device__ __forceinline__ int candidate_target(const RowParams& r, const Args& 
                                                       // and best-n, the draw re-reads the row
   int t;
   if (k > 0) {
-    // top-k needs its k largest in the list, plus head-room for the sampling noise of the
-    // threshold; whatever top-p and min-p do afterwards happens inside those k
-    t = k + (k >> 2) + 512;
+    // top-k needs its k largest in the list.  The threshold is the j-th largest of kSampleSize
+    // sampled values, j = t * kSampleSize / V, so the list comes out t * (1 +- 1/sqrt(j)): ask
+    // for 3.5 such deviations more than k (whatever top-p and min-p do afterwards happens
+    // inside those k)
+    t = k + 256 + (int)(3.5f * sqrtf((float)k * (float)a.V * (1.0f / (float)kSampleSize)));
   } else {
     // a nucleus with nothing else to bound it tends to be longer than one cut by min-p, so it
-    // starts from a longer list -- as long as still fits, after the threshold's rounding, the 8
-    // entries per thread of the finishing kernel's faster variant
-    t = minp_on ? 1536 : 2560;
+    // starts from a longer list -- as long as still fits the 8 entries per thread of the
+    // finishing kernel's faster variants
+    t = minp_on ? 1920 : 2816;
     // min-p keeps what lies within tau * ln(1/min_p) of the maximum: the list must reach that
     // far down, and how many elements that is grows quickly with the temperature
-    if (minp_on && r.min_p < 1.0f) t = max(t, 1024 + (int)(341.0f * r.tau * -__logf(r.min_p)));
+    if (minp_on && r.min_p < 1.0f) t = max(t, 1280 + (int)(400.0f * r.tau * -__logf(r.min_p)));
   }
-  // the 13-bit threshold rounds down: up to ~1.3x more entries than asked for
-  if (t + (t >> 2) + (t >> 3) > a.nc_cap) return 0;
+  // the threshold comes from a sample: allow for a list a quarter longer than asked for
+  if (t + (t >> 2) > a.nc_cap) return 0;
   return t;
 }
 
@@ -138,7 +140,8 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   __shared__ uint32_t red32[kStreamWaves];
   __shared__ unsigned long long red64[kStreamWaves];
   __shared__ uint32_t wave_cnt[kStreamWaves];
-  __shared__ uint32_t key_thr;
+  __shared__ uint32_t key_thr, need_thr;            // 13-bit key of the threshold bin; entries still wanted from inside it
+  __shared__ uint32_t sub_hist[32];                 // that bin, split by the next 5 key bits
 
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
 #ifdef SIP_TIMING
@@ -197,7 +200,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
 
   // ---- threshold: the same 4096-element sample (1 KB blocks spread evenly over the row) is
   // read by every chunk of the row, so all chunks agree on Tc = the j-th largest sample value
-  // rounded down to a 13-bit key, j / 4096 = target / V
+  // rounded down to an 18-bit key (found in two levels: 13 bits, then 5 more), j / 4096 = target / V
   uint4 smp[SLOADS];
 #pragma unroll
   for (int j = 0; j < SLOADS; ++j) {
@@ -206,39 +209,41 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     smp[j] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);      // e0 + EPL <= V since V >= 16384
   }
   for (int i = tid; i < kSampleBins / 2; i += kStreamThreads) hist[i] = 0;
+  if (tid < 32) sub_hist[tid] = 0;
   __syncthreads();
   SIP_SMARK(1);
   long long want = ((long long)target * kSampleSize + V - 1) / V;
   if (want < 2) want = 2;
   if (want > kSampleSize) want = kSampleSize;
   const uint32_t j = (uint32_t)want;
+  // Only the upper tail of the sample matters.  When j is small, a thread enters just the
+  // three largest of its keys: far fewer LDS atomics, and hardly any on the same word.
+  // (Should one thread hold more than three of the j largest, the threshold comes out a
+  // little low, which only lengthens the candidate list.)
+  const bool tail_only = j <= 128;                   // workgroup-uniform
+  uint32_t t0 = 0, t1 = 0, t2 = 0;                   // full keys of this thread's three largest sample values
   {
-    // Only the upper tail of the sample matters.  When j is small, a thread enters just the
-    // three largest of its 16 keys: far fewer LDS atomics, and hardly any on the same word.
-    // (Should one thread hold more than three of the j largest, the threshold comes out a
-    // little low, which only lengthens the candidate list.)
-    const bool tail_only = j <= 128;                 // workgroup-uniform
-    uint32_t t0 = 0, t1 = 0, t2 = 0;
 #pragma unroll
     for (int l = 0; l < SLOADS; ++l) {
       float z[EPL];
       unpack(smp[l], z);
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
-        const uint32_t k13 = key_of(z[i]) >> 19;
+        const uint32_t kf = key_of(z[i]);
         if (tail_only) {
-          const uint32_t a1 = min(t0, k13); t0 = max(t0, k13);
+          const uint32_t a1 = min(t0, kf); t0 = max(t0, kf);
           const uint32_t a2 = min(t1, a1); t1 = max(t1, a1);
           t2 = max(t2, a2);
         } else {
+          const uint32_t k13 = kf >> 19;
           atomicAdd(&hist[k13 >> 1], (k13 & 1u) ? 0x10000u : 1u);
         }
       }
     }
     if (tail_only) {
-      atomicAdd(&hist[t0 >> 1], (t0 & 1u) ? 0x10000u : 1u);
-      atomicAdd(&hist[t1 >> 1], (t1 & 1u) ? 0x10000u : 1u);
-      atomicAdd(&hist[t2 >> 1], (t2 & 1u) ? 0x10000u : 1u);
+      atomicAdd(&hist[t0 >> 20], ((t0 >> 19) & 1u) ? 0x10000u : 1u);
+      atomicAdd(&hist[t1 >> 20], ((t1 >> 19) & 1u) ? 0x10000u : 1u);
+      atomicAdd(&hist[t2 >> 20], ((t2 >> 19) & 1u) ? 0x10000u : 1u);
     }
   }
   __syncthreads();
@@ -255,20 +260,49 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     for (int w = 0; w < wave; ++w) off += red32[w];
     const uint32_t incl = off + incl_w, excl = incl - local;
     if (excl < j && j <= incl) {
-      uint32_t run = excl, found = 0;
+      uint32_t run = excl, found = 0, need = 1;      // run: sample values above the bin looked at
       for (int i = 1; i <= WPT; ++i) {
         const uint32_t w = hist[wtop - i];
+        if (run + (w >> 16) >= j) { found = 2u * (uint32_t)(wtop - i) + 1u; need = j - run; break; }
         run += (w >> 16);
-        if (run >= j) { found = 2u * (uint32_t)(wtop - i) + 1u; break; }
+        if (run + (w & 0xFFFFu) >= j) { found = 2u * (uint32_t)(wtop - i); need = j - run; break; }
         run += (w & 0xFFFFu);
-        if (run >= j) { found = 2u * (uint32_t)(wtop - i); break; }
       }
-      key_thr = found;
+      key_thr = found; need_thr = need;
     }
     __syncthreads();                                 // also: the histogram is dead from here on
   }
+  // ---- second level: the threshold bin is as wide as 1/16 of its values (and bf16 logits
+  // or a spike-and-bulk row put hundreds of sample values into it), so it is split by the
+  // next 5 key bits and only as many of its sub-bins are taken as the target asks for
+  {
+    const uint32_t K = key_thr;
+    auto enter = [&](uint32_t kf) {
+      if ((kf >> 19) == K) atomicAdd(&sub_hist[(kf >> 14) & 31u], 1u);
+    };
+    if (tail_only) {
+      enter(t0); enter(t1); enter(t2);
+    } else {
+#pragma unroll
+      for (int l = 0; l < SLOADS; ++l) {
+        float z[EPL];
+        unpack(smp[l], z);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) enter(key_of(z[i]));
+      }
+    }
+    __syncthreads();
+    if (wave == 0) {
+      const uint32_t c = lane < 32 ? sub_hist[31 - min(lane, 31)] : 0u;       // lane l: sub-bin 31 - l, descending
+      const uint32_t incl = dpp_scan_add_u32(c);
+      const unsigned long long reach = __ballot(lane < 32 && incl >= need_thr);
+      const uint32_t first = reach ? (uint32_t)__ffsll((long long)reach) - 1u : 31u;
+      if (lane == 0) key_thr = (K << 5) | (31u - first);                       // 18-bit key from here on
+    }
+    __syncthreads();
+  }
   SIP_SMARK(2);
-  const uint32_t kb = key_thr << 19;
+  const uint32_t kb = key_thr << 14;
   const float Tc = value_of(kb);
   const BulkRef ref = make_bulk_ref(Tc, rp);
   const int R = ref.R;
