@@ -39,6 +39,8 @@ constexpr int kWordRegs = 16;        // bitmap words a thread owns (2^18 / 32 / 
 constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
 constexpr int kNeedLong = 30;        // internal: more history tokens than this variant holds per thread
 constexpr int kNeedLongList = 31;    // internal: more candidates than this variant holds per thread
+constexpr int kWholeRowCut = 32;     // internal: the nucleus cut lies below the list -- settle it, and draw, over the whole row
+constexpr int kWholeRow = 33;        // internal: no filter at all -- draw over the whole row
 constexpr int kCandLong = 24;        // candidate entries per thread of the largest variant
 
 struct FastShared {
@@ -55,6 +57,9 @@ struct FastShared {
   uint32_t ridx[kFinalWaves];
   uint32_t fail_seg, anyc, dropped;
   float m_out, zmax_out, trow_out;      // for a second attempt: max of s, max of z', threshold used
+  unsigned long long limit_out;         // for the whole-row continuation: top-p limit, ln Z, whether penalties apply
+  double lnz_out;
+  int has_pen_out;
   uint32_t rq_n;                         // candidates found by the second pass
   int bin_k, bin_n, bin_p, bin_low, bin_d;
   uint32_t above_k, above_n;
@@ -702,7 +707,12 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       }
       __syncthreads();
       const bool inside = k_act || bin_p > fs.bin_low || fs.dropped != 0;
-      if (!inside && !minp_bounds) return 11;                                 // uniform: the cut may lie below the list
+      if (!inside && !minp_bounds) {
+        // uniform: the cut may lie below the list; it is settled, and the token drawn, over the
+        // whole row by the caller (out of this function: code that is rarely needed slows it down)
+        if (tid == 0) { fs.limit_out = limit; fs.lnz_out = lnZ; fs.has_pen_out = has_pen; }
+        return kWholeRowCut;
+      }
       key_cut = max(key_k, fs.key_p);
     } else if (!k_act && !minp_bounds) {
       if (minp_on) return 12;                                                 // uniform: min-p reaches below the list
@@ -711,144 +721,8 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
 
     SIP_MARK(8);
     if (whole_row) {
-      // ---- (8') draw over the whole row (plain temperature sampling).  Maximum, total mass
-      // and best-n came from the list; the draw itself needs every element's mass in
-      // vocabulary order, so the row is read once more here (it is still in the last-level
-      // cache), plus the one block in which the running mass crosses the target.
-      constexpr int EPL = (DT == SIP_F32) ? 4 : 8;
-      constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
-      const float zmax = value_of(bkey);
-      const int e_last = ((V - 1) / EPL) * EPL;
-      auto ldrow = [&](int e0) {                            // clamped: always a valid address
-        return *reinterpret_cast<const uint4*>(row + (size_t)min(e0, e_last) * ESZ);
-      };
-      auto masses = [&](const uint4& q, int e0, unsigned long long (&E)[EPL], uint32_t (&keys)[EPL]) {
-        float z[EPL];
-        if (DT == SIP_F32) {
-          z[0] = __uint_as_float(q.x); z[1] = __uint_as_float(q.y);
-          z[2] = __uint_as_float(q.z); z[3] = __uint_as_float(q.w);
-        } else {
-          const uint32_t w4[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            z[2 * i] = __uint_as_float(w4[i] << 16);
-            z[2 * i + 1] = __uint_as_float(w4[i] & 0xFFFF0000u);
-          }
-        }
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) {
-          const int v = e0 + i;
-          E[i] = 0; keys[i] = 0;
-          if (v < V) {
-            const uint32_t word = has_pen ? bm[v >> 5] : 0u;
-            if ((word >> (v & 31)) & 1u) {                                     // carries a penalty: value from the list
-              const float sv = value_of(cnt[pre[v >> 5] + __popc(word & ((1u << (v & 31)) - 1u))]);
-              keys[i] = key_of(sv);
-              E[i] = mass(sv);
-            } else {
-              // exp(z/tau - max) as 2^((z - zmax) * c): no division, hardware exp2; the two passes
-              // below use the same expression, which is all the draw needs
-              keys[i] = __float_as_uint(z[i]);                                 // raw bits, turned into a key on a hit
-              E[i] = fix_of(__builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(z[i], zmax), c_row)));
-            }
-          }
-        }
-      };
-      // first read: mass of every block of BLK consecutive elements (one block = UNR loads per
-      // lane of one wave) into hd[] (still all zero); waves take contiguous runs of blocks
-      constexpr int UNR = 4;
-      constexpr int BLK = UNR * kWave * EPL;
-      const int nblk = (V + BLK - 1) / BLK;                 // <= kBins because V <= 262144
-      const int per_wave = (nblk + kFinalWaves - 1) / kFinalWaves;
-      for (int blk = wave * per_wave; blk < min(nblk, (wave + 1) * per_wave); ++blk) {
-        const int base = blk * BLK;
-        uint4 q[UNR];
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) q[u] = ldrow(base + (u * kWave + lane) * EPL);
-        unsigned long long mine = 0;
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-          unsigned long long E[EPL];
-          uint32_t keys[EPL];
-          masses(q[u], base + (u * kWave + lane) * EPL, E, keys);        // zero past the end of the row
-#pragma unroll
-          for (int i = 0; i < EPL; ++i) mine += E[i];
-        }
-        mine = dpp_scan_add_u64(mine);
-        if (lane == kWave - 1) hd[blk] = mine;
-      }
-      __syncthreads();
-      // prefix over the blocks, find the block that holds the crossing
-      unsigned long long target;
-      {
-        const int b0 = kBinsPerThread * tid;
-        unsigned long long w[kBinsPerThread], msum = 0;
-#pragma unroll
-        for (int j = 0; j < kBinsPerThread; ++j) { w[j] = hd[b0 + j]; msum += w[j]; }
-        const unsigned long long minc = dpp_scan_add_u64(msum);
-        if (lane == kWave - 1) fs.r64[wave] = minc;
-        __syncthreads();
-        unsigned long long ex = minc - msum, S3 = 0;
-#pragma unroll
-        for (int ww = 0; ww < kFinalWaves; ++ww) {
-          if (ww < wave) ex += fs.r64[ww];
-          S3 += fs.r64[ww];
-        }
-        target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);           // floor(j * S3 / 2^24)
-#pragma unroll
-        for (int j = 0; j < kBinsPerThread; ++j) {
-          if (ex <= target && target < ex + w[j]) { fs.bin_d = b0 + j; fs.before_d = ex; }
-          ex += w[j];
-        }
-      }
-      __syncthreads();
-      const int blk_d = fs.bin_d;
-      if (blk_d < 0) return 13;                                               // uniform (no mass at all)
-      // second read, one block, one wave: lane prefixes in vocabulary order
-      if (wave == 0) {
-        const int base = blk_d * BLK;
-        unsigned long long running = fs.before_d;
-        int found = -1;
-        uint32_t found_key = 0;
-        uint4 q[UNR];
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) q[u] = ldrow(base + (u * kWave + lane) * EPL);
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-          const int e0 = base + (u * kWave + lane) * EPL;
-          unsigned long long E[EPL];
-          uint32_t keys[EPL];
-          masses(q[u], e0, E, keys);
-          unsigned long long lane_tot = 0;
-#pragma unroll
-          for (int i = 0; i < EPL; ++i) lane_tot += E[i];
-          const unsigned long long incl = dpp_scan_add_u64(lane_tot);
-          unsigned long long c = running + incl - lane_tot;
-          int hit = -1;
-          uint32_t hit_key = 0;
-#pragma unroll
-          for (int i = 0; i < EPL; ++i) {
-            c += E[i];
-            if (hit < 0 && c > target) { hit = e0 + i; hit_key = keys[i]; }   // key, or raw bits if unpenalised
-          }
-          const unsigned long long ball = __ballot(hit >= 0);
-          if (ball && found < 0) {
-            const int src = __ffsll((long long)ball) - 1;
-            found = __builtin_amdgcn_readlane(hit, src);
-            found_key = (uint32_t)__builtin_amdgcn_readlane((int)hit_key, src);
-          }
-          running += last_lane_u64(incl);
-        }
-        if (lane == 0) {
-          if (found >= 0 && !(has_pen && ((bm[found >> 5] >> (found & 31)) & 1u)))
-            found_key = key_of(scaled_s(__uint_as_float(found_key)));
-          fs.token = found; fs.token_key = found_key;
-        }
-      }
-      __syncthreads();
-      token = fs.token;
-      if (token == 0x7FFFFFFF || token < 0) return 13;                        // uniform
-      token_key = fs.token_key;
+      if (tid == 0) { fs.limit_out = 0; fs.lnz_out = lnZ; fs.has_pen_out = has_pen; }
+      return kWholeRow;                                                       // uniform: finished by the caller
     } else {
       // ---- (8) draw: kept mass per index bin, prefix, then resolve inside the crossing bin
       auto kept = [&](uint32_t k) {
@@ -968,7 +842,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
 // the result where the first attempt's data was: one segment of S*4*cap_w entries and one
 // chunk summary.  Same arithmetic as stream_kernel.
 template <int DT>
-__device__ __attribute__((noinline)) void restream_row(const Args& a, const int b, const RowParams& rp, const float Tc,
+__device__ __attribute__((noinline)) void restream_row(const Args& a, const int b, const RowParams rp, const float Tc,
                                                        FastShared& fs) {
   constexpr int NT = kFinalThreads;
   constexpr int EPL = (DT == SIP_F32) ? 4 : 8;
@@ -1042,6 +916,11 @@ __device__ __attribute__((noinline)) void restream_row(const Args& a, const int 
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 
+// Rarely needed continuations, defined after the kernel (see there).
+template <int DT>
+__device__ int whole_row_finish(const Args& a, const int b, const RowParams rp, unsigned char* dyn, FastShared& fs,
+                                const bool cut);
+
 // Runs the smallest instantiation of fast_row that can hold the row: the history length bounds
 // the number of distinct tokens; a variant that turns out too small says so early and the next
 // one starts over.  Three variants, one after the other: every further instantiation in this
@@ -1085,8 +964,9 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
     for (int attempt = 0; attempt < 2; ++attempt) {
       const int r = fast_any<DT>(a, b, rp, dynraw, fs, S, cap_w, hist_len);
       if (attempt == 1) {
-        how = r == 1 ? 1 : 16 + r;               // 17..29: failed again after the retry
-        if (r == 1) code = 15;                   // 15: finished by the retry (still one HBM pass)
+        const bool fine = r == 1 || r == kWholeRowCut || r == kWholeRow;
+        how = fine ? r : 16 + r;                 // 17..29: failed again after the retry
+        if (fine) code = 15;                     // 15: finished by the retry (still one HBM pass)
         break;
       }
       how = r;
@@ -1107,6 +987,16 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
       S = 1; cap_w = a.S * kStreamWaves * a.cap_w;
     }
   }
+  if (how == kWholeRowCut || how == kWholeRow) {
+    // rows that are finished over the whole row: nucleus cut below the list, or no filter at all
+    how = whole_row_finish<DT>(a, b, rp, dynraw, fs, how == kWholeRowCut);
+    if (how != 1) code = 0;
+  }
+  if (how == kWholeRowCut || how == kWholeRow) {
+    // rows that are finished over the whole row: nucleus cut below the list, or no filter at all
+    how = whole_row_finish<DT>(a, b, rp, dynraw, fs, how == kWholeRowCut);
+    if (how != 1) code = 0;
+  }
   if (how != 1) {
     __syncthreads();
     exact_row<DT>(a, b, reinterpret_cast<uint32_t*>(dynraw), ex);
@@ -1117,6 +1007,367 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
 #else
   if (threadIdx.x == 0) a.row_path[b] = code ? code : how;
 #endif
+}
+
+// Draw over the whole row: for a row without any filter (plain temperature sampling), or, with
+// `key_cut` / min-p, for a row whose kept set reaches below the candidate list.  Maximum,
+// total mass and best-n came from the list; the draw itself needs every element's mass in
+// vocabulary order, so the row is read once more here (it is still in the last-level cache),
+// plus the one block in which the running mass crosses the target.  Out of line: rarely needed,
+// and the finishing kernel gets slower with every piece of code inlined into it.  Leaves the
+// token and its key in fs; returns 1, or 13 if there is no mass to draw from.
+template <int DT>
+__device__ __attribute__((noinline)) int whole_row_draw(const char* row, const int V, const bool has_pen,
+                                                        const uint32_t* bm, const unsigned short* pre,
+                                                        const uint32_t* cnt, unsigned long long* hd, FastShared& fs,
+                                                        const float tau, const bool greedy, const float m,
+                                                        const float zmax, const float c_row,
+                                                        const unsigned long long j24, const uint32_t key_cut,
+                                                        const bool minp_on, const float t_minp) {
+  const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+  const bool filtered = key_cut != 0 || minp_on;        // uniform: only part of the row is kept
+  auto scaled_s = [&](float z) { return greedy ? z : __fdiv_rn(z, tau); };
+  auto mass = [&](float s) { return fix_of(expf(__fsub_rn(s, m))); };
+  constexpr int EPL = (DT == SIP_F32) ? 4 : 8;
+  constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
+  const int e_last = ((V - 1) / EPL) * EPL;
+  auto ldrow = [&](int e0) {                            // clamped: always a valid address
+    return *reinterpret_cast<const uint4*>(row + (size_t)min(e0, e_last) * ESZ);
+  };
+  auto masses = [&](const uint4& q, int e0, unsigned long long (&E)[EPL], uint32_t (&keys)[EPL]) {
+    float z[EPL];
+    if (DT == SIP_F32) {
+      z[0] = __uint_as_float(q.x); z[1] = __uint_as_float(q.y);
+      z[2] = __uint_as_float(q.z); z[3] = __uint_as_float(q.w);
+    } else {
+      const uint32_t w4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        z[2 * i] = __uint_as_float(w4[i] << 16);
+        z[2 * i + 1] = __uint_as_float(w4[i] & 0xFFFF0000u);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      const int v = e0 + i;
+      E[i] = 0; keys[i] = 0;
+      if (v < V) {
+        const uint32_t word = has_pen ? bm[v >> 5] : 0u;
+        if ((word >> (v & 31)) & 1u) {                                     // carries a penalty: value from the list
+          const float sv = value_of(cnt[pre[v >> 5] + __popc(word & ((1u << (v & 31)) - 1u))]);
+          keys[i] = key_of(sv);
+          E[i] = mass(sv);
+          if (filtered && !(keys[i] >= key_cut && (!minp_on || __fsub_rn(sv, m) >= t_minp))) E[i] = 0;
+        } else if (filtered) {
+          // a cut by value: the exact s decides who is kept; the mass is exp(s - max) with the
+          // hardware exp2, the same expression in both passes below
+          const float sv = scaled_s(z[i]);
+          keys[i] = key_of(sv);
+          const bool keep = keys[i] >= key_cut && (!minp_on || __fsub_rn(sv, m) >= t_minp);
+          E[i] = keep ? fix_of(__builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(sv, m), 1.44269504f))) : 0ull;
+        } else {
+          // exp(z/tau - max) as 2^((z - zmax) * c): no division, hardware exp2; the two passes
+          // below use the same expression, which is all the draw needs
+          keys[i] = __float_as_uint(z[i]);                                 // raw bits, turned into a key on a hit
+          E[i] = fix_of(__builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(z[i], zmax), c_row)));
+        }
+      }
+    }
+  };
+  // first read: mass of every block of BLK consecutive elements (one block = UNR loads per
+  // lane of one wave) into hd[] (still all zero); waves take contiguous runs of blocks
+  constexpr int UNR = 4;
+  constexpr int BLK = UNR * kWave * EPL;
+  const int nblk = (V + BLK - 1) / BLK;                 // <= kBins because V <= 262144
+  const int per_wave = (nblk + kFinalWaves - 1) / kFinalWaves;
+  for (int blk = wave * per_wave; blk < min(nblk, (wave + 1) * per_wave); ++blk) {
+    const int base = blk * BLK;
+    uint4 q[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) q[u] = ldrow(base + (u * kWave + lane) * EPL);
+    unsigned long long mine = 0;
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      unsigned long long E[EPL];
+      uint32_t keys[EPL];
+      masses(q[u], base + (u * kWave + lane) * EPL, E, keys);        // zero past the end of the row
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) mine += E[i];
+    }
+    mine = dpp_scan_add_u64(mine);
+    if (lane == kWave - 1) hd[blk] = mine;
+  }
+  __syncthreads();
+  // prefix over the blocks, find the block that holds the crossing
+  unsigned long long target;
+  {
+    const int b0 = kBinsPerThread * tid;
+    unsigned long long w[kBinsPerThread], msum = 0;
+#pragma unroll
+    for (int j = 0; j < kBinsPerThread; ++j) { w[j] = hd[b0 + j]; msum += w[j]; }
+    const unsigned long long minc = dpp_scan_add_u64(msum);
+    if (lane == kWave - 1) fs.r64[wave] = minc;
+    __syncthreads();
+    unsigned long long ex = minc - msum, S3 = 0;
+#pragma unroll
+    for (int ww = 0; ww < kFinalWaves; ++ww) {
+      if (ww < wave) ex += fs.r64[ww];
+      S3 += fs.r64[ww];
+    }
+    target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);           // floor(j * S3 / 2^24)
+#pragma unroll
+    for (int j = 0; j < kBinsPerThread; ++j) {
+      if (ex <= target && target < ex + w[j]) { fs.bin_d = b0 + j; fs.before_d = ex; }
+      ex += w[j];
+    }
+  }
+  __syncthreads();
+  const int blk_d = fs.bin_d;
+  if (blk_d < 0) return 13;                                               // uniform (no mass at all)
+  // second read, one block, one wave: lane prefixes in vocabulary order
+  if (wave == 0) {
+    const int base = blk_d * BLK;
+    unsigned long long running = fs.before_d;
+    int found = -1;
+    uint32_t found_key = 0;
+    uint4 q[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) q[u] = ldrow(base + (u * kWave + lane) * EPL);
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int e0 = base + (u * kWave + lane) * EPL;
+      unsigned long long E[EPL];
+      uint32_t keys[EPL];
+      masses(q[u], e0, E, keys);
+      unsigned long long lane_tot = 0;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) lane_tot += E[i];
+      const unsigned long long incl = dpp_scan_add_u64(lane_tot);
+      unsigned long long c = running + incl - lane_tot;
+      int hit = -1;
+      uint32_t hit_key = 0;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        c += E[i];
+        if (hit < 0 && c > target) { hit = e0 + i; hit_key = keys[i]; }   // key, or raw bits if unpenalised
+      }
+      const unsigned long long ball = __ballot(hit >= 0);
+      if (ball && found < 0) {
+        const int src = __ffsll((long long)ball) - 1;
+        found = __builtin_amdgcn_readlane(hit, src);
+        found_key = (uint32_t)__builtin_amdgcn_readlane((int)hit_key, src);
+      }
+      running += last_lane_u64(incl);
+    }
+    if (lane == 0) {
+      if (!filtered && found >= 0 && !(has_pen && ((bm[found >> 5] >> (found & 31)) & 1u)))
+        found_key = key_of(scaled_s(__uint_as_float(found_key)));
+      fs.token = found; fs.token_key = found_key;
+    }
+  }
+  __syncthreads();
+  const int token = fs.token;
+  return (token == 0x7FFFFFFF || token < 0) ? 13 : 1;
+}
+
+// Nucleus cut of a row whose cut lies below the candidate list (top-p alone on a flat
+// distribution keeps tens of thousands of tokens): a radix descent over the whole row on the
+// exact fp32 s.  Each level is one read of the row (it is in the last-level cache): count
+// and integer mass per bin, 2048 bins over the current interval of s, monotone in s so that
+// equal values never part; the bin in which the mass of everything larger first stays short
+// of the limit becomes the next interval.  Once that bin holds at most kMembers elements
+// they are gathered and resolved by all-pairs comparison as in the list path.  Leaves the key
+// of the smallest kept value in fs.key_p and returns 1, or returns 11 (more than kMembers equal
+// values at the cut, no mass): the caller then takes the row to the exact path.
+template <int DT>
+__device__ __attribute__((noinline)) int whole_row_cut(const char* row, const int V, const bool has_pen,
+                                                       const uint32_t* bm, const unsigned short* pre,
+                                                       const uint32_t* cnt, unsigned long long* hm, uint32_t* hc,
+                                                       FastShared& fs, const float tau, const float m,
+                                                       const unsigned long long limit) {
+  const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+  constexpr int NT = kFinalThreads;
+  constexpr int EPL = (DT == SIP_F32) ? 4 : 8;
+  constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
+  constexpr int kLevels = 3;
+  constexpr float kSpan = 28.0f;                          // exp(-28) * 2^40 < 1: nothing below has mass
+  // s of every element of one 16-byte load (penalised elements take theirs from the slot table)
+  auto svals = [&](int e0, float (&sv)[EPL]) {
+    const int e_last = ((V - 1) / EPL) * EPL;
+    const uint4 q = *reinterpret_cast<const uint4*>(row + (size_t)min(e0, e_last) * ESZ);
+    float z[EPL];
+    if (DT == SIP_F32) {
+      z[0] = __uint_as_float(q.x); z[1] = __uint_as_float(q.y);
+      z[2] = __uint_as_float(q.z); z[3] = __uint_as_float(q.w);
+    } else {
+      const uint32_t w4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        z[2 * i] = __uint_as_float(w4[i] << 16);
+        z[2 * i + 1] = __uint_as_float(w4[i] & 0xFFFF0000u);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      const int v = min(e0 + i, V - 1);
+      const uint32_t word = has_pen ? bm[v >> 5] : 0u;
+      sv[i] = ((word >> (v & 31)) & 1u) ? value_of(cnt[pre[v >> 5] + __popc(word & ((1u << (v & 31)) - 1u))])
+                                        : __fdiv_rn(z[i], tau);
+    }
+  };
+  auto mass = [&](float sv) { return fix_of(__builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(sv, m), 1.44269504f))); };
+  float lo[kLevels], sc[kLevels];
+  int pick[kLevels];
+  auto bin_at = [&](int l, float sv) { return min(kBins - 1, max(0, (int)(__fsub_rn(sv, lo[l]) * sc[l]))); };
+  float cur_lo = m - kSpan, cur_w = kSpan;
+  unsigned long long above = 0;                           // mass of everything larger than the current interval
+  uint32_t n_in = 0;
+  int levels = 0;
+#pragma unroll
+  for (int level = 0; level < kLevels; ++level) {
+    const float cur_sc = (float)kBins / cur_w;
+    lo[level] = cur_lo; sc[level] = cur_sc; pick[level] = 0;
+    __syncthreads();
+    for (int i = tid; i < kBins; i += NT) { hm[i] = 0; hc[i] = 0; }
+    if (tid == 0) fs.bin_p = 1 << 30;
+    __syncthreads();
+    for (int e0 = tid * EPL; e0 < V; e0 += NT * EPL) {
+      float sv[EPL];
+      svals(e0, sv);
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        bool in = e0 + i < V && sv[i] == sv[i];
+#pragma unroll
+        for (int l = 0; l < kLevels; ++l)
+          if (l < level) in = in && bin_at(l, sv[i]) == pick[l];
+        if (in) {
+          const int bin = min(kBins - 1, max(0, (int)(__fsub_rn(sv[i], cur_lo) * cur_sc)));
+          atomicAdd(&hc[bin], 1u);
+          const unsigned long long E = mass(sv[i]);
+          if (E) atomicAdd(&hm[bin], E);
+        }
+      }
+    }
+    __syncthreads();
+    {
+      // thread t owns bins kBins-1-4t .. kBins-4-4t; exclusive suffix mass in descending bin order
+      const int b0 = kBins - 1 - kBinsPerThread * tid;
+      uint32_t c[kBinsPerThread];
+      unsigned long long w[kBinsPerThread], msum = 0;
+#pragma unroll
+      for (int j = 0; j < kBinsPerThread; ++j) { c[j] = hc[b0 - j]; w[j] = hm[b0 - j]; msum += w[j]; }
+      const unsigned long long minc = dpp_scan_add_u64(msum);
+      if (lane == kWave - 1) fs.r64[wave] = minc;
+      __syncthreads();
+      unsigned long long mex = above + minc - msum;
+#pragma unroll
+      for (int ww = 0; ww < kFinalWaves; ++ww)
+        if (ww < wave) mex += fs.r64[ww];
+      int mine = 1 << 30;
+      unsigned long long mex_j[kBinsPerThread];
+#pragma unroll
+      for (int j = 0; j < kBinsPerThread; ++j) {
+        mex_j[j] = mex;
+        if (c[j] && mex < limit) mine = b0 - j;           // bins descend: the last one wins
+        mex += w[j];
+      }
+      const uint32_t wmin = last_lane_u32(dpp_scan_min_u32((uint32_t)mine));
+      if (lane == kWave - 1 && wmin < (1u << 30)) atomicMin(&fs.bin_p, (int)wmin);
+      __syncthreads();
+      const int bp = fs.bin_p;
+#pragma unroll
+      for (int j = 0; j < kBinsPerThread; ++j)
+        if (b0 - j == bp) { fs.before_d = mex_j[j]; fs.n_memb3 = c[j]; }
+    }
+    __syncthreads();
+    const int bp = fs.bin_p;
+    if (bp >= kBins) return 11;                           // uniform: nothing qualifies (limit of 0)
+    pick[level] = bp; above = fs.before_d; n_in = fs.n_memb3;
+    levels = level + 1;
+    if (n_in <= (uint32_t)kMembers) break;                // uniform
+    cur_w = cur_w * (1.0f / (float)kBins);
+    cur_lo = lo[level] + (float)bp * cur_w;
+  }
+  if (n_in > (uint32_t)kMembers) return 11;               // uniform
+  // gather the elements of the last bin and resolve them
+  __syncthreads();
+  if (tid == 0) { fs.n_memb2 = 0; fs.key_p = 0xFFFFFFFFu; }
+  __syncthreads();
+  for (int e0 = tid * EPL; e0 < V; e0 += NT * EPL) {
+    float sv[EPL];
+    svals(e0, sv);
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      bool in = e0 + i < V && sv[i] == sv[i];
+#pragma unroll
+      for (int l = 0; l < kLevels; ++l)
+        if (l < levels) in = in && bin_at(l, sv[i]) == pick[l];
+      if (in) {
+        const uint32_t q = atomicAdd(&fs.n_memb2, 1u);
+        if (q < (uint32_t)kMembers) { fs.m_key[q] = key_of(sv[i]); fs.m_E[q] = mass(sv[i]); }
+      }
+    }
+  }
+  __syncthreads();
+  const uint32_t nm = min(fs.n_memb2, (uint32_t)kMembers);
+  if ((uint32_t)tid < nm) {
+    const uint32_t kt = fs.m_key[tid];
+    unsigned long long G = above;
+    for (uint32_t q = 0; q < nm; ++q) {
+      const uint32_t kq = fs.m_key[q];
+      const unsigned long long Eq = fs.m_E[q];
+      G += kq > kt ? Eq : 0ull;
+    }
+    if (G < limit) atomicMin(&fs.key_p, kt);
+  }
+  __syncthreads();
+  return fs.key_p == 0xFFFFFFFFu ? 11 : 1;
+}
+
+// Continuation of fast_row for the two kinds of row that are finished over the whole row
+// (codes kWholeRowCut and kWholeRow): nucleus cut if asked for, draw, token and its logprob.
+// The best-n list is already written.  Returns 1, or a code that sends the row to the exact path.
+template <int DT>
+__device__ __attribute__((noinline)) int whole_row_finish(const Args& a, const int b, const RowParams rp,
+                                                          unsigned char* dyn, FastShared& fs, const bool cut) {
+  const int V = a.V;
+  const int W = (V + 31) >> 5;
+  const uint32_t* bm = reinterpret_cast<const uint32_t*>(dyn);
+  const unsigned short* pre = reinterpret_cast<const unsigned short*>(dyn + (size_t)W * 4);
+  unsigned char* p2 = dyn + (((size_t)W * 6 + 15) / 16) * 16;
+  unsigned long long* hm = reinterpret_cast<unsigned long long*>(p2);
+  unsigned long long* hd = hm + kBins;
+  uint32_t* hc = reinterpret_cast<uint32_t*>(hd + kBins);
+  const uint32_t* cnt = hc + kBins;
+  const char* row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * (DT == SIP_F32 ? 4 : 2);
+  __syncthreads();
+  const float m = fs.m_out, zmax = fs.zmax_out;
+  const unsigned long long limit = fs.limit_out;
+  const double lnZ = fs.lnz_out;
+  const bool has_pen = fs.has_pen_out != 0;
+  const bool minp_on = cut && rp.min_p > 0.0f;
+  const float t_minp = minp_on ? (float)log((double)rp.min_p) : 0.0f;
+  const unsigned long long j24 = (unsigned long long)(philox_word0(a.seed, rp.row_id, a.step) >> 8);
+  float c_row, c_lo;
+  scale_pair(rp, c_row, c_lo);
+  uint32_t key_cut = 0;
+  if (cut) {
+    if (whole_row_cut<DT>(row, V, has_pen, bm, pre, cnt, hm, hc, fs, rp.tau, m, limit) != 1) return 10;   // uniform
+    key_cut = fs.key_p;
+  }
+  if (whole_row_draw<DT>(row, V, has_pen, bm, pre, cnt, hd, fs, rp.tau, rp.greedy, m, zmax, c_row, j24, key_cut,
+                         minp_on, t_minp) != 1)
+    return 13;                                                                // uniform
+  if (threadIdx.x == 0) {
+    const int token = fs.token;
+    a.out_ids[b] = token;
+    if (a.k_lp >= 0) {
+      const int cols = 1 + a.k_lp;
+      a.out_lp_ids[(size_t)b * cols] = token;
+      a.out_lp[(size_t)b * cols] = (float)((double)value_of(fs.token_key) - (double)m - lnZ);
+    }
+  }
+  return 1;
 }
 
 }  // namespace sip

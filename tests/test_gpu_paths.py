@@ -60,6 +60,24 @@ def test_second_attempt_with_a_lower_threshold():
     assert st.rows == 36                                   # ... and every row matched the oracle
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_nucleus_that_reaches_far_below_the_candidate_list(bf16):
+    """top-p alone on flat and on hot distributions keeps tens of thousands of tokens: the cut is
+    settled by a radix descent over the whole row and the token drawn there, still on the
+    single-pass path.  With and without penalties, with a min-p that does not bound the set."""
+    rng = np.random.default_rng(11)
+    V, B = 70001, 8
+    z = (rng.standard_normal((B, V)) * np.array([0.05, 0.5, 1.0, 2.0, 2.5, 2.5, 1.0, 0.3])[:, None]).astype(np.float32)
+    params = dict(temperature=[1.0, 1.0, 1.3, 1.5, 1.5, 2.0, 0.9, 1.0], top_p=[0.9, 0.5, 0.95, 0.9, 0.99, 0.8, 0.7, 0.999],
+                  min_p=[0.0, 0.0, 0.0, 0.0, 1e-6, 0.0, 1e-4, 0.0], frequency_penalty=[0.0, 0.7, 0.0, 0.4, 0.0, 0.0, 0.3, 0.0],
+                  repetition_penalty=[1.0, 1.2, 1.0, 1.0, 1.1, 1.0, 1.0, 1.0])
+    hist = [[] if b % 2 == 0 else rng.integers(0, V, 700).tolist() for b in range(B)]
+    logits = workloads.f32_to_bf16_bits(z) if bf16 else z
+    st, paths = _check(H.custom("wide_nucleus", logits, params, hist, k_logprobs=5), steps=(0, 1, 2))
+    assert st.rows == 3 * B
+    assert (paths == 1).mean() >= 0.75, paths                # bf16 ties by the hundred may still need the exact path
+
+
 def test_rows_that_must_take_the_exact_path():
     rng = np.random.default_rng(2)
     V, B = 50000, 5
