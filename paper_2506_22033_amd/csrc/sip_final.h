@@ -60,6 +60,7 @@ struct FastShared {
   unsigned long long limit_out;         // for the whole-row continuation: top-p limit, ln Z, whether penalties apply
   double lnz_out;
   int has_pen_out;
+  int retry_ok_out;                     // a second, longer list can hold the nucleus (lower bound on its length)
   uint32_t rq_n;                         // candidates found by the second pass
   int bin_k, bin_n, bin_p, bin_low, bin_d;
   uint32_t above_k, above_n;
@@ -710,7 +711,17 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       if (!inside && !minp_bounds) {
         // uniform: the cut may lie below the list; it is settled, and the token drawn, over the
         // whole row by the caller (out of this function: code that is rarely needed slows it down)
-        if (tid == 0) { fs.limit_out = limit; fs.lnz_out = lnZ; fs.has_pen_out = has_pen; }
+        if (tid == 0) {
+          fs.limit_out = limit; fs.lnz_out = lnZ; fs.has_pen_out = has_pen;
+          // Every token below the list weighs at most what the completeness threshold weighs, so
+          // the nucleus needs at least (limit - mass of the complete part of the list) / that many
+          // more: if even this bound does not fit a second list, do not try one.
+          const unsigned long long have = hm[0], e_c = mass(s_c);
+          const unsigned long long lack = limit > have ? limit - have : 0ull;
+          // (and a list that holds less than three quarters of the nucleus' mass is taken as a sign
+          // that the rest is far longer than this bound)
+          fs.retry_ok_out = e_c > 0 && lack / e_c + total_seg < 10000ull && have >= limit - (limit >> 2);
+        }
         return kWholeRowCut;
       }
       key_cut = max(key_k, fs.key_p);
@@ -962,7 +973,14 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
     int S = a.S, cap_w = a.cap_w;
 #pragma nounroll
     for (int attempt = 0; attempt < 2; ++attempt) {
-      const int r = fast_any<DT>(a, b, rp, dynraw, fs, S, cap_w, hist_len);
+      int r = fast_any<DT>(a, b, rp, dynraw, fs, S, cap_w, hist_len);
+      bool cut_below = false;
+      if (attempt == 0 && r == kWholeRowCut) {
+        // a nucleus somewhat longer than the list is cheaper to settle from a second list than
+        // over the whole row
+        __syncthreads();
+        if (fs.retry_ok_out) { r = 11; cut_below = true; }
+      }
       if (attempt == 1) {
         const bool fine = r == 1 || r == kWholeRowCut || r == kWholeRow;
         how = fine ? r : 16 + r;                 // 17..29: failed again after the retry
@@ -984,6 +1002,11 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
       }
       if (!(t_new < t_old)) break;
       restream_row<DT>(a, b, rp, t_new, fs);
+      if (cut_below && fs.rq_n > (uint32_t)(kFinalThreads * kCandLong)) {
+        // the second list does not fit either: the first attempt's tables are untouched, go on from them
+        how = kWholeRowCut;
+        break;
+      }
       S = 1; cap_w = a.S * kStreamWaves * a.cap_w;
     }
   }
