@@ -72,8 +72,10 @@ typedef struct {
  *
  * Diagnostic: after a call has completed, the first B int32 of the workspace say which
  * code path finished each row: 1 = the single-pass path (logits read once), any other value
- * = finished after re-reading the row: 15 = the single-pass logic again on a longer candidate
- * list (one extra read of that row, normally from cache), anything else = the exact
+ * = finished after reading the row again (normally from cache): 15 = the single-pass logic
+ * on a second, longer candidate list (one more read of that row); 16 = by the row's workgroup
+ * over the whole row (plain temperature sampling without any filter: two more reads; a
+ * nucleus that reaches below the candidate list: four to six); anything else = the exact
  * multi-pass path, the value naming the reason (2 top_k too large for the candidate list,
  * 3-13 the candidate list could not prove the answer, 17-29 nor could the longer one,
  * 14 vocabulary size outside the single-pass kernels).  Results mean the same either way.
@@ -84,7 +86,8 @@ size_t sip_workspace_bytes(int32_t B, int32_t V, sip_dtype dtype, int64_t hist_n
  * Sample one token per row (Sec. 2.1 step 3 (1)-(3)).
  *
  *  logits        [B, row_stride] row-major, fp32 or bf16 (SIP_BF16: raw 16-bit patterns);
- *                only the first V entries of a row are read; base pointer and
+ *                only the first V entries of a row are used (16-byte loads may touch the
+ *                rest of the row's last 16-byte group); base pointer and
  *                row_stride * sizeof(element) must be multiples of 16 bytes; never written.
  *  params        host struct, see sip_params; NULL = every feature off.
  *  hist_indptr   [B+1] CSR offsets into hist_tokens: row b's previously generated tokens

@@ -1013,12 +1013,7 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   if (how == kWholeRowCut || how == kWholeRow) {
     // rows that are finished over the whole row: nucleus cut below the list, or no filter at all
     how = whole_row_finish<DT>(a, b, rp, dynraw, fs, how == kWholeRowCut);
-    if (how != 1) code = 0;
-  }
-  if (how == kWholeRowCut || how == kWholeRow) {
-    // rows that are finished over the whole row: nucleus cut below the list, or no filter at all
-    how = whole_row_finish<DT>(a, b, rp, dynraw, fs, how == kWholeRowCut);
-    if (how != 1) code = 0;
+    code = how == 1 ? 16 : 0;                    // 16: finished over the whole row by this workgroup
   }
   if (how != 1) {
     __syncthreads();
