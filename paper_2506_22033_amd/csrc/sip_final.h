@@ -1045,14 +1045,16 @@ __device__ __attribute__((noinline)) int whole_row_draw(const char* row, const i
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
   const bool filtered = key_cut != 0 || minp_on;        // uniform: only part of the row is kept
   auto scaled_s = [&](float z) { return greedy ? z : __fdiv_rn(z, tau); };
-  auto mass = [&](float s) { return fix_of(expf(__fsub_rn(s, m))); };
   constexpr int EPL = (DT == SIP_F32) ? 4 : 8;
   constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
   const int e_last = ((V - 1) / EPL) * EPL;
   auto ldrow = [&](int e0) {                            // clamped: always a valid address
     return *reinterpret_cast<const uint4*>(row + (size_t)min(e0, e_last) * ESZ);
   };
-  auto masses = [&](const uint4& q, int e0, unsigned long long (&E)[EPL], uint32_t (&keys)[EPL]) {
+  // Masses as fp32, relative to the maximum; a lane adds those of one 16-byte load in a fixed
+  // order and only the sum becomes an integer (units of 2^-40), so that both reads of the row
+  // agree bit for bit on every partial sum while converting once per load, not per element.
+  auto masses = [&](const uint4& q, int e0, float (&E)[EPL], uint32_t (&keys)[EPL]) {
     float z[EPL];
     if (DT == SIP_F32) {
       z[0] = __uint_as_float(q.x); z[1] = __uint_as_float(q.y);
@@ -1065,29 +1067,30 @@ __device__ __attribute__((noinline)) int whole_row_draw(const char* row, const i
         z[2 * i + 1] = __uint_as_float(w4[i] & 0xFFFF0000u);
       }
     }
+    // the elements of one load share a bitmap word (e0 is a multiple of EPL <= 8)
+    const uint32_t word = has_pen ? bm[min(e0, V - 1) >> 5] : 0u;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
       const int v = e0 + i;
-      E[i] = 0; keys[i] = 0;
+      E[i] = 0.0f; keys[i] = 0;
       if (v < V) {
-        const uint32_t word = has_pen ? bm[v >> 5] : 0u;
         if ((word >> (v & 31)) & 1u) {                                     // carries a penalty: value from the list
           const float sv = value_of(cnt[pre[v >> 5] + __popc(word & ((1u << (v & 31)) - 1u))]);
           keys[i] = key_of(sv);
-          E[i] = mass(sv);
-          if (filtered && !(keys[i] >= key_cut && (!minp_on || __fsub_rn(sv, m) >= t_minp))) E[i] = 0;
+          E[i] = expf(__fsub_rn(sv, m));
+          if (filtered && !(keys[i] >= key_cut && (!minp_on || __fsub_rn(sv, m) >= t_minp))) E[i] = 0.0f;
         } else if (filtered) {
           // a cut by value: the exact s decides who is kept; the mass is exp(s - max) with the
           // hardware exp2, the same expression in both passes below
           const float sv = scaled_s(z[i]);
           keys[i] = key_of(sv);
           const bool keep = keys[i] >= key_cut && (!minp_on || __fsub_rn(sv, m) >= t_minp);
-          E[i] = keep ? fix_of(__builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(sv, m), 1.44269504f))) : 0ull;
+          E[i] = keep ? __builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(sv, m), 1.44269504f)) : 0.0f;
         } else {
           // exp(z/tau - max) as 2^((z - zmax) * c): no division, hardware exp2; the two passes
           // below use the same expression, which is all the draw needs
           keys[i] = __float_as_uint(z[i]);                                 // raw bits, turned into a key on a hit
-          E[i] = fix_of(__builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(z[i], zmax), c_row)));
+          E[i] = __builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(z[i], zmax), c_row));
         }
       }
     }
@@ -1106,11 +1109,13 @@ __device__ __attribute__((noinline)) int whole_row_draw(const char* row, const i
     unsigned long long mine = 0;
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-      unsigned long long E[EPL];
+      float E[EPL];
       uint32_t keys[EPL];
       masses(q[u], base + (u * kWave + lane) * EPL, E, keys);        // zero past the end of the row
+      float part = 0.0f;
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) mine += E[i];
+      for (int i = 0; i < EPL; ++i) part += E[i];
+      mine += fix_of(part);
     }
     mine = dpp_scan_add_u64(mine);
     if (lane == kWave - 1) hd[blk] = mine;
@@ -1154,20 +1159,22 @@ __device__ __attribute__((noinline)) int whole_row_draw(const char* row, const i
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
       const int e0 = base + (u * kWave + lane) * EPL;
-      unsigned long long E[EPL];
+      float E[EPL];
       uint32_t keys[EPL];
       masses(q[u], e0, E, keys);
-      unsigned long long lane_tot = 0;
+      float part = 0.0f;
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) lane_tot += E[i];
+      for (int i = 0; i < EPL; ++i) part += E[i];
+      const unsigned long long lane_tot = fix_of(part);
       const unsigned long long incl = dpp_scan_add_u64(lane_tot);
-      unsigned long long c = running + incl - lane_tot;
+      const unsigned long long c = running + incl - lane_tot;
       int hit = -1;
       uint32_t hit_key = 0;
+      float upto = 0.0f;                             // same additions in the same order as `part`
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
-        c += E[i];
-        if (hit < 0 && c > target) { hit = e0 + i; hit_key = keys[i]; }   // key, or raw bits if unpenalised
+        upto += E[i];
+        if (hit < 0 && E[i] > 0.0f && c + fix_of(upto) > target) { hit = e0 + i; hit_key = keys[i]; }   // key, or raw bits if unpenalised
       }
       const unsigned long long ball = __ballot(hit >= 0);
       if (ball && found < 0) {
