@@ -26,6 +26,11 @@ tau=0 reduce to lowest-index argmax, p=1 with k=0 is a no-op, unseen tokens unto
 chi-square of draw frequencies.  The conventions themselves (tie handling, filter order,
 index-order CDF, pre-filter logprobs) are not fixed by the paper and are therefore
 "parity unpinned" with respect to it: they are pinned only to their own definitions.
+
+The persistent decode state at the end of the file (history appended and token frequencies
+updated incrementally from one iteration to the next, Sec. 5.1) is pinned in
+tests/test_oracle_state.py: a hand-worked greedy sequence, the from-scratch route on a
+history the test records by itself and counts with numpy, and the invariants of slots.
 """
 from __future__ import annotations
 
@@ -146,14 +151,17 @@ def sample_row(row: np.ndarray, *, temperature: float = 1.0, top_k: int = 0, top
                min_p: float = 0.0, repetition_penalty: float = 1.0, frequency_penalty: float = 0.0,
                presence_penalty: float = 0.0, history: Optional[np.ndarray] = None,
                seed: int = 0, step: int = 0, row_id: int = 0, n_logprobs: int = 0,
-               u_override: Optional[float] = None, keep_arrays: bool = False) -> RowResult:
+               u_override: Optional[float] = None, keep_arrays: bool = False,
+               counts: Optional[np.ndarray] = None) -> RowResult:
     f32 = np.float32
     V = int(row.shape[0])
     idx = np.arange(V)
 
     # (0) widen, (1) counts, (2) penalties -- fp32
+    # ``counts`` (instead of ``history``) hands in a frequency vector kept up to date across
+    # iterations, the incremental construction of Sec. 5.1 (see DecodeState below).
     z = widen(row)
-    c = history_counts(history, V)
+    c = history_counts(history, V) if counts is None else np.asarray(counts, dtype=np.int64)
     z = apply_penalties(z, c, repetition_penalty, frequency_penalty, presence_penalty)
 
     tau = f32(temperature)
@@ -276,4 +284,80 @@ def sample_batch(logits: np.ndarray, params: dict, hist_indptr: Optional[np.ndar
         rid = b if row_ids is None else int(row_ids[b])
         out.append(sample_row(logits[b], history=hist, seed=seed, step=step, row_id=rid,
                               n_logprobs=n_logprobs, keep_arrays=keep_arrays, **kw))
+    return out
+
+
+# ----------------------------------------------------------------------------------
+# State that persists across decode iterations (Sec. 5.1, "memory reuse" and "incremental
+# penalty construction").  The paper preallocates the output matrix Y (L_max x B) and
+# appends each iteration's ids to it, and keeps a frequency table f (V x B) per penalty
+# type that it updates only at the B newly generated tokens instead of rebuilding it from
+# Y.  Here a *slot* is one column of those tables: a sequence keeps its slot for its whole
+# life, a batch names the slot of each of its rows, and a finished sequence's slot is
+# handed to a new one by ``assign``.  Microbatches in flight at once (the paper's p
+# replicas of the state) are disjoint sets of slots of one state.
+#
+# Readings (the paper does not say): a full slot (L_max tokens) takes no further tokens,
+# its history stays as it is and ``overflow`` counts the dropped ids; a prompt longer
+# than L_max keeps its first L_max tokens and counts once; the random stream of call
+# number t on a state (t = 0 for the first call after ``__init__``) uses Philox step
+# ``step + t``, so that a caller who replays one recorded call still gets fresh numbers.
+
+class DecodeState:
+    def __init__(self, slots: int, L_max: int, V: int):
+        self.slots, self.L_max, self.V = int(slots), int(L_max), int(V)
+        self.Y = np.full((self.slots, self.L_max), -1, dtype=np.int32)   # token history per slot
+        self.length = np.zeros(self.slots, dtype=np.int64)
+        self.f = np.zeros((self.slots, self.V), dtype=np.int32)          # occurrences of v in the slot's history
+        self.tick = 0                                                     # sampling calls made so far
+        self.overflow = 0
+
+    def _push(self, s: int, t: int) -> bool:
+        if self.length[s] >= self.L_max:
+            return False
+        self.Y[s, self.length[s]] = t
+        self.length[s] += 1
+        if 0 <= t < self.V:                 # ids outside the vocabulary are padding: stored, never counted
+            self.f[s, t] += 1
+        return True
+
+    def assign(self, slot: int, tokens: Sequence[int]) -> None:
+        """Hand ``slot`` to a new sequence whose history so far (its prompt) is ``tokens``."""
+        s = int(slot)
+        self.Y[s, :] = -1
+        self.length[s] = 0
+        self.f[s, :] = 0
+        dropped = False
+        for t in tokens:
+            if not self._push(s, int(t)):
+                dropped = True
+        self.overflow += int(dropped)
+
+    def history(self, slot: int) -> np.ndarray:
+        return self.Y[int(slot), :int(self.length[int(slot)])].copy()
+
+
+def sample_state(logits: np.ndarray, params: dict, state: DecodeState, slot_of_row: Sequence[int],
+                 seed: int, step: int, n_logprobs: int, row_ids: Optional[np.ndarray] = None):
+    """One decode iteration on persistent state: every row is sampled with the frequency
+    vector of its slot as it stands *before* this call, then the B new ids are appended
+    (Y) and counted (f).  A row whose slot is outside [0, slots) has no history and leaves
+    no trace.  The slots named by one call must be distinct."""
+    B = logits.shape[0]
+    out = []
+    for b in range(B):
+        kw = {}
+        for name, dflt in _DEFAULTS.items():
+            arr = params.get(name)
+            kw[name] = dflt if arr is None else arr[b]
+        s = int(slot_of_row[b])
+        counts = state.f[s] if 0 <= s < state.slots else np.zeros(state.V, dtype=np.int32)
+        rid = b if row_ids is None else int(row_ids[b])
+        out.append(sample_row(logits[b], counts=counts, seed=seed, step=step + state.tick, row_id=rid,
+                              n_logprobs=n_logprobs, **kw))
+    for b in range(B):
+        s = int(slot_of_row[b])
+        if 0 <= s < state.slots and not state._push(s, int(out[b].token)):
+            state.overflow += 1
+    state.tick += 1
     return out
