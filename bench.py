@@ -77,6 +77,70 @@ def read_traffic(name: str):
     return None
 
 
+def decode_on_state(w, d, bufs, sip, dev, stream, args, csr_ws_bytes):
+    """The same steps as a decode loop: every step's ids join the histories that the next step is
+    penalised with.  Timed twice: with the histories in a device-resident state that the library
+    appends to (sip_sample_state: enqueues only), and -- on fewer steps -- the way a caller of the
+    stateless entry point has to do it (ids to the host, CSR rebuilt there, uploaded again)."""
+    import torch
+    B, V, k = w.B, w.V, w.k_logprobs
+    nbuf = len(bufs)
+    lens = np.diff(w.hist_indptr)
+    L_max = int(-(-(lens.max() + args.warmup + args.steps + 1) // 256) * 256)
+    slots = B
+    state = torch.empty(sip.sip_state_bytes(slots, L_max), dtype=torch.uint8, device=dev)
+    slot_of_row = torch.arange(B, dtype=torch.int32, device=dev)
+    dt_code = sip.SIP_F32 if w.dtype == "f32" else sip.SIP_BF16
+    ws = torch.empty(sip.sip_workspace_bytes(B, V, dt_code, B * L_max, k), dtype=torch.uint8, device=dev)
+    out_ids = torch.empty(B, dtype=torch.int32, device=dev)
+    out_lp_ids = torch.empty(B, 1 + k, dtype=torch.int32, device=dev)
+    out_lp = torch.empty(B, 1 + k, dtype=torch.float32, device=dev)
+    with torch.cuda.stream(stream):
+        sip.sip_state_init(state, slots, L_max)
+        sip.sip_state_assign(state, slots, L_max, slot_of_row, d.indptr, d.tokens)
+
+        def step(i):
+            sip.sip_sample_state(bufs[i % nbuf], d.params, state, slots, L_max, slot_of_row, 0, 0, k,
+                                 out_ids=out_ids, out_lp_ids=out_lp_ids, out_lp=out_lp, workspace=ws, V=V)
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+        ms_state = (time.perf_counter() - t0) * 1e3 / args.steps
+        tick, overflow, length, _ = sip.state_views(state, slots, L_max)
+        ok = int(tick.item()) == args.warmup + args.steps and int(overflow.item()) == 0 and \
+            bool((length.cpu().numpy() == lens + args.warmup + args.steps).all())
+
+        # the stateless way: one host round trip per step
+        n_host = max(5, min(40, args.steps // 5))
+        host_tok = np.full((B, int(lens.max()) + n_host + 2), -1, dtype=np.int32)
+        for b in range(B):
+            host_tok[b, :lens[b]] = w.hist_tokens[w.hist_indptr[b]:w.hist_indptr[b + 1]]
+        host_len = lens.copy()
+        ws2 = torch.empty(sip.sip_workspace_bytes(B, V, dt_code, int(lens.sum()) + B * (n_host + 2), k),
+                          dtype=torch.uint8, device=dev)
+        indptr, tokens = d.indptr, d.tokens
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_host):
+            sip.sip_sample(bufs[i % nbuf], d.params, indptr, tokens, 0, i, k, out_ids=out_ids, out_lp_ids=out_lp_ids,
+                           out_lp=out_lp, workspace=ws2, V=V)
+            ids = out_ids.cpu().numpy()                                   # waits for the step
+            host_tok[np.arange(B), host_len] = ids
+            host_len = host_len + 1
+            mask = np.arange(host_tok.shape[1])[None, :] < host_len[:, None]
+            indptr = torch.from_numpy(np.concatenate(([0], np.cumsum(host_len))).astype(np.int64)).to(dev)
+            tokens = torch.from_numpy(host_tok[mask]).to(dev)
+        torch.cuda.synchronize()
+        ms_host = (time.perf_counter() - t0) * 1e3 / n_host
+    return {"ms_per_step": ms_state, "value": B / (ms_state * 1e-3), "unit": "rows/s", "slots": slots, "L_max": L_max,
+            "state_consistent_after_run": ok,
+            "stateless_with_host_round_trip_ms_per_step": ms_host, "stateless_steps_timed": n_host}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -183,6 +247,8 @@ def main() -> int:
     achieved = alg / (dom_ms * 1e-3) / 1e9
     whole_call = alg / (launch_ms * 1e-3) / 1e9
 
+    state_leg = decode_on_state(w, d, bufs, sip, dev, stream, args, ws.numel()) if nnz else None
+
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -217,6 +283,7 @@ def main() -> int:
                      "whole_call_frac": whole_call / HBM_PEAK_GBS,
                      "rows_on_single_pass_path_last_step": single_pass_rows},
         "cpu_baseline": cpu,
+        "decode_on_device_state": state_leg,
     }
     print(json.dumps(res))
     return 0

@@ -43,6 +43,8 @@ typedef enum {
 
 #define SIP_MAX_V (1 << 19)        /* largest vocabulary the kernels support            */
 #define SIP_MAX_K_LOGPROBS 64      /* largest k_logprobs                                */
+#define SIP_MAX_SLOTS (1 << 20)    /* most slots a sampler state can have               */
+#define SIP_MAX_L (1 << 17)        /* longest history a slot of a sampler state can hold */
 
 /*
  * Per-row sampling parameters (Sec. 2.1 step 3: tau, k, p; Sec. 7.1 "Workload" adds min-p
@@ -116,8 +118,68 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * ---- Device-resident sampler state ---------------------------------------------------------
+ * The counterpart, in device memory, of what Sec. 5.1 keeps on the host between iterations
+ * ("memory reuse": a preallocated table of generated ids that each iteration appends to, instead
+ * of a history rebuilt per call; "incremental penalty construction": per-iteration work that
+ * grows with the B new tokens, not with the history).  A state holds `slots` histories of up to
+ * `L_max` tokens.  A sequence keeps its slot for its whole life; sip_sample_state() reads each
+ * row's history from its slot and appends the id it sampled; a finished sequence's slot is handed
+ * to a new one with sip_state_assign().  Batches that are in flight at once (the p copies of the
+ * sampler state the paper keeps for a pipeline of depth p) use disjoint slots of one state, or
+ * states of their own.  A decode loop on a state is a pure sequence of enqueues: no host copy of
+ * the history, no synchronisation, and nothing in it that a stream capture cannot record.
+ *
+ * Layout of the caller-owned, 256-byte aligned buffer (all little endian, part of this ABI so
+ * that callers can read it back):
+ *   byte 0    uint64  tick      sampling calls made on the state since sip_state_init()
+ *   byte 8    uint32  overflow  ids that found their slot full, plus prompts cut to L_max
+ *   byte 256  int32   len[slots]
+ *   byte 256 + round_up(4 * slots, 256)   int32 tokens[slots][L_max]
+ * Calls that touch one state must be ordered (same stream, or events between streams).
+ */
+
+/* Bytes of a state with this shape; 0 if slots or L_max is not in 1..SIP_MAX_SLOTS / 1..SIP_MAX_L. */
+size_t sip_state_bytes(int32_t slots, int32_t L_max);
+
+/* Enqueue: every slot empty, tick = 0, overflow = 0.  `state` is a device buffer of at least
+ * sip_state_bytes() bytes (else SIP_ERR_WORKSPACE).  Must precede any other use of the buffer. */
+sip_status sip_state_init(void* state, size_t state_bytes, int32_t slots, int32_t L_max, void* hip_stream);
+
+/*
+ * Enqueue: hand n slots to new sequences.  Slot slot_ids[i] (device array [n]) forgets what it
+ * held and takes tokens[indptr[i] .. indptr[i+1]) -- the sequence's history so far, normally its
+ * prompt -- as its history; indptr (device, [n+1]) and tokens (device, [nnz]) may be NULL with
+ * nnz = 0 for empty histories.  A prompt longer than L_max keeps its first L_max tokens and adds
+ * one to `overflow`.  Entries of slot_ids outside [0, slots) are skipped; the same slot twice
+ * in one call leaves either prompt.  n = 0 is allowed and does nothing.
+ */
+sip_status sip_state_assign(void* state, size_t state_bytes, int32_t slots, int32_t L_max, int32_t n,
+                            const int32_t* slot_ids, const int64_t* indptr, const int32_t* tokens, int64_t nnz,
+                            void* hip_stream);
+
+/*
+ * sip_sample() on a state (Sec. 2.1 step 3 with y_<s taken from, and y_s appended to, the state).
+ * Arguments as for sip_sample() except:
+ *  slot_of_row   device [B]: row b's history is slot slot_of_row[b] as it stands before this
+ *                call.  A value outside [0, slots) = a row without history that leaves no trace.
+ *                The slots named by one call must be distinct (otherwise one of the ids is kept).
+ *  step          the Philox step of this call is step + tick, so that a recorded call, replayed,
+ *                draws fresh numbers each time.
+ *  workspace     at least sip_workspace_bytes(B, V, dtype, (int64_t)B * L_max, k_logprobs) bytes.
+ * After the rows are sampled, out_ids[b] is appended to slot_of_row[b] (a full slot stays as it
+ * is and `overflow` grows by one) and tick grows by one.  Same error behaviour as sip_sample():
+ * an argument or workspace error is found before anything is enqueued and leaves the state as it is.
+ */
+sip_status sip_sample_state(const void* logits, int32_t B, int32_t V, int64_t row_stride, sip_dtype dtype,
+                            const sip_params* params, void* state, size_t state_bytes, int32_t slots,
+                            int32_t L_max, const int32_t* slot_of_row, uint64_t seed, uint64_t step,
+                            int32_t* out_ids, int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Profiling aid.  Arms a one-shot hook on the calling host thread: the next sip_sample() call
- * made by this thread that takes the single-pass path launches its two kernels with the given
+ * (or sip_sample_state() call) made by this thread that takes the single-pass path launches its two kernels with the given
  * hipEvent_t handles (created by the caller with timing enabled) attached to the kernel
  * dispatches themselves: `stream_start` / `stream_stop` take the begin and end time stamps of
  * the streaming kernel -- the one pass over the logits, Sec. 5.1's dense row-wise work --

@@ -17,6 +17,8 @@ SIP_F32, SIP_BF16 = 0, 1
 SIP_OK, SIP_ERR_INVALID_ARG, SIP_ERR_UNSUPPORTED, SIP_ERR_WORKSPACE, SIP_ERR_HIP = range(5)
 SIP_MAX_V = 1 << 19
 SIP_MAX_K_LOGPROBS = 64
+SIP_MAX_SLOTS = 1 << 20
+SIP_MAX_L = 1 << 17
 
 PARAM_FIELDS = ("temperature", "top_k", "top_p", "min_p", "repetition_penalty",
                 "frequency_penalty", "presence_penalty", "row_id")
@@ -56,6 +58,21 @@ def load() -> ctypes.CDLL:
             ctypes.POINTER(SipParams), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
             ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        lib.sip_state_bytes.restype = ctypes.c_size_t
+        lib.sip_state_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+        lib.sip_state_init.restype = ctypes.c_int
+        lib.sip_state_init.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32,
+                                       ctypes.c_void_p]
+        lib.sip_state_assign.restype = ctypes.c_int
+        lib.sip_state_assign.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_int64, ctypes.c_void_p]
+        lib.sip_sample_state.restype = ctypes.c_int
+        lib.sip_sample_state.argtypes = [
+            ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int,
+            ctypes.POINTER(SipParams), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32,
+            ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         lib.sip_status_string.restype = ctypes.c_char_p
         lib.sip_status_string.argtypes = [ctypes.c_int]
         lib.sip_profile_kernel_events.restype = None
@@ -152,3 +169,94 @@ def sip_sample(logits: torch.Tensor, params: Optional[Dict[str, Optional[torch.T
     if status != SIP_OK:
         raise SipError(status)
     return out_ids, out_lp_ids, out_lp
+
+
+# ---- device-resident sampler state
+
+def sip_state_bytes(slots: int, L_max: int) -> int:
+    return int(load().sip_state_bytes(slots, L_max))
+
+
+def _nbytes(t: torch.Tensor) -> int:
+    return t.numel() * t.element_size()
+
+
+def _stream_handle(dev, stream):
+    return (torch.cuda.current_stream(dev) if stream is None else stream).cuda_stream
+
+
+def sip_state_init(state: torch.Tensor, slots: int, L_max: int,
+                   stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Enqueue the initialisation of ``state`` (a device byte buffer of sip_state_bytes())."""
+    if not state.is_cuda:
+        raise TypeError("state must be a device tensor")
+    status = load().sip_state_init(_ptr(state), _nbytes(state), slots, L_max, _stream_handle(state.device, stream))
+    if status != SIP_OK:
+        raise SipError(status)
+
+
+def sip_state_assign(state: torch.Tensor, slots: int, L_max: int, slot_ids: torch.Tensor,
+                     indptr: Optional[torch.Tensor], tokens: Optional[torch.Tensor],
+                     stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Enqueue: slot ``slot_ids[i]`` restarts with ``tokens[indptr[i]:indptr[i+1]]`` as its history."""
+    if not state.is_cuda or not slot_ids.is_cuda or slot_ids.dtype != torch.int32:
+        raise TypeError("state and slot_ids (int32) must be device tensors")
+    n = slot_ids.numel()
+    nnz = 0
+    if indptr is not None and tokens is not None:
+        if indptr.dtype != torch.int64 or tokens.dtype != torch.int32 or indptr.numel() != n + 1:
+            raise TypeError("indptr must be int64 with n + 1 entries and tokens int32")
+        nnz = tokens.numel()
+    status = load().sip_state_assign(_ptr(state), _nbytes(state), slots, L_max, n, _ptr(slot_ids),
+                                     _ptr(indptr) if nnz else None, _ptr(tokens) if nnz else None, nnz,
+                                     _stream_handle(state.device, stream))
+    if status != SIP_OK:
+        raise SipError(status)
+
+
+def sip_sample_state(logits: torch.Tensor, params: Optional[Dict[str, Optional[torch.Tensor]]],
+                     state: torch.Tensor, slots: int, L_max: int, slot_of_row: torch.Tensor,
+                     seed: int, step: int, k_logprobs: int, *,
+                     out_ids: Optional[torch.Tensor] = None, out_lp_ids: Optional[torch.Tensor] = None,
+                     out_lp: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                     V: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None
+                     ) -> Tuple[torch.Tensor, Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """sip_sample with the histories read from, and the sampled ids appended to, ``state``."""
+    lib = load()
+    if not logits.is_cuda or logits.dim() != 2 or logits.stride(1) != 1:
+        raise TypeError("logits must be a 2-D device tensor with contiguous rows")
+    B = logits.shape[0]
+    V = logits.shape[1] if V is None else int(V)
+    dt = dtype_code(logits)
+    dev = logits.device
+    if not slot_of_row.is_cuda or slot_of_row.dtype != torch.int32 or slot_of_row.numel() != B:
+        raise TypeError("slot_of_row must be a device tensor of B x int32")
+    if out_ids is None:
+        out_ids = torch.empty(B, dtype=torch.int32, device=dev)
+    if k_logprobs >= 0:
+        if out_lp_ids is None:
+            out_lp_ids = torch.empty(B, 1 + k_logprobs, dtype=torch.int32, device=dev)
+        if out_lp is None:
+            out_lp = torch.empty(B, 1 + k_logprobs, dtype=torch.float32, device=dev)
+    if workspace is None:
+        need = sip_workspace_bytes(B, V, dt, B * L_max, k_logprobs)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    sp = make_params(params, B)
+    status = lib.sip_sample_state(_ptr(logits), B, V, logits.stride(0), dt, ctypes.byref(sp), _ptr(state),
+                                  _nbytes(state), slots, L_max, _ptr(slot_of_row), seed, step, _ptr(out_ids),
+                                  _ptr(out_lp_ids), _ptr(out_lp), k_logprobs, _ptr(workspace), _nbytes(workspace),
+                                  _stream_handle(dev, stream))
+    if status != SIP_OK:
+        raise SipError(status)
+    return out_ids, out_lp_ids, out_lp
+
+
+def state_views(state: torch.Tensor, slots: int, L_max: int):
+    """(tick, overflow, len [slots], tokens [slots, L_max]) as views of a state buffer, per the
+    layout that include/sip.h documents."""
+    len_bytes = (4 * slots + 255) // 256 * 256
+    tick = state[0:8].view(torch.int64)
+    overflow = state[8:12].view(torch.int32)
+    length = state[256:256 + 4 * slots].view(torch.int32)
+    tokens = state[256 + len_bytes:256 + len_bytes + 4 * slots * L_max].view(torch.int32).view(slots, L_max)
+    return tick, overflow, length, tokens

@@ -10,6 +10,7 @@
 #include "sip_device.h"
 #include "sip_exact.h"
 #include "sip_final.h"
+#include "sip_state.h"
 #include "sip_stream.h"
 
 namespace {
@@ -83,32 +84,33 @@ Layout make_layout(int32_t B, const Plan& p, int64_t nnz) {
   return l;
 }
 
-}  // namespace
+// Where a call's token histories come from: a CSR handed in by the caller, or the slots of a
+// device-resident state.
+struct HistSource {
+  const int64_t* indptr = nullptr;
+  const int32_t* tokens = nullptr;
+  int64_t nnz = 0;                                   // entries the side tables of the workspace are sized for
+  const int32_t* slot = nullptr;
+  const int* st_len = nullptr;
+  const unsigned long long* st_tick = nullptr;
+  int L_max = 0, slots = 0;
+};
 
-extern "C" {
-
-size_t sip_workspace_bytes(int32_t B, int32_t V, sip_dtype dtype, int64_t hist_nnz, int32_t k_logprobs) {
-  if (!shape_ok(B, V, (int)dtype, hist_nnz, k_logprobs)) return 0;
-  if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
-  return make_layout(B, make_plan(B, V, (int)dtype), hist_nnz).total;
-}
-
-sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stride, sip_dtype dtype,
-                      const sip_params* params, const int64_t* hist_indptr, const int32_t* hist_tokens,
-                      int64_t hist_nnz, uint64_t seed, uint64_t step, int32_t* out_ids, int32_t* out_lp_ids,
-                      float* out_lp, int32_t k_logprobs, void* workspace, size_t workspace_bytes,
-                      void* hip_stream) {
-  if (!shape_ok(B, V, (int)dtype, hist_nnz, k_logprobs)) return SIP_ERR_INVALID_ARG;
+// Argument checks common to both entry points, workspace carving and the kernel launches.
+sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_stride, sip_dtype dtype,
+                       const sip_params* params, const HistSource& h, uint64_t seed, uint64_t step,
+                       int32_t* out_ids, int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs, void* workspace,
+                       size_t workspace_bytes, hipStream_t stream) {
+  if (!shape_ok(B, V, (int)dtype, h.nnz, k_logprobs)) return SIP_ERR_INVALID_ARG;
   if (!logits || !out_ids || row_stride < V) return SIP_ERR_INVALID_ARG;
   if ((k_logprobs >= 0) != (out_lp_ids != nullptr) || (k_logprobs >= 0) != (out_lp != nullptr))
     return SIP_ERR_INVALID_ARG;
-  if (hist_nnz > 0 && (!hist_indptr || !hist_tokens)) return SIP_ERR_INVALID_ARG;
   const size_t esz = dtype == SIP_F32 ? 4 : 2;
   if ((reinterpret_cast<uintptr_t>(logits) & 15u) != 0 || ((size_t)row_stride * esz) % 16 != 0)
     return SIP_ERR_INVALID_ARG;
   if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return SIP_ERR_UNSUPPORTED;
   const Plan plan = make_plan(B, V, (int)dtype);
-  const Layout lay = make_layout(B, plan, hist_nnz);
+  const Layout lay = make_layout(B, plan, h.nnz);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 || workspace_bytes < lay.total)
     return SIP_ERR_WORKSPACE;
 
@@ -116,9 +118,10 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
   a.logits = logits;
   a.B = B; a.V = V; a.row_stride = row_stride;
   if (params) a.p = *params; else a.p = sip_params{};
-  a.indptr = reinterpret_cast<const long long*>(hist_indptr);
-  a.tokens = hist_tokens;
-  a.nnz = (hist_indptr && hist_tokens) ? hist_nnz : 0;
+  a.indptr = reinterpret_cast<const long long*>(h.indptr);
+  a.tokens = h.tokens;
+  a.nnz = h.slot ? (long long)h.slots * h.L_max : ((h.indptr && h.tokens) ? h.nnz : 0);
+  a.slot = h.slot; a.st_len = h.st_len; a.st_tick = h.st_tick; a.L_max = h.L_max; a.slots = h.slots;
   a.seed = seed; a.step = step;
   a.out_ids = out_ids; a.out_lp_ids = out_lp_ids; a.out_lp = out_lp; a.k_lp = k_logprobs;
   char* ws = static_cast<char*>(workspace);
@@ -129,7 +132,6 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
   a.cand = reinterpret_cast<uint2*>(ws + lay.cand);
   a.S = plan.S; a.cap_w = plan.cap_w; a.nc_cap = plan.nc_cap;
 
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t words = ((size_t)V + 31) / 32;
   if (!plan.fast) {
     // every row takes the exact multi-pass path
@@ -157,6 +159,87 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
     hipLaunchKernelGGL(k_final, dim3(B), dim3(sip::kFinalThreads), dyn, stream, a);
   if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
   return SIP_OK;
+}
+
+bool state_shape_ok(int32_t slots, int32_t L_max) {
+  return slots > 0 && L_max > 0 && slots <= SIP_MAX_SLOTS && L_max <= SIP_MAX_L;
+}
+bool state_ok(const void* state, size_t state_bytes, int32_t slots, int32_t L_max) {
+  return state && (reinterpret_cast<uintptr_t>(state) & (kAlign - 1)) == 0 &&
+         state_bytes >= sip::state_total(slots, L_max);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t sip_workspace_bytes(int32_t B, int32_t V, sip_dtype dtype, int64_t hist_nnz, int32_t k_logprobs) {
+  if (!shape_ok(B, V, (int)dtype, hist_nnz, k_logprobs)) return 0;
+  if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
+  return make_layout(B, make_plan(B, V, (int)dtype), hist_nnz).total;
+}
+
+sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stride, sip_dtype dtype,
+                      const sip_params* params, const int64_t* hist_indptr, const int32_t* hist_tokens,
+                      int64_t hist_nnz, uint64_t seed, uint64_t step, int32_t* out_ids, int32_t* out_lp_ids,
+                      float* out_lp, int32_t k_logprobs, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  if (hist_nnz > 0 && (!hist_indptr || !hist_tokens)) return SIP_ERR_INVALID_ARG;
+  HistSource h;
+  h.indptr = hist_indptr; h.tokens = hist_tokens; h.nnz = hist_nnz;
+  return sample_impl(logits, B, V, row_stride, dtype, params, h, seed, step, out_ids, out_lp_ids, out_lp,
+                     k_logprobs, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t sip_state_bytes(int32_t slots, int32_t L_max) {
+  if (!state_shape_ok(slots, L_max)) return 0;
+  return sip::state_total(slots, L_max);
+}
+
+sip_status sip_state_init(void* state, size_t state_bytes, int32_t slots, int32_t L_max, void* hip_stream) {
+  if (!state_shape_ok(slots, L_max)) return SIP_ERR_INVALID_ARG;
+  if (!state_ok(state, state_bytes, slots, L_max)) return SIP_ERR_WORKSPACE;
+  const sip::StateView v = sip::state_view(state, slots, L_max);
+  const int blocks = (slots + sip::kStateThreads - 1) / sip::kStateThreads;
+  hipLaunchKernelGGL(sip::state_init_kernel, dim3(blocks), dim3(sip::kStateThreads), 0,
+                     static_cast<hipStream_t>(hip_stream), v.head, v.len, slots);
+  return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
+}
+
+sip_status sip_state_assign(void* state, size_t state_bytes, int32_t slots, int32_t L_max, int32_t n,
+                            const int32_t* slot_ids, const int64_t* indptr, const int32_t* tokens, int64_t nnz,
+                            void* hip_stream) {
+  if (!state_shape_ok(slots, L_max) || n < 0 || nnz < 0) return SIP_ERR_INVALID_ARG;
+  if (n > 0 && !slot_ids) return SIP_ERR_INVALID_ARG;
+  if (nnz > 0 && (!indptr || !tokens)) return SIP_ERR_INVALID_ARG;
+  if (!state_ok(state, state_bytes, slots, L_max)) return SIP_ERR_WORKSPACE;
+  if (n == 0) return SIP_OK;
+  const sip::StateView v = sip::state_view(state, slots, L_max);
+  hipLaunchKernelGGL(sip::state_assign_kernel, dim3(n), dim3(sip::kStateThreads), 0,
+                     static_cast<hipStream_t>(hip_stream), v.head, v.len, v.tokens, slots, L_max, slot_ids,
+                     reinterpret_cast<const long long*>(indptr), tokens, (long long)nnz);
+  return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
+}
+
+sip_status sip_sample_state(const void* logits, int32_t B, int32_t V, int64_t row_stride, sip_dtype dtype,
+                            const sip_params* params, void* state, size_t state_bytes, int32_t slots,
+                            int32_t L_max, const int32_t* slot_of_row, uint64_t seed, uint64_t step,
+                            int32_t* out_ids, int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs,
+                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!state_shape_ok(slots, L_max) || !slot_of_row || B <= 0) return SIP_ERR_INVALID_ARG;
+  if (!state_ok(state, state_bytes, slots, L_max)) return SIP_ERR_WORKSPACE;
+  const sip::StateView v = sip::state_view(state, slots, L_max);
+  HistSource h;
+  h.tokens = v.tokens; h.nnz = (int64_t)B * L_max;
+  h.slot = slot_of_row; h.st_len = v.len; h.st_tick = &v.head->tick; h.L_max = L_max; h.slots = slots;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const sip_status st = sample_impl(logits, B, V, row_stride, dtype, params, h, seed, step, out_ids, out_lp_ids,
+                                    out_lp, k_logprobs, workspace, workspace_bytes, stream);
+  if (st != SIP_OK) return st;
+  const int blocks = (B + sip::kStateThreads - 1) / sip::kStateThreads;
+  hipLaunchKernelGGL(sip::state_append_kernel, dim3(blocks), dim3(sip::kStateThreads), 0, stream, v.head, v.len,
+                     v.tokens, slots, L_max, slot_of_row, out_ids, B);
+  return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
 }
 
 const char* sip_status_string(sip_status status) {

@@ -43,7 +43,40 @@ struct Args {
   int cap_w;                // candidate slots per wave segment
   int nc_cap;               // candidates the finishing kernel can hold in LDS
   int* row_path;            // [B] diagnostic: 1 = finished by the single-pass path, >1 = exact path (reason)
+  // Device-resident history (sip_sample_state): `slot` != nullptr replaces the CSR above.  Row b's
+  // history is tokens[slot[b] * L_max .. + st_len[slot[b]]); `tokens` then points at the state's
+  // token table and nnz = slots * L_max.
+  const int* slot;                     // [B]; outside [0, slots): the row has no history
+  const int* st_len;                   // [slots]
+  const unsigned long long* st_tick;   // sampling calls made on the state so far; added to `step`
+  int L_max, slots;
 };
+
+// Extent of row b's history in a.tokens, clamped so that no read leaves the array, and where the
+// row's part of the exact path's side tables starts.
+struct HistRange { long long lo, hi, side; };
+__device__ __forceinline__ HistRange hist_range(const Args& a, int b) {
+  HistRange h{0, 0, 0};
+  if (a.slot) {
+    const int s = a.slot[b];
+    h.side = (long long)b * a.L_max;
+    if (s >= 0 && s < a.slots) {
+      const int n = a.st_len[s];
+      h.lo = (long long)s * a.L_max;
+      h.hi = h.lo + (n < 0 ? 0 : (n > a.L_max ? a.L_max : n));
+    }
+  } else if (a.indptr && a.tokens && a.nnz > 0) {
+    h.lo = a.indptr[b]; h.hi = a.indptr[b + 1];
+    h.lo = h.lo < 0 ? 0 : (h.lo > a.nnz ? a.nnz : h.lo);
+    h.hi = h.hi < h.lo ? h.lo : (h.hi > a.nnz ? a.nnz : h.hi);
+    h.side = h.lo;
+  }
+  return h;
+}
+// Philox step of this call.
+__device__ __forceinline__ unsigned long long step_of(const Args& a) {
+  return a.step + (a.st_tick ? *a.st_tick : 0ull);
+}
 
 // A row is cut into S chunks of whole units of `unit` elements (what one wave reads with one
 // 16-byte load per lane), the chunk sizes differing by at most one unit.  First element of

@@ -356,17 +356,13 @@ __device__ __attribute__((noinline)) void exact_row(const Args& a, const int b, 
   r.greedy = (r.tau == 0.0f) || (top_k == 1);
 
   // ---- (1) history -> bitmap, ranks, multiplicities, penalised values  (Sec. 5.1 CalcPenalty)
-  long long lo = 0, hi = 0;
-  if (a.indptr && a.tokens && a.nnz > 0) {
-    lo = a.indptr[b]; hi = a.indptr[b + 1];
-    lo = lo < 0 ? 0 : (lo > a.nnz ? a.nnz : lo);
-    hi = hi < lo ? lo : (hi > a.nnz ? a.nnz : hi);
-  }
+  const HistRange hr = hist_range(a, b);
+  const long long lo = hr.lo, hi = hr.hi;
   r.has_pen = (hi > lo) && (theta != 1.0f || phi != 0.0f || psi != 0.0f);
-  r.side_z = a.side_z + lo;
+  r.side_z = a.side_z + hr.side;
   if (r.has_pen) {
-    float* side_z = a.side_z + lo;
-    unsigned int* side_c = a.side_c + lo;
+    float* side_z = a.side_z + hr.side;
+    unsigned int* side_c = a.side_c + hr.side;
     for (int w = tid; w < W; w += (int)blockDim.x) bm[w] = 0;
     __syncthreads();
     for (long long i = lo + tid; i < hi; i += (int)blockDim.x) {
@@ -483,7 +479,7 @@ __device__ __attribute__((noinline)) void exact_row(const Args& a, const int b, 
     unsigned long long p3 = 0;
     for_each_elem<DT>(r, [&](int v, float z) { p3 += kept_mass(v, z); });
     const unsigned long long S3 = block_sum_u64(p3, sh);
-    const unsigned long long j = philox_word0(a.seed, row_id, a.step) >> 8;
+    const unsigned long long j = philox_word0(a.seed, row_id, step_of(a)) >> 8;
     // floor(j * S3 / 2^24), exact in 128-bit integer arithmetic
     const unsigned long long target = (__umul64hi(j, S3) << 40) | ((j * S3) >> 24);
     const int hit = first_crossing<DT>(r, target, sh, kept_mass);

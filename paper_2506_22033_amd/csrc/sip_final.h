@@ -135,12 +135,8 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
 
   SIP_MARK(0);
   // ---- (0) chunk summaries, history extent; clear the LDS tables meanwhile
-  long long lo = 0, hi = 0;
-  if (a.indptr && a.tokens && a.nnz > 0) {
-    lo = a.indptr[b]; hi = a.indptr[b + 1];
-    lo = lo < 0 ? 0 : (lo > a.nnz ? a.nnz : lo);
-    hi = hi < lo ? lo : (hi > a.nnz ? a.nnz : hi);
-  }
+  const HistRange hr = hist_range(a, b);
+  const long long lo = hr.lo, hi = hr.hi;
   const bool has_pen = (hi > lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
   const int nseg = S * kStreamWaves;
   if (tid == 0) {
@@ -175,7 +171,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   // row constants that take long arithmetic, worked out while the loads above travel
   const bool minp_on = !rp.greedy && rp.min_p > 0.0f;
   const float t_minp = minp_on ? (float)log((double)rp.min_p) : 0.0f;
-  const unsigned long long j24 = rp.greedy ? 0ull : (unsigned long long)(philox_word0(a.seed, rp.row_id, a.step) >> 8);
+  const unsigned long long j24 = rp.greedy ? 0ull : (unsigned long long)(philox_word0(a.seed, rp.row_id, step_of(a)) >> 8);
   float c_row, c_lo;
   scale_pair(rp, c_row, c_lo);
   __syncthreads();
@@ -966,9 +962,8 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   int code = 0;
   const int target = candidate_target(rp, a);
   if (target != 0) {
-    long long hist_len = 0;
-    if (a.indptr && a.tokens && a.nnz > 0) hist_len = a.indptr[b + 1] - a.indptr[b];
-    if (hist_len < 0 || hist_len > a.nnz) hist_len = a.nnz;
+    const HistRange hr = hist_range(a, b);
+    const long long hist_len = hr.hi - hr.lo;
     // At most two attempts, written as a loop so that the kernel holds one copy of the code.
     int S = a.S, cap_w = a.cap_w;
 #pragma nounroll
@@ -1372,7 +1367,7 @@ __device__ __attribute__((noinline)) int whole_row_finish(const Args& a, const i
   const bool has_pen = fs.has_pen_out != 0;
   const bool minp_on = cut && rp.min_p > 0.0f;
   const float t_minp = minp_on ? (float)log((double)rp.min_p) : 0.0f;
-  const unsigned long long j24 = (unsigned long long)(philox_word0(a.seed, rp.row_id, a.step) >> 8);
+  const unsigned long long j24 = (unsigned long long)(philox_word0(a.seed, rp.row_id, step_of(a)) >> 8);
   float c_row, c_lo;
   scale_pair(rp, c_row, c_lo);
   uint32_t key_cut = 0;

@@ -114,14 +114,19 @@ def check_lp(got: np.ndarray, want: np.ndarray, st: ParityStats, ctx: str):
 
 def compare(w, gpu_out, seed: int, step: int, rows: Optional[Sequence[int]] = None,
             k_logprobs: Optional[int] = None, row_ids: Optional[np.ndarray] = None) -> ParityStats:
-    ids, lp_ids, lp = gpu_out
     k = w.k_logprobs if k_logprobs is None else k_logprobs
     rows = list(range(w.B)) if rows is None else list(rows)
     ref = O.sample_batch(w.logits, w.params, w.hist_indptr, w.hist_tokens, seed, step, max(k, 0),
                          row_ids=row_ids, rows=rows)
+    return check_rows(f"{w.name} step {step}", rows, ref, gpu_out, k)
+
+
+def check_rows(name: str, rows: Sequence[int], ref, gpu_out, k: int) -> ParityStats:
+    """Apply the comparison rules to the oracle's RowResults ``ref`` of the rows ``rows``."""
+    ids, lp_ids, lp = gpu_out
     st = ParityStats()
     for b, r in zip(rows, ref):
-        ctx = f"{w.name} row {b} step {step}"
+        ctx = f"{name} row {b}"
         st.rows += 1
         if r.greedy:
             st.greedy_rows += 1

@@ -89,6 +89,55 @@ def test_bad_arguments_are_rejected_on_the_host(over, want):
     assert _call(**over) == want
 
 
+def test_state_size_query():
+    assert sip.sip_state_bytes(256, 4096) == 256 + 1024 + 256 * 4096 * 4
+    assert sip.sip_state_bytes(3, 5) == 256 + 256 + 60
+    for slots, L in [(0, 5), (-1, 5), (4, 0), (sip.SIP_MAX_SLOTS + 1, 4), (4, sip.SIP_MAX_L + 1)]:
+        assert sip.sip_state_bytes(slots, L) == 0
+
+
+def _call_state(**over):
+    """sip_sample_state / sip_state_init / sip_state_assign with fake addresses; every case is
+    rejected on the host."""
+    lib = sip.load()
+    a = dict(logits=0x10000, B=4, V=1000, stride=1000, dtype=sip.SIP_F32, state=0x80000, state_bytes=1 << 20,
+             slots=8, L_max=64, slot_of_row=0x90000, out_ids=0x20000, out_lp_ids=0x30000, out_lp=0x40000, k=5,
+             ws=0x50000, ws_bytes=1 << 22)
+    a.update(over)
+    return lib.sip_sample_state(a["logits"], a["B"], a["V"], a["stride"], a["dtype"], None, a["state"],
+                                a["state_bytes"], a["slots"], a["L_max"], a["slot_of_row"], 0, 0, a["out_ids"],
+                                a["out_lp_ids"], a["out_lp"], a["k"], a["ws"], a["ws_bytes"], None)
+
+
+@pytest.mark.parametrize("over,want", [
+    (dict(slots=0), binding.SIP_ERR_INVALID_ARG),
+    (dict(L_max=0), binding.SIP_ERR_INVALID_ARG),
+    (dict(L_max=binding.SIP_MAX_L + 1), binding.SIP_ERR_INVALID_ARG),
+    (dict(slot_of_row=None), binding.SIP_ERR_INVALID_ARG),
+    (dict(B=0), binding.SIP_ERR_INVALID_ARG),
+    (dict(state=None), binding.SIP_ERR_WORKSPACE),
+    (dict(state=0x80010), binding.SIP_ERR_WORKSPACE),                # not 256-byte aligned
+    (dict(state_bytes=256 + 256 + 8 * 64 * 4 - 1), binding.SIP_ERR_WORKSPACE),
+    (dict(logits=None), binding.SIP_ERR_INVALID_ARG),                # the checks of sip_sample apply too
+    (dict(stride=1001), binding.SIP_ERR_INVALID_ARG),
+    (dict(ws_bytes=4 * 64 * 8 - 1), binding.SIP_ERR_WORKSPACE),      # side tables of B * L_max entries
+])
+def test_bad_state_arguments_are_rejected_on_the_host(over, want):
+    assert _call_state(**over) == want
+
+
+def test_state_init_and_assign_reject_bad_arguments_on_the_host():
+    lib = sip.load()
+    assert lib.sip_state_init(None, 1 << 20, 8, 64, None) == binding.SIP_ERR_WORKSPACE
+    assert lib.sip_state_init(0x80000, 100, 8, 64, None) == binding.SIP_ERR_WORKSPACE
+    assert lib.sip_state_init(0x80000, 1 << 20, 0, 64, None) == binding.SIP_ERR_INVALID_ARG
+    assert lib.sip_state_assign(0x80000, 1 << 20, 8, 64, 2, None, None, None, 0, None) == binding.SIP_ERR_INVALID_ARG
+    assert lib.sip_state_assign(0x80000, 1 << 20, 8, 64, 2, 0x90000, None, None, 5, None) == binding.SIP_ERR_INVALID_ARG
+    assert lib.sip_state_assign(0x80000, 1 << 20, 8, 64, -1, 0x90000, None, None, 0, None) == binding.SIP_ERR_INVALID_ARG
+    assert lib.sip_state_assign(0x80000, 100, 8, 64, 2, 0x90000, None, None, 0, None) == binding.SIP_ERR_WORKSPACE
+    assert lib.sip_state_assign(0x80000, 1 << 20, 8, 64, 0, None, None, None, 0, None) == binding.SIP_OK   # nothing to do
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError):
