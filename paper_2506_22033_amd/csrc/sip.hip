@@ -91,8 +91,7 @@ struct HistSource {
   const int32_t* tokens = nullptr;
   int64_t nnz = 0;                                   // entries the side tables of the workspace are sized for
   const int32_t* slot = nullptr;
-  const int* st_len = nullptr;
-  const unsigned long long* st_tick = nullptr;
+  sip::StateView state{};                            // valid when slot != nullptr
   int L_max = 0, slots = 0;
 };
 
@@ -121,7 +120,11 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
   a.indptr = reinterpret_cast<const long long*>(h.indptr);
   a.tokens = h.tokens;
   a.nnz = h.slot ? (long long)h.slots * h.L_max : ((h.indptr && h.tokens) ? h.nnz : 0);
-  a.slot = h.slot; a.st_len = h.st_len; a.st_tick = h.st_tick; a.L_max = h.L_max; a.slots = h.slots;
+  a.slot = h.slot; a.L_max = h.L_max; a.slots = h.slots;
+  a.st_len = h.state.len; a.st_tokens = h.state.tokens;
+  a.st_tick = h.slot ? &h.state.head->tick : nullptr;
+  a.st_overflow = h.slot ? &h.state.head->overflow : nullptr;
+  a.tick_bias = 0;
   a.seed = seed; a.step = step;
   a.out_ids = out_ids; a.out_lp_ids = out_lp_ids; a.out_lp = out_lp; a.k_lp = k_logprobs;
   char* ws = static_cast<char*>(workspace);
@@ -140,8 +143,13 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
     if (!allow_big_lds(reinterpret_cast<const void*>(kern), dtype == SIP_F32 ? 0 : 1)) return SIP_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3(B), dim3(sip::kExactThreads), dyn, stream, a);
     if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
+    if (h.slot) {
+      hipLaunchKernelGGL(sip::state_tick_kernel, dim3(1), dim3(64), 0, stream, h.state.head);
+      if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
+    }
     return SIP_OK;
   }
+  a.tick_bias = h.slot ? 1 : 0;            // the streaming kernel counts the call, the finishing kernel knows
   auto k_stream = dtype == SIP_F32 ? sip::stream_kernel<SIP_F32> : sip::stream_kernel<SIP_BF16>;
   auto k_final = dtype == SIP_F32 ? sip::final_kernel<SIP_F32> : sip::final_kernel<SIP_BF16>;
   const size_t dyn = std::max(plan.final_lds, 2 * words * sizeof(uint32_t));
@@ -228,18 +236,13 @@ sip_status sip_sample_state(const void* logits, int32_t B, int32_t V, int64_t ro
                             void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!state_shape_ok(slots, L_max) || !slot_of_row || B <= 0) return SIP_ERR_INVALID_ARG;
   if (!state_ok(state, state_bytes, slots, L_max)) return SIP_ERR_WORKSPACE;
-  const sip::StateView v = sip::state_view(state, slots, L_max);
   HistSource h;
-  h.tokens = v.tokens; h.nnz = (int64_t)B * L_max;
-  h.slot = slot_of_row; h.st_len = v.len; h.st_tick = &v.head->tick; h.L_max = L_max; h.slots = slots;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const sip_status st = sample_impl(logits, B, V, row_stride, dtype, params, h, seed, step, out_ids, out_lp_ids,
-                                    out_lp, k_logprobs, workspace, workspace_bytes, stream);
-  if (st != SIP_OK) return st;
-  const int blocks = (B + sip::kStateThreads - 1) / sip::kStateThreads;
-  hipLaunchKernelGGL(sip::state_append_kernel, dim3(blocks), dim3(sip::kStateThreads), 0, stream, v.head, v.len,
-                     v.tokens, slots, L_max, slot_of_row, out_ids, B);
-  return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
+  h.state = sip::state_view(state, slots, L_max);
+  h.tokens = h.state.tokens; h.nnz = (int64_t)B * L_max;
+  h.slot = slot_of_row; h.L_max = L_max; h.slots = slots;
+  // the kernels append the ids to the slots and count the call themselves
+  return sample_impl(logits, B, V, row_stride, dtype, params, h, seed, step, out_ids, out_lp_ids, out_lp,
+                     k_logprobs, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 const char* sip_status_string(sip_status status) {

@@ -47,8 +47,11 @@ struct Args {
   // history is tokens[slot[b] * L_max .. + st_len[slot[b]]); `tokens` then points at the state's
   // token table and nnz = slots * L_max.
   const int* slot;                     // [B]; outside [0, slots): the row has no history
-  const int* st_len;                   // [slots]
-  const unsigned long long* st_tick;   // sampling calls made on the state so far; added to `step`
+  int* st_len;                         // [slots]
+  int* st_tokens;                      // [slots, L_max]: same memory as `tokens`, for the append
+  unsigned long long* st_tick;         // sampling calls made on the state so far; added to `step`
+  unsigned int* st_overflow;           // ids that found their slot full
+  int tick_bias;                       // 1: the streaming kernel has already counted this call in *st_tick
   int L_max, slots;
 };
 
@@ -75,7 +78,21 @@ __device__ __forceinline__ HistRange hist_range(const Args& a, int b) {
 }
 // Philox step of this call.
 __device__ __forceinline__ unsigned long long step_of(const Args& a) {
-  return a.step + (a.st_tick ? *a.st_tick : 0ull);
+  return a.step + (a.st_tick ? *a.st_tick - (unsigned long long)a.tick_bias : 0ull);
+}
+// Row b's sampled id joins the history of its slot.  For one thread of the row's workgroup, once
+// out_ids[b] is written and visible to it.  Nobody else reads or writes this slot during the call
+// (the slots of a call are distinct).
+__device__ __forceinline__ void state_append_row(const Args& a, int b) {
+  const int s = a.slot[b];
+  if (s < 0 || s >= a.slots) return;
+  const int n = a.st_len[s];
+  if (n >= 0 && n < a.L_max) {
+    a.st_tokens[(size_t)s * (size_t)a.L_max + n] = a.out_ids[b];
+    a.st_len[s] = n + 1;
+  } else {
+    atomicAdd(a.st_overflow, 1u);
+  }
 }
 
 // A row is cut into S chunks of whole units of `unit` elements (what one wave reads with one

@@ -544,6 +544,10 @@ __global__ __launch_bounds__(kExactThreads) void exact_kernel(Args a) {
   __shared__ ExactShared sh;
   exact_row<DT>(a, blockIdx.x, dyn, sh);
   if (threadIdx.x == 0) a.row_path[blockIdx.x] = 14;     // 14: shape outside the single-pass kernels
+  if (a.slot) {                                          // device-resident history: the row's id joins it
+    __syncthreads();
+    if (threadIdx.x == 0) state_append_row(a, blockIdx.x);
+  }
 }
 
 }  // namespace sip

@@ -1020,6 +1020,10 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
 #else
   if (threadIdx.x == 0) a.row_path[b] = code ? code : how;
 #endif
+  if (a.slot) {                                  // device-resident history: the row's id joins it
+    __syncthreads();
+    if (threadIdx.x == 0) state_append_row(a, b);
+  }
 }
 
 // Draw over the whole row: for a row without any filter (plain temperature sampling), or, with

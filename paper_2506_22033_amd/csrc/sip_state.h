@@ -72,24 +72,9 @@ __global__ __launch_bounds__(kStateThreads) void state_assign_kernel(StateHeader
   }
 }
 
-// After the sampling kernels of a call: row b's id goes to the end of its slot's history, and the
-// call counter moves on.  The slots named by one call are distinct, so no two threads write the
-// same slot.
-__global__ __launch_bounds__(kStateThreads) void state_append_kernel(StateHeader* head, int* len, int* tokens,
-                                                                      int slots, int L_max, const int* slot,
-                                                                      const int* out_ids, int B) {
-  const int b = blockIdx.x * kStateThreads + threadIdx.x;
-  if (b == 0) head->tick += 1;
-  if (b >= B) return;
-  const int s = slot[b];
-  if (s < 0 || s >= slots) return;
-  const int n = len[s];
-  if (n >= 0 && n < L_max) {
-    tokens[(size_t)s * (size_t)L_max + n] = out_ids[b];
-    len[s] = n + 1;
-  } else {
-    atomicAdd(&head->overflow, 1u);
-  }
+// A call on a shape that the single-pass kernels do not serve is counted after its one kernel.
+__global__ void state_tick_kernel(StateHeader* head) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) head->tick += 1;
 }
 
 }  // namespace sip

@@ -150,6 +150,9 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   // Workgroups are handed to the 8 XCDs round-robin by their id.  The chunks of one row read
   // the same sample, so they are renumbered to land on the same XCD (and its L2): id i works
   // on logical chunk (i % 8) * (n / 8) + i / 8 when n, the grid size, is a multiple of 8.
+  // Device-resident history: this call is counted here, before the finishing kernel (which runs
+  // after this one and knows that it has been counted) reads the counter.
+  if (a.tick_bias && blockIdx.x == 0 && tid == 0) *a.st_tick += 1ull;
   int wg = blockIdx.x;
   if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   const int b = wg / a.S, ch = wg - b * a.S;
