@@ -135,7 +135,8 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
  *   byte 0    uint64  tick      sampling calls made on the state since sip_state_init()
  *   byte 8    uint32  overflow  ids that found their slot full, plus prompts cut to L_max
  *   byte 256  int32   len[slots]
- *   byte 256 + round_up(4 * slots, 256)   int32 tokens[slots][L_max]
+ *   byte 256 + round_up(4 * slots, 256)       int32 for the library's own use [slots]
+ *   byte 256 + 2 * round_up(4 * slots, 256)   int32 tokens[slots][L_max]
  * Calls that touch one state must be ordered (same stream, or events between streams).
  */
 

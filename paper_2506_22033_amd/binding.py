@@ -258,5 +258,6 @@ def state_views(state: torch.Tensor, slots: int, L_max: int):
     tick = state[0:8].view(torch.int64)
     overflow = state[8:12].view(torch.int32)
     length = state[256:256 + 4 * slots].view(torch.int32)
-    tokens = state[256 + len_bytes:256 + len_bytes + 4 * slots * L_max].view(torch.int32).view(slots, L_max)
+    base = 256 + 2 * len_bytes
+    tokens = state[base:base + 4 * slots * L_max].view(torch.int32).view(slots, L_max)
     return tick, overflow, length, tokens

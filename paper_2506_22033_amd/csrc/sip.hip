@@ -121,7 +121,7 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
   a.tokens = h.tokens;
   a.nnz = h.slot ? (long long)h.slots * h.L_max : ((h.indptr && h.tokens) ? h.nnz : 0);
   a.slot = h.slot; a.L_max = h.L_max; a.slots = h.slots;
-  a.st_len = h.state.len; a.st_tokens = h.state.tokens;
+  a.st_len = h.state.len; a.st_ndist = h.state.ndist; a.st_tokens = h.state.tokens;
   a.st_tick = h.slot ? &h.state.head->tick : nullptr;
   a.st_overflow = h.slot ? &h.state.head->overflow : nullptr;
   a.tick_bias = 0;
@@ -210,7 +210,7 @@ sip_status sip_state_init(void* state, size_t state_bytes, int32_t slots, int32_
   const sip::StateView v = sip::state_view(state, slots, L_max);
   const int blocks = (slots + sip::kStateThreads - 1) / sip::kStateThreads;
   hipLaunchKernelGGL(sip::state_init_kernel, dim3(blocks), dim3(sip::kStateThreads), 0,
-                     static_cast<hipStream_t>(hip_stream), v.head, v.len, slots);
+                     static_cast<hipStream_t>(hip_stream), v.head, v.len, v.ndist, slots);
   return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
 }
 
@@ -224,7 +224,7 @@ sip_status sip_state_assign(void* state, size_t state_bytes, int32_t slots, int3
   if (n == 0) return SIP_OK;
   const sip::StateView v = sip::state_view(state, slots, L_max);
   hipLaunchKernelGGL(sip::state_assign_kernel, dim3(n), dim3(sip::kStateThreads), 0,
-                     static_cast<hipStream_t>(hip_stream), v.head, v.len, v.tokens, slots, L_max, slot_ids,
+                     static_cast<hipStream_t>(hip_stream), v.head, v.len, v.ndist, v.tokens, slots, L_max, slot_ids,
                      reinterpret_cast<const long long*>(indptr), tokens, (long long)nnz);
   return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
 }

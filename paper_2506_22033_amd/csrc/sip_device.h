@@ -48,6 +48,7 @@ struct Args {
   // token table and nnz = slots * L_max.
   const int* slot;                     // [B]; outside [0, slots): the row has no history
   int* st_len;                         // [slots]
+  int* st_ndist;                       // [slots] upper bound on the slot's distinct tokens, -1 = unknown
   int* st_tokens;                      // [slots, L_max]: same memory as `tokens`, for the append
   unsigned long long* st_tick;         // sampling calls made on the state so far; added to `step`
   unsigned int* st_overflow;           // ids that found their slot full
@@ -82,15 +83,21 @@ __device__ __forceinline__ unsigned long long step_of(const Args& a) {
 }
 // Row b's sampled id joins the history of its slot.  For one thread of the row's workgroup, once
 // out_ids[b] is written and visible to it.  Nobody else reads or writes this slot during the call
-// (the slots of a call are distinct).
-__device__ __forceinline__ void state_append_row(const Args& a, int b) {
+// (the slots of a call are distinct).  `ndist`: the distinct tokens the slot held before the
+// append if this call counted them, else -1; either way the stored bound stays a bound, because
+// one more token is at most one more distinct token.
+__device__ __forceinline__ void state_append_row(const Args& a, int b, int ndist) {
   const int s = a.slot[b];
   if (s < 0 || s >= a.slots) return;
   const int n = a.st_len[s];
+  const int old = a.st_ndist[s];
+  const int known = ndist >= 0 ? ndist : old;
   if (n >= 0 && n < a.L_max) {
     a.st_tokens[(size_t)s * (size_t)a.L_max + n] = a.out_ids[b];
     a.st_len[s] = n + 1;
+    a.st_ndist[s] = known >= 0 ? known + 1 : -1;
   } else {
+    a.st_ndist[s] = known;
     atomicAdd(a.st_overflow, 1u);
   }
 }

@@ -62,6 +62,7 @@ struct FastShared {
   int has_pen_out;
   int retry_ok_out;                     // a second, longer list can hold the nucleus (lower bound on its length)
   uint32_t rq_n;                         // candidates found by the second pass
+  int ndist_out;                        // distinct history tokens of the row, -1 while not counted (thread 0 only)
   int bin_k, bin_n, bin_p, bin_low, bin_d;
   uint32_t above_k, above_n;
   uint32_t key_k, key_p, token_key;
@@ -271,6 +272,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       if (ww < wave) slot += t;
       ndist += t;
     }
+    if (tid == 0) fs.ndist_out = (int)ndist;
     if (ndist > (uint32_t)kSideMax) return 4;                                 // uniform
     if (ndist > (uint32_t)(NT * SR)) return kNeedLong;                        // uniform
 #pragma unroll
@@ -934,10 +936,10 @@ __device__ int whole_row_finish(const Args& a, const int b, const RowParams rp, 
 // kernel was measured to slow all of them down (0.6-1 us each).
 template <int DT>
 __device__ __forceinline__ int fast_any(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
-                                        FastShared& fs, const int S, const int cap_w, const long long hist_len) {
+                                        FastShared& fs, const int S, const int cap_w, const long long ndist_ub) {
   constexpr int NT = kFinalThreads;
   int r = kNeedLong;
-  if (hist_len <= 2 * NT) r = fast_row<DT, 8, 2>(a, b, rp, dyn, fs, S, cap_w);
+  if (ndist_ub <= 2 * NT) r = fast_row<DT, 8, 2>(a, b, rp, dyn, fs, S, cap_w);
   if (r == kNeedLong) r = fast_row<DT, 8, 8>(a, b, rp, dyn, fs, S, cap_w);
   if (r == kNeedLong || r == kNeedLongList) r = fast_row<DT, kCandLong, 8>(a, b, rp, dyn, fs, S, cap_w);
   return (r == kNeedLong || r == kNeedLongList) ? 5 : r;
@@ -962,13 +964,21 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   int code = 0;
   const int target = candidate_target(rp, a);
   if (target != 0) {
+    // Upper bound on the row's distinct history tokens, which decides the instantiation that is
+    // tried first: the history's length, or what a device-resident state remembers from the
+    // slot's previous call.
     const HistRange hr = hist_range(a, b);
-    const long long hist_len = hr.hi - hr.lo;
+    long long ndist_ub = hr.hi - hr.lo;
+    if (a.slot && hr.hi > hr.lo) {
+      const int hint = a.st_ndist[a.slot[b]];
+      if (hint >= 0 && hint < ndist_ub) ndist_ub = hint;
+    }
+    if (threadIdx.x == 0) fs.ndist_out = -1;
     // At most two attempts, written as a loop so that the kernel holds one copy of the code.
     int S = a.S, cap_w = a.cap_w;
 #pragma nounroll
     for (int attempt = 0; attempt < 2; ++attempt) {
-      int r = fast_any<DT>(a, b, rp, dynraw, fs, S, cap_w, hist_len);
+      int r = fast_any<DT>(a, b, rp, dynraw, fs, S, cap_w, ndist_ub);
       bool cut_below = false;
       if (attempt == 0 && r == kWholeRowCut) {
         // a nucleus somewhat longer than the list is cheaper to settle from a second list than
@@ -1022,7 +1032,7 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
 #endif
   if (a.slot) {                                  // device-resident history: the row's id joins it
     __syncthreads();
-    if (threadIdx.x == 0) state_append_row(a, b);
+    if (threadIdx.x == 0) state_append_row(a, b, target != 0 ? fs.ndist_out : -1);
   }
 }
 

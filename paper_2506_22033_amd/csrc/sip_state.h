@@ -19,13 +19,14 @@ struct StateHeader {
 struct StateView {
   StateHeader* head;
   int* len;        // [slots]
+  int* ndist;      // [slots] upper bound on the distinct tokens of the slot's history, -1 = unknown
   int* tokens;     // [slots, L_max]
   size_t total;
 };
 
 inline size_t state_len_bytes(int slots) { return ((size_t)slots * sizeof(int) + 255) / 256 * 256; }
 inline size_t state_total(int slots, int L_max) {
-  return kStateHeaderBytes + state_len_bytes(slots) + (size_t)slots * (size_t)L_max * sizeof(int);
+  return kStateHeaderBytes + 2 * state_len_bytes(slots) + (size_t)slots * (size_t)L_max * sizeof(int);
 }
 inline StateView state_view(void* base, int slots, int L_max) {
   StateView v;
@@ -33,7 +34,8 @@ inline StateView state_view(void* base, int slots, int L_max) {
   const size_t len_bytes = state_len_bytes(slots);
   v.head = reinterpret_cast<StateHeader*>(p);
   v.len = reinterpret_cast<int*>(p + kStateHeaderBytes);
-  v.tokens = reinterpret_cast<int*>(p + kStateHeaderBytes + len_bytes);
+  v.ndist = reinterpret_cast<int*>(p + kStateHeaderBytes + len_bytes);
+  v.tokens = reinterpret_cast<int*>(p + kStateHeaderBytes + 2 * len_bytes);
   v.total = state_total(slots, L_max);
   return v;
 }
@@ -42,16 +44,16 @@ constexpr int kStateThreads = 256;
 
 // Header and every slot's length to zero.  A kernel rather than a memset so that the call can be
 // recorded into a graph like the others.
-__global__ __launch_bounds__(kStateThreads) void state_init_kernel(StateHeader* head, int* len, int slots) {
+__global__ __launch_bounds__(kStateThreads) void state_init_kernel(StateHeader* head, int* len, int* ndist, int slots) {
   const int i = blockIdx.x * kStateThreads + threadIdx.x;
   if (i == 0) { head->tick = 0; head->overflow = 0; }
-  if (i < slots) len[i] = 0;
+  if (i < slots) { len[i] = 0; ndist[i] = 0; }
 }
 
 // One workgroup per (slot, prompt) pair: the slot's history becomes the prompt (its first L_max
 // tokens).  Pairs whose slot is outside [0, slots) are skipped.
-__global__ __launch_bounds__(kStateThreads) void state_assign_kernel(StateHeader* head, int* len, int* tokens,
-                                                                      int slots, int L_max, const int* slot_ids,
+__global__ __launch_bounds__(kStateThreads) void state_assign_kernel(StateHeader* head, int* len, int* ndist,
+                                                                      int* tokens, int slots, int L_max, const int* slot_ids,
                                                                       const long long* indptr, const int* src,
                                                                       long long src_nnz) {
   const int s = slot_ids[blockIdx.x];
@@ -68,6 +70,7 @@ __global__ __launch_bounds__(kStateThreads) void state_assign_kernel(StateHeader
   for (int i = threadIdx.x; i < keep; i += kStateThreads) dst[i] = src[lo + i];
   if (threadIdx.x == 0) {
     len[s] = keep;
+    ndist[s] = keep == 0 ? 0 : -1;                 // a prompt's distinct tokens are not counted here
     if (n > (long long)L_max) atomicAdd(&head->overflow, 1u);
   }
 }

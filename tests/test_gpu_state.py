@@ -106,6 +106,13 @@ def _decode(name, V, B, slots, L_max, slot_of_row, prompts, T, seed, bf16=False,
     assert np.array_equal(length, ost.length)
     for s in range(slots):
         assert np.array_equal(tokens[s, :length[s]], ost.history(s)), f"{name}: slot {s}"
+    # the library's own per-slot figure (an upper bound on the slot's distinct tokens, or -1) must
+    # never be too small: it decides which code path is tried first
+    lb = (4 * slots + 255) // 256 * 256
+    hint = dst.buf[256 + lb:256 + lb + 4 * slots].view(torch.int32).cpu().numpy()
+    for s in range(slots):
+        h = ost.history(s)
+        assert hint[s] == -1 or hint[s] >= len(np.unique(h[(h >= 0) & (h < V)])), f"{name}: slot {s} hint {hint[s]}"
     print(f"[state] {name}: {stats.rows} rows, paths {paths}, flagged={stats.flagged} "
           f"mismatch={stats.flagged_mismatch} overflow={ovf} max|dlogprob|={stats.max_lp_err:.2e}")
     return stats
