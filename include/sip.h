@@ -43,6 +43,7 @@ typedef enum {
 
 #define SIP_MAX_V (1 << 19)        /* largest vocabulary the kernels support            */
 #define SIP_MAX_K_LOGPROBS 64      /* largest k_logprobs                                */
+#define SIP_MAX_SHARDS 8           /* most vocabulary shards sip_sample_sharded() takes */
 #define SIP_MAX_SLOTS (1 << 20)    /* most slots a sampler state can have               */
 #define SIP_MAX_L (1 << 17)        /* longest history a slot of a sampler state can hold */
 
@@ -116,6 +117,35 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
                       uint64_t seed, uint64_t step,
                       int32_t* out_ids, int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * ---- Vocabulary-sharded logits ---------------------------------------------------------------
+ * With tensor parallelism of degree t the last pipeline stage's workers each hold B x V/t logits
+ * (Sec. 5.1 (3), "pipelined integration": the paper's sampler puts the t pieces side by side
+ * instead of gathering them on every worker).  sip_sample_sharded() takes the t pieces where they
+ * are -- t base pointers, no concatenated copy: row b of the call is piece 0's row b, then piece
+ * 1's, ..., so vocabulary id v lives in piece v / V_shard at column v % V_shard, and V = t * V_shard.
+ * The result is defined as that of sip_sample() on the concatenated matrix (log-probabilities may
+ * differ in the last bits: partial sums are formed per piece).
+ *
+ *  shard_logits  HOST array of t DEVICE pointers, each [B, shard_stride] row-major, 16-byte
+ *                aligned; V_shard * sizeof(element) and shard_stride * sizeof(element) must be
+ *                multiples of 16 bytes (else SIP_ERR_INVALID_ARG); never written.  The array is
+ *                read before the call returns.
+ *  t             1..SIP_MAX_SHARDS.
+ *  workspace     at least sip_workspace_bytes_sharded(...) bytes: it includes room for B whole
+ *                rows, used only by rows that leave the single-pass path (their workgroup puts
+ *                the row together there first) and by shapes the single-pass kernels do not
+ *                serve (V or V_shard below 16384, V above 262144).
+ * Everything else as for sip_sample().
+ */
+size_t sip_workspace_bytes_sharded(int32_t B, int32_t V_shard, int32_t t, sip_dtype dtype, int64_t hist_nnz,
+                                   int32_t k_logprobs);
+sip_status sip_sample_sharded(const void* const* shard_logits, int32_t t, int32_t B, int32_t V_shard,
+                              int64_t shard_stride, sip_dtype dtype, const sip_params* params,
+                              const int64_t* hist_indptr, const int32_t* hist_tokens, int64_t hist_nnz,
+                              uint64_t seed, uint64_t step, int32_t* out_ids, int32_t* out_lp_ids, float* out_lp,
+                              int32_t k_logprobs, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * ---- Device-resident sampler state ---------------------------------------------------------

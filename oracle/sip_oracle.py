@@ -361,3 +361,19 @@ def sample_state(logits: np.ndarray, params: dict, state: DecodeState, slot_of_r
             state.overflow += 1
     state.tick += 1
     return out
+
+
+# ----------------------------------------------------------------------------------
+# Vocabulary-sharded logits (Sec. 5.1 (3), "pipelined integration"): with tensor parallelism of
+# degree t each worker of the last stage emits a B x V/t piece of the logits, and the sampler
+# sees them side by side.  Definition: piece i holds the vocabulary ids [i * V/t, (i+1) * V/t),
+# and sampling the pieces is sampling the matrix they form when put side by side in that order.
+
+def join_shards(shards: Sequence[np.ndarray]) -> np.ndarray:
+    return np.concatenate([np.asarray(x) for x in shards], axis=1)
+
+
+def sample_sharded(shards: Sequence[np.ndarray], params: dict, hist_indptr, hist_tokens, seed: int, step: int,
+                   n_logprobs: int, row_ids: Optional[np.ndarray] = None, rows: Optional[Sequence[int]] = None):
+    return sample_batch(join_shards(shards), params, hist_indptr, hist_tokens, seed, step, n_logprobs,
+                        row_ids=row_ids, rows=rows)

@@ -18,6 +18,7 @@ SIP_OK, SIP_ERR_INVALID_ARG, SIP_ERR_UNSUPPORTED, SIP_ERR_WORKSPACE, SIP_ERR_HIP
 SIP_MAX_V = 1 << 19
 SIP_MAX_K_LOGPROBS = 64
 SIP_MAX_SLOTS = 1 << 20
+SIP_MAX_SHARDS = 8
 SIP_MAX_L = 1 << 17
 
 PARAM_FIELDS = ("temperature", "top_k", "top_p", "min_p", "repetition_penalty",
@@ -56,6 +57,15 @@ def load() -> ctypes.CDLL:
         lib.sip_sample.argtypes = [
             ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int,
             ctypes.POINTER(SipParams), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+            ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        lib.sip_workspace_bytes_sharded.restype = ctypes.c_size_t
+        lib.sip_workspace_bytes_sharded.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
+                                                    ctypes.c_int64, ctypes.c_int32]
+        lib.sip_sample_sharded.restype = ctypes.c_int
+        lib.sip_sample_sharded.argtypes = [
+            ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
+            ctypes.c_int, ctypes.POINTER(SipParams), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
             ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         lib.sip_state_bytes.restype = ctypes.c_size_t
@@ -261,3 +271,55 @@ def state_views(state: torch.Tensor, slots: int, L_max: int):
     base = 256 + 2 * len_bytes
     tokens = state[base:base + 4 * slots * L_max].view(torch.int32).view(slots, L_max)
     return tick, overflow, length, tokens
+
+
+# ---- vocabulary-sharded logits
+
+def sip_workspace_bytes_sharded(B: int, V_shard: int, t: int, dtype: int, hist_nnz: int, k_logprobs: int) -> int:
+    return int(load().sip_workspace_bytes_sharded(B, V_shard, t, dtype, hist_nnz, k_logprobs))
+
+
+def sip_sample_sharded(shards, params: Optional[Dict[str, Optional[torch.Tensor]]],
+                       hist_indptr: Optional[torch.Tensor], hist_tokens: Optional[torch.Tensor],
+                       seed: int, step: int, k_logprobs: int, *,
+                       out_ids: Optional[torch.Tensor] = None, out_lp_ids: Optional[torch.Tensor] = None,
+                       out_lp: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                       V_shard: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None
+                       ) -> Tuple[torch.Tensor, Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """sip_sample on logits that come as ``t`` vocabulary pieces: ``shards`` is a sequence of 2-D
+    device tensors [B, >= V_shard] of one dtype and one row stride."""
+    lib = load()
+    t = len(shards)
+    first = shards[0]
+    for x in shards:
+        if (not x.is_cuda or x.dim() != 2 or x.stride(1) != 1 or x.dtype != first.dtype
+                or x.shape[0] != first.shape[0] or x.stride(0) != first.stride(0)):
+            raise TypeError("shards must be 2-D device tensors with contiguous rows, one dtype, one shape")
+    B = first.shape[0]
+    V_shard = first.shape[1] if V_shard is None else int(V_shard)
+    dt = dtype_code(first)
+    dev = first.device
+    nnz = 0
+    if hist_indptr is not None and hist_tokens is not None:
+        if hist_indptr.dtype != torch.int64 or hist_tokens.dtype != torch.int32 or hist_indptr.numel() != B + 1:
+            raise TypeError("hist_indptr must be int64 with B + 1 entries and hist_tokens int32")
+        nnz = hist_tokens.numel()
+    if out_ids is None:
+        out_ids = torch.empty(B, dtype=torch.int32, device=dev)
+    if k_logprobs >= 0:
+        if out_lp_ids is None:
+            out_lp_ids = torch.empty(B, 1 + k_logprobs, dtype=torch.int32, device=dev)
+        if out_lp is None:
+            out_lp = torch.empty(B, 1 + k_logprobs, dtype=torch.float32, device=dev)
+    if workspace is None:
+        need = sip_workspace_bytes_sharded(B, V_shard, t, dt, nnz, k_logprobs)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    sp = make_params(params, B)
+    table = (ctypes.c_void_p * t)(*[x.data_ptr() for x in shards])
+    status = lib.sip_sample_sharded(table, t, B, V_shard, first.stride(0), dt, ctypes.byref(sp),
+                                    _ptr(hist_indptr) if nnz else None, _ptr(hist_tokens) if nnz else None, nnz,
+                                    seed, step, _ptr(out_ids), _ptr(out_lp_ids), _ptr(out_lp), k_logprobs,
+                                    _ptr(workspace), _nbytes(workspace), _stream_handle(dev, stream))
+    if status != SIP_OK:
+        raise SipError(status)
+    return out_ids, out_lp_ids, out_lp

@@ -28,18 +28,22 @@ struct Plan {
 constexpr int kFastMinV = 16384;
 constexpr int kFastMaxV = 262144;
 
-Plan make_plan(int32_t B, int32_t V, int dtype) {
+// `t` > 0: the logits come in t vocabulary shards of V / t elements (0: one piece).
+Plan make_plan(int32_t B, int32_t V, int dtype, int t = 0) {
   Plan p{};
-  p.fast = V >= kFastMinV && V <= kFastMaxV;
+  const int pieces = t > 0 ? t : 1;
+  const int Vp = V / pieces;                           // elements per piece
+  p.fast = V >= kFastMinV && V <= kFastMaxV && Vp >= kFastMinV && pieces <= sip::kMaxChunks;
   if (!p.fast) return p;
   const int tile = sip::kStreamThreads * sip::kStreamLoads * (dtype == SIP_F32 ? 4 : 8);
-  const int n_tiles = (V + tile - 1) / tile;
+  const int n_tiles = (Vp + tile - 1) / tile * pieces;
   // Chunks per row.  Small batches: as many workgroups as fit on the chip at once (4 per compute
   // unit), so that there is a single, full round.  Large batches: 4, which makes many rounds
   // and lets the per-wave candidate queues (kQueueCap each) add up to 16K entries per row.
   constexpr int kResident = 256 * 4;
   int want = B * 4 <= kResident ? kResident / B : (B * 2 <= kResident ? kResident / B : 4);
   want = std::max(1, std::min({want, sip::kMaxChunks, std::max(1, n_tiles / 2)}));
+  want = std::max(1, want / pieces) * pieces;          // a chunk lies inside one piece: a multiple of their number
   p.S = want;                                          // <= n_tiles / 2: every chunk holds at least two tiles
   p.cap_w = sip::kQueueCap;
   p.nc_cap = sip::kFinalThreads * sip::kCandLong;     // the finishing kernel holds the list in registers
@@ -48,7 +52,7 @@ Plan make_plan(int32_t B, int32_t V, int dtype) {
 }
 
 struct Layout {
-  size_t row_path, side_z, side_c, chunks, cand, total;
+  size_t row_path, side_z, side_c, chunks, cand, gather, total;
 };
 
 thread_local hipEvent_t g_prof[4] = {nullptr, nullptr, nullptr, nullptr};   // one-shot, see sip_profile_kernel_events()
@@ -56,7 +60,7 @@ thread_local hipEvent_t g_prof[4] = {nullptr, nullptr, nullptr, nullptr};   // o
 // Kernels that use more than the default 64 KB of dynamic LDS have to be told so once.
 constexpr int kMaxDynLds = 144 * 1024;
 bool allow_big_lds(const void* kernel, int slot) {
-  static std::atomic<bool> done[4];
+  static std::atomic<bool> done[8];
   if (done[slot].load(std::memory_order_acquire)) return true;
   if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds) != hipSuccess) {
     (void)hipGetLastError();
@@ -70,7 +74,8 @@ bool shape_ok(int32_t B, int32_t V, int dtype, int64_t nnz, int32_t k_lp) {
   return B > 0 && V > 0 && (dtype == SIP_F32 || dtype == SIP_BF16) && nnz >= 0 && k_lp >= -1;
 }
 
-Layout make_layout(int32_t B, const Plan& p, int64_t nnz) {
+// `gather_row_bytes` > 0 (sharded logits): room for B whole rows.
+Layout make_layout(int32_t B, const Plan& p, int64_t nnz, size_t gather_row_bytes = 0) {
   Layout l;
   size_t off = 0;
   l.row_path = off; off += align_up((size_t)B * sizeof(int) + 8 + 64 * 8);   // first, so that callers can find it
@@ -80,6 +85,7 @@ Layout make_layout(int32_t B, const Plan& p, int64_t nnz) {
   if (p.fast) off += align_up((size_t)B * p.S * sizeof(sip::ChunkOut));
   l.cand = off;
   if (p.fast) off += align_up((size_t)B * p.S * sip::kStreamWaves * (size_t)p.cap_w * sizeof(uint2));
+  l.gather = off; off += align_up((size_t)B * gather_row_bytes);
   l.total = off ? off : kAlign;
   return l;
 }
@@ -95,27 +101,55 @@ struct HistSource {
   int L_max = 0, slots = 0;
 };
 
-// Argument checks common to both entry points, workspace carving and the kernel launches.
+// Vocabulary shards of a call (sip_sample_sharded); t == 0: the logits are one matrix.
+struct ShardSource {
+  const void* const* base = nullptr;                 // host array of t device pointers
+  int t = 0, V_shard = 0;
+  int64_t stride = 0;
+};
+
+template <bool SH>
+sip_status launch(const sip::Args& a, int32_t B, int dtype, const Plan& plan, bool state, sip::StateHeader* head,
+                  hipStream_t stream);
+
+// Argument checks common to the entry points, workspace carving and the kernel launches.
 sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_stride, sip_dtype dtype,
                        const sip_params* params, const HistSource& h, uint64_t seed, uint64_t step,
                        int32_t* out_ids, int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs, void* workspace,
-                       size_t workspace_bytes, hipStream_t stream) {
+                       size_t workspace_bytes, hipStream_t stream, const ShardSource& sh = ShardSource{}) {
   if (!shape_ok(B, V, (int)dtype, h.nnz, k_logprobs)) return SIP_ERR_INVALID_ARG;
-  if (!logits || !out_ids || row_stride < V) return SIP_ERR_INVALID_ARG;
+  if (!out_ids) return SIP_ERR_INVALID_ARG;
   if ((k_logprobs >= 0) != (out_lp_ids != nullptr) || (k_logprobs >= 0) != (out_lp != nullptr))
     return SIP_ERR_INVALID_ARG;
   const size_t esz = dtype == SIP_F32 ? 4 : 2;
-  if ((reinterpret_cast<uintptr_t>(logits) & 15u) != 0 || ((size_t)row_stride * esz) % 16 != 0)
-    return SIP_ERR_INVALID_ARG;
+  if (sh.t == 0) {
+    if (!logits || row_stride < V) return SIP_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(logits) & 15u) != 0 || ((size_t)row_stride * esz) % 16 != 0)
+      return SIP_ERR_INVALID_ARG;
+  } else {
+    if (!sh.base || sh.stride < sh.V_shard) return SIP_ERR_INVALID_ARG;
+    if (((size_t)sh.V_shard * esz) % 16 != 0 || ((size_t)sh.stride * esz) % 16 != 0) return SIP_ERR_INVALID_ARG;
+    for (int i = 0; i < sh.t; ++i)
+      if (!sh.base[i] || (reinterpret_cast<uintptr_t>(sh.base[i]) & 15u) != 0) return SIP_ERR_INVALID_ARG;
+  }
   if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return SIP_ERR_UNSUPPORTED;
-  const Plan plan = make_plan(B, V, (int)dtype);
-  const Layout lay = make_layout(B, plan, h.nnz);
+  const Plan plan = make_plan(B, V, (int)dtype, sh.t);
+  const Layout lay = make_layout(B, plan, h.nnz, sh.t ? (size_t)V * esz : 0);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 || workspace_bytes < lay.total)
     return SIP_ERR_WORKSPACE;
 
   sip::Args a;
   a.logits = logits;
   a.B = B; a.V = V; a.row_stride = row_stride;
+  for (int i = 0; i < 8; ++i) a.shard[i] = nullptr;
+  a.t_shards = 1; a.V_shard = V; a.shard_stride = row_stride;
+  if (sh.t) {
+    // whole-row code paths read the row from the workspace, where its workgroup puts it together first
+    a.logits = static_cast<char*>(workspace) + lay.gather;
+    a.row_stride = V;
+    for (int i = 0; i < sh.t; ++i) a.shard[i] = sh.base[i];
+    a.t_shards = sh.t; a.V_shard = sh.V_shard; a.shard_stride = sh.stride;
+  }
   if (params) a.p = *params; else a.p = sip_params{};
   a.indptr = reinterpret_cast<const long long*>(h.indptr);
   a.tokens = h.tokens;
@@ -135,25 +169,35 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
   a.cand = reinterpret_cast<uint2*>(ws + lay.cand);
   a.S = plan.S; a.cap_w = plan.cap_w; a.nc_cap = plan.nc_cap;
 
-  const size_t words = ((size_t)V + 31) / 32;
+  sip::StateHeader* head = h.slot ? h.state.head : nullptr;
+  return sh.t ? launch<true>(a, B, (int)dtype, plan, h.slot != nullptr, head, stream)
+              : launch<false>(a, B, (int)dtype, plan, h.slot != nullptr, head, stream);
+}
+
+template <bool SH>
+sip_status launch(const sip::Args& a_in, int32_t B, int dtype, const Plan& plan, bool state, sip::StateHeader* head,
+                  hipStream_t stream) {
+  sip::Args a = a_in;
+  const size_t words = ((size_t)a.V + 31) / 32;
+  const int slot0 = (SH ? 4 : 0) + (dtype == SIP_F32 ? 0 : 1);
   if (!plan.fast) {
     // every row takes the exact multi-pass path
     const size_t dyn = 2 * words * sizeof(uint32_t);
-    auto kern = dtype == SIP_F32 ? sip::exact_kernel<SIP_F32> : sip::exact_kernel<SIP_BF16>;
-    if (!allow_big_lds(reinterpret_cast<const void*>(kern), dtype == SIP_F32 ? 0 : 1)) return SIP_ERR_HIP;
+    auto kern = dtype == SIP_F32 ? sip::exact_kernel<SIP_F32, SH> : sip::exact_kernel<SIP_BF16, SH>;
+    if (!allow_big_lds(reinterpret_cast<const void*>(kern), slot0)) return SIP_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3(B), dim3(sip::kExactThreads), dyn, stream, a);
     if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
-    if (h.slot) {
-      hipLaunchKernelGGL(sip::state_tick_kernel, dim3(1), dim3(64), 0, stream, h.state.head);
+    if (state) {
+      hipLaunchKernelGGL(sip::state_tick_kernel, dim3(1), dim3(64), 0, stream, head);
       if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
     }
     return SIP_OK;
   }
-  a.tick_bias = h.slot ? 1 : 0;            // the streaming kernel counts the call, the finishing kernel knows
-  auto k_stream = dtype == SIP_F32 ? sip::stream_kernel<SIP_F32> : sip::stream_kernel<SIP_BF16>;
-  auto k_final = dtype == SIP_F32 ? sip::final_kernel<SIP_F32> : sip::final_kernel<SIP_BF16>;
+  a.tick_bias = state ? 1 : 0;             // the streaming kernel counts the call, the finishing kernel knows
+  auto k_stream = dtype == SIP_F32 ? sip::stream_kernel<SIP_F32, SH> : sip::stream_kernel<SIP_BF16, SH>;
+  auto k_final = dtype == SIP_F32 ? sip::final_kernel<SIP_F32, SH> : sip::final_kernel<SIP_BF16, SH>;
   const size_t dyn = std::max(plan.final_lds, 2 * words * sizeof(uint32_t));
-  if (!allow_big_lds(reinterpret_cast<const void*>(k_final), dtype == SIP_F32 ? 2 : 3)) return SIP_ERR_HIP;
+  if (!allow_big_lds(reinterpret_cast<const void*>(k_final), slot0 + 2)) return SIP_ERR_HIP;
   hipEvent_t ev[4];
   for (int i = 0; i < 4; ++i) { ev[i] = g_prof[i]; g_prof[i] = nullptr; }
   if (ev[0] || ev[1])       // the events take the dispatch's own begin / end time stamps
@@ -197,6 +241,30 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
   h.indptr = hist_indptr; h.tokens = hist_tokens; h.nnz = hist_nnz;
   return sample_impl(logits, B, V, row_stride, dtype, params, h, seed, step, out_ids, out_lp_ids, out_lp,
                      k_logprobs, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t sip_workspace_bytes_sharded(int32_t B, int32_t V_shard, int32_t t, sip_dtype dtype, int64_t hist_nnz,
+                                   int32_t k_logprobs) {
+  if (t < 1 || t > SIP_MAX_SHARDS || V_shard <= 0 || (int64_t)V_shard * t > SIP_MAX_V) return 0;
+  const int32_t V = V_shard * t;
+  if (!shape_ok(B, V, (int)dtype, hist_nnz, k_logprobs) || k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
+  return make_layout(B, make_plan(B, V, (int)dtype, t), hist_nnz, (size_t)V * (dtype == SIP_F32 ? 4 : 2)).total;
+}
+
+sip_status sip_sample_sharded(const void* const* shard_logits, int32_t t, int32_t B, int32_t V_shard,
+                              int64_t shard_stride, sip_dtype dtype, const sip_params* params,
+                              const int64_t* hist_indptr, const int32_t* hist_tokens, int64_t hist_nnz,
+                              uint64_t seed, uint64_t step, int32_t* out_ids, int32_t* out_lp_ids, float* out_lp,
+                              int32_t k_logprobs, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (t < 1 || t > SIP_MAX_SHARDS || V_shard <= 0 || !shard_logits) return SIP_ERR_INVALID_ARG;
+  if ((int64_t)V_shard * t > SIP_MAX_V) return SIP_ERR_UNSUPPORTED;
+  if (hist_nnz > 0 && (!hist_indptr || !hist_tokens)) return SIP_ERR_INVALID_ARG;
+  HistSource h;
+  h.indptr = hist_indptr; h.tokens = hist_tokens; h.nnz = hist_nnz;
+  ShardSource sh;
+  sh.base = shard_logits; sh.t = t; sh.V_shard = V_shard; sh.stride = shard_stride;
+  return sample_impl(nullptr, B, V_shard * t, 0, dtype, params, h, seed, step, out_ids, out_lp_ids, out_lp,
+                     k_logprobs, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream), sh);
 }
 
 size_t sip_state_bytes(int32_t slots, int32_t L_max) {

@@ -53,6 +53,12 @@ struct Args {
   unsigned long long* st_tick;         // sampling calls made on the state so far; added to `step`
   unsigned int* st_overflow;           // ids that found their slot full
   int tick_bias;                       // 1: the streaming kernel has already counted this call in *st_tick
+  // Vocabulary-sharded logits (sip_sample_sharded): row b is the concatenation of t_shards pieces of
+  // V_shard elements, piece i at shard[i] + b * shard_stride elements.  `logits` / `row_stride` then
+  // describe the workspace rows that a workgroup gathers its row into before any whole-row access.
+  const void* shard[8];
+  int t_shards, V_shard;
+  long long shard_stride;
   int L_max, slots;
 };
 
@@ -76,6 +82,29 @@ __device__ __forceinline__ HistRange hist_range(const Args& a, int b) {
     h.side = h.lo;
   }
   return h;
+}
+// Base of shard `sh` (uniform or per lane): a chain of selects, because the table lives in the
+// kernel-argument segment and must be indexed with constants.
+__device__ __forceinline__ const char* shard_base(const Args& a, int sh) {
+  const void* p = a.shard[0];
+#pragma unroll
+  for (int i = 1; i < 8; ++i)
+    if (sh == i) p = a.shard[i];
+  return reinterpret_cast<const char*>(p);
+}
+// Gather row b of a sharded call into its workspace row (a.logits / a.row_stride describe those
+// rows), for the code paths that walk a whole row.  Called by all threads of the row's workgroup.
+template <int DT>
+__device__ __attribute__((noinline)) void gather_row(const Args& a, int b) {
+  constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
+  char* dst = const_cast<char*>(reinterpret_cast<const char*>(a.logits)) + (size_t)b * (size_t)a.row_stride * ESZ;
+  const size_t piece = (size_t)a.V_shard * ESZ / 16;                  // 16-byte groups per piece
+  for (int sh = 0; sh < a.t_shards; ++sh) {
+    const uint4* src = reinterpret_cast<const uint4*>(shard_base(a, sh) + (size_t)b * (size_t)a.shard_stride * ESZ);
+    uint4* d = reinterpret_cast<uint4*>(dst) + (size_t)sh * piece;
+    for (size_t i = threadIdx.x; i < piece; i += blockDim.x) d[i] = src[i];
+  }
+  __syncthreads();
 }
 // Philox step of this call.
 __device__ __forceinline__ unsigned long long step_of(const Args& a) {

@@ -538,10 +538,11 @@ __device__ __attribute__((noinline)) void exact_row(const Args& a, const int b, 
   }
 }
 
-template <int DT>
+template <int DT, bool SH>
 __global__ __launch_bounds__(kExactThreads) void exact_kernel(Args a) {
   extern __shared__ uint32_t dyn[];
   __shared__ ExactShared sh;
+  if (SH) gather_row<DT>(a, blockIdx.x);                  // sharded logits: the row is put together first
   exact_row<DT>(a, blockIdx.x, dyn, sh);
   if (threadIdx.x == 0) a.row_path[blockIdx.x] = 14;     // 14: shape outside the single-pass kernels
   if (a.slot) {                                          // device-resident history: the row's id joins it

@@ -111,7 +111,7 @@ __device__ __forceinline__ float load_elem(const char* row, int v) {
 // smallest one that fits.  Returns 1 (finished), kNeedLong / kNeedLongList (the row does not fit
 // SR / CR entries per thread) or a reason code > 1; outputs written before a failure are overwritten
 // by the path that takes the row over.
-template <int DT, int CR, int SR>
+template <int DT, int CR, int SR, bool SH>
 __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
                                         FastShared& fs, const int S, const int cap_w) {
   constexpr int NT = kFinalThreads;
@@ -146,7 +146,14 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     fs.key_p = 0xFFFFFFFFu; fs.n_memb = 0; fs.n_memb2 = 0; fs.n_memb3 = 0; fs.n_top = 0;
     fs.token = 0x7FFFFFFF; fs.key_k = 0; fs.s1_part = 0;
   }
-  if (tid <= S) fs.cbeg[tid] = chunk_begin(tid, V, S, kWave * (DT == SIP_F32 ? 4 : 8));
+  if (tid <= S) {
+    int cb = chunk_begin(tid, V, S, kWave * (DT == SIP_F32 ? 4 : 8));
+    if (SH && S == a.S) {                       // first attempt on sharded logits: chunks lie inside the shards
+      const int S_sh = S / a.t_shards, sh = tid / S_sh;
+      cb = sh * a.V_shard + chunk_begin(tid - sh * S_sh, a.V_shard, S_sh, kWave * (DT == SIP_F32 ? 4 : 8));
+    }
+    fs.cbeg[tid] = cb;
+  }
   if (tid < S) {
     const ChunkOut co = a.chunks[(size_t)b * a.S + tid];
     fs.Tc[tid] = co.Tc; fs.R[tid] = co.R; fs.bulk[tid] = co.bulk;
@@ -303,7 +310,17 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   }
 #pragma unroll
   for (int r = 0; r < SR; ++r)
-    if (idx[CR + r] != kNoIdx) raw[r] = load_elem<DT>(row, (int)idx[CR + r]);
+    if (idx[CR + r] != kNoIdx) {
+      if (!SH) {
+        raw[r] = load_elem<DT>(row, (int)idx[CR + r]);
+      } else {                                  // the token's shard, then its place inside it
+        const int v = (int)idx[CR + r];
+        int sh = min((int)((float)v * (1.0f / (float)a.V_shard)), a.t_shards - 1);
+        sh += (v >= (sh + 1) * a.V_shard) - (v < sh * a.V_shard);
+        raw[r] = load_elem<DT>(shard_base(a, sh) + (size_t)b * (size_t)a.shard_stride * (DT == SIP_F32 ? 4 : 2),
+                               v - sh * a.V_shard);
+      }
+    }
   // ---- (3) multiplicities of the history tokens
   if (has_pen && rp.phi != 0.0f) {
     auto count = [&](int t) {
@@ -364,6 +381,10 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
         int c = min((int)((float)v * per_elem), S - 1);
         const int lo_c = fs.cbeg[c], hi_c = fs.cbeg[c + 1];
         c += (v >= hi_c) - (v < lo_c);
+        if (SH) {                               // chunk sizes start over at every shard: make sure
+          while (c + 1 < S && v >= fs.cbeg[c + 1]) ++c;
+          while (c > 0 && v < fs.cbeg[c]) --c;
+        }
         mult[r] = cnt[r * NT + tid];
         ref[r].Tc = fs.Tc[c]; ref[r].c = c_row; ref[r].r0 = fs.r0[c]; ref[r].R = fs.R[c];
       }
@@ -934,18 +955,18 @@ __device__ int whole_row_finish(const Args& a, const int b, const RowParams rp, 
 // the number of distinct tokens; a variant that turns out too small says so early and the next
 // one starts over.  Three variants, one after the other: every further instantiation in this
 // kernel was measured to slow all of them down (0.6-1 us each).
-template <int DT>
+template <int DT, bool SH>
 __device__ __forceinline__ int fast_any(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
                                         FastShared& fs, const int S, const int cap_w, const long long ndist_ub) {
   constexpr int NT = kFinalThreads;
   int r = kNeedLong;
-  if (ndist_ub <= 2 * NT) r = fast_row<DT, 8, 2>(a, b, rp, dyn, fs, S, cap_w);
-  if (r == kNeedLong) r = fast_row<DT, 8, 8>(a, b, rp, dyn, fs, S, cap_w);
-  if (r == kNeedLong || r == kNeedLongList) r = fast_row<DT, kCandLong, 8>(a, b, rp, dyn, fs, S, cap_w);
+  if (ndist_ub <= 2 * NT) r = fast_row<DT, 8, 2, SH>(a, b, rp, dyn, fs, S, cap_w);
+  if (r == kNeedLong) r = fast_row<DT, 8, 8, SH>(a, b, rp, dyn, fs, S, cap_w);
+  if (r == kNeedLong || r == kNeedLongList) r = fast_row<DT, kCandLong, 8, SH>(a, b, rp, dyn, fs, S, cap_w);
   return (r == kNeedLong || r == kNeedLongList) ? 5 : r;
 }
 
-template <int DT>
+template <int DT, bool SH>
 __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   // The arguments are read where they are used, straight from the kernel-argument segment
   // (the struct is the only parameter, so it starts at offset 0), instead of being held in
@@ -962,6 +983,7 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   const RowParams rp = load_row_params(a, b);
   int how = 2;                                   // 2: not eligible for the single-pass path
   int code = 0;
+  bool gathered = false;                         // sharded logits: the row has been put together in the workspace
   const int target = candidate_target(rp, a);
   if (target != 0) {
     // Upper bound on the row's distinct history tokens, which decides the instantiation that is
@@ -978,7 +1000,7 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
     int S = a.S, cap_w = a.cap_w;
 #pragma nounroll
     for (int attempt = 0; attempt < 2; ++attempt) {
-      int r = fast_any<DT>(a, b, rp, dynraw, fs, S, cap_w, ndist_ub);
+      int r = fast_any<DT, SH>(a, b, rp, dynraw, fs, S, cap_w, ndist_ub);
       bool cut_below = false;
       if (attempt == 0 && r == kWholeRowCut) {
         // a nucleus somewhat longer than the list is cheaper to settle from a second list than
@@ -1006,6 +1028,7 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
         if (r != 8) t_new = zt - 1.0e-5f * fabsf(zt) - 1.0e-30f;
       }
       if (!(t_new < t_old)) break;
+      if (SH && !gathered) { gather_row<DT>(a, b); gathered = true; }
       restream_row<DT>(a, b, rp, t_new, fs);
       if (cut_below && fs.rq_n > (uint32_t)(kFinalThreads * kCandLong)) {
         // the second list does not fit either: the first attempt's tables are untouched, go on from them
@@ -1017,11 +1040,13 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   }
   if (how == kWholeRowCut || how == kWholeRow) {
     // rows that are finished over the whole row: nucleus cut below the list, or no filter at all
+    if (SH && !gathered) { gather_row<DT>(a, b); gathered = true; }
     how = whole_row_finish<DT>(a, b, rp, dynraw, fs, how == kWholeRowCut);
     code = how == 1 ? 16 : 0;                    // 16: finished over the whole row by this workgroup
   }
   if (how != 1) {
     __syncthreads();
+    if (SH && !gathered) { gather_row<DT>(a, b); gathered = true; }
     exact_row<DT>(a, b, reinterpret_cast<uint32_t*>(dynraw), ex);
   }
 #ifdef SIP_TIMING

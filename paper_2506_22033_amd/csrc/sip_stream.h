@@ -125,7 +125,7 @@ __device__ __forceinline__ unsigned long long bulk_units(float acc) {
 #define SIP_SMARK(i) do { } while (0)
 #endif
 
-template <int DT>
+template <int DT, bool SH>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   constexpr int EPL = (DT == SIP_F32) ? 4 : 8;      // elements per 16-byte load
   constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
@@ -160,10 +160,19 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   const int target = candidate_target(rp, a);
   if (target == 0) return;
   const int V = a.V;
-  const int c0 = chunk_begin(ch, V, a.S, kWave * EPL);
-  const int c1 = chunk_begin(ch + 1, V, a.S, kWave * EPL);
+  // SH (vocabulary-sharded logits): the row's chunks are dealt out to the shards, S / t_shards
+  // each, and a chunk lies inside its shard; c0, c1 and every element index below are then
+  // relative to the shard, `ibase` being the shard's first vocabulary id.
+  const int S_sh = SH ? a.S / a.t_shards : a.S;
+  const int sh = SH ? ch / S_sh : 0;
+  const int lc = SH ? ch - sh * S_sh : ch;
+  const int Vl = SH ? a.V_shard : V;
+  const uint32_t ibase = SH ? (uint32_t)(sh * Vl) : 0u;
+  const int c0 = chunk_begin(lc, Vl, S_sh, kWave * EPL);
+  const int c1 = chunk_begin(lc + 1, Vl, S_sh, kWave * EPL);
   if (c0 >= c1) return;                              // host guarantees every chunk is non-empty
-  const char* row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * ESZ;
+  const char* row = SH ? shard_base(a, sh) + (size_t)b * (size_t)a.shard_stride * ESZ
+                       : reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * ESZ;
 
   // Loads are unconditional (a select on the loaded value would make the wave wait for it at
   // once): lanes past the end of the chunk re-read its last 16 bytes and `process` discards
@@ -208,8 +217,19 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
 #pragma unroll
   for (int j = 0; j < SLOADS; ++j) {
     const int sb = j * kStreamWaves + wave;
-    const int e0 = (int)(((long long)sb * V / NSB) / (kWave * EPL)) * (kWave * EPL) + lane * EPL;
-    smp[j] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);      // e0 + EPL <= V since V >= 16384
+    if (!SH) {
+      const int e0 = (int)(((long long)sb * V / NSB) / (kWave * EPL)) * (kWave * EPL) + lane * EPL;
+      smp[j] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);    // e0 + EPL <= V since V >= 16384
+    } else {
+      // the same NSB blocks for every chunk of the row, dealt out to the shards in order and
+      // spread evenly inside each (V_shard >= 16384 as well, so a block fits)
+      const int ssh = sb * a.t_shards / NSB;
+      const int first = (ssh * NSB + a.t_shards - 1) / a.t_shards;          // first block of that shard
+      const int nb = ((ssh + 1) * NSB + a.t_shards - 1) / a.t_shards - first;
+      const int e0 = (int)(((long long)(sb - first) * Vl / nb) / (kWave * EPL)) * (kWave * EPL) + lane * EPL;
+      const char* srow = shard_base(a, ssh) + (size_t)b * (size_t)a.shard_stride * ESZ;
+      smp[j] = *reinterpret_cast<const uint4*>(srow + (size_t)e0 * ESZ);
+    }
   }
   for (int i = tid; i < kSampleBins / 2; i += kStreamThreads) hist[i] = 0;
   if (tid < 32) sub_hist[tid] = 0;
@@ -375,7 +395,11 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   SIP_SMARK(4);
   // the queue goes out to the wave's segment in one burst (no global stores inside the loop:
   // they would force every wait on a tile load to drain the whole memory queue)
-  for (uint32_t i = lane; i < min(qn, min(cap, (uint32_t)kQueueCap)); i += kWave) seg[i] = queue[i];
+  for (uint32_t i = lane; i < min(qn, min(cap, (uint32_t)kQueueCap)); i += kWave) {
+    uint2 q = queue[i];
+    if (SH) q.y += ibase;                            // vocabulary id from the index inside the shard
+    seg[i] = q;
+  }
 
   // ---- chunk summary
   const unsigned long long wsum = dpp_scan_add_u64(bulk_units(acc));      // integer from here on

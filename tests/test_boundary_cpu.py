@@ -138,6 +138,44 @@ def test_state_init_and_assign_reject_bad_arguments_on_the_host():
     assert lib.sip_state_assign(0x80000, 1 << 20, 8, 64, 0, None, None, None, 0, None) == binding.SIP_OK   # nothing to do
 
 
+def _call_sharded(**over):
+    lib = sip.load()
+    a = dict(ptrs=[0x10000, 0x20000], t=2, B=4, V_shard=20000, stride=20000, dtype=sip.SIP_F32, nnz=0,
+             out_ids=0x30000, out_lp_ids=0x40000, out_lp=0x50000, k=5, ws=0x60000, ws_bytes=1 << 30)
+    a.update(over)
+    table = None if a["ptrs"] is None else (ctypes.c_void_p * len(a["ptrs"]))(*a["ptrs"])
+    return lib.sip_sample_sharded(table, a["t"], a["B"], a["V_shard"], a["stride"], a["dtype"], None, None, None,
+                                  a["nnz"], 0, 0, a["out_ids"], a["out_lp_ids"], a["out_lp"], a["k"], a["ws"],
+                                  a["ws_bytes"], None)
+
+
+@pytest.mark.parametrize("over,want", [
+    (dict(t=0), binding.SIP_ERR_INVALID_ARG),
+    (dict(t=binding.SIP_MAX_SHARDS + 1, ptrs=[0x10000] * 9), binding.SIP_ERR_INVALID_ARG),
+    (dict(ptrs=None), binding.SIP_ERR_INVALID_ARG),
+    (dict(ptrs=[0x10000, None]), binding.SIP_ERR_INVALID_ARG),
+    (dict(ptrs=[0x10000, 0x20004]), binding.SIP_ERR_INVALID_ARG),          # piece not 16-byte aligned
+    (dict(V_shard=20001, stride=20004), binding.SIP_ERR_INVALID_ARG),       # pieces must be whole 16-byte groups
+    (dict(stride=19996), binding.SIP_ERR_INVALID_ARG),                      # stride < V_shard
+    (dict(stride=20002), binding.SIP_ERR_INVALID_ARG),
+    (dict(V_shard=0), binding.SIP_ERR_INVALID_ARG),
+    (dict(B=0), binding.SIP_ERR_INVALID_ARG),
+    (dict(V_shard=binding.SIP_MAX_V // 2 + 8, stride=binding.SIP_MAX_V // 2 + 8), binding.SIP_ERR_UNSUPPORTED),
+    (dict(ws_bytes=4 * 40000 * 4 - 1), binding.SIP_ERR_WORKSPACE),          # room for B whole rows
+    (dict(nnz=3), binding.SIP_ERR_INVALID_ARG),
+])
+def test_bad_sharded_arguments_are_rejected_on_the_host(over, want):
+    assert _call_sharded(**over) == want
+
+
+def test_sharded_workspace_query():
+    two = sip.sip_workspace_bytes_sharded(4, 20000, 2, sip.SIP_F32, 0, 5)
+    assert two > 4 * 40000 * 4 and two % 256 == 0                   # holds B whole rows, and more
+    assert sip.sip_workspace_bytes_sharded(4, 20000, 0, sip.SIP_F32, 0, 5) == 0
+    assert sip.sip_workspace_bytes_sharded(4, 20000, 9, sip.SIP_F32, 0, 5) == 0
+    assert sip.sip_workspace_bytes_sharded(4, sip.SIP_MAX_V, 2, sip.SIP_F32, 0, 5) == 0
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError):

@@ -1,0 +1,120 @@
+"""GPU parity of sip_sample_sharded (logits handed over as t vocabulary pieces, Sec. 5.1 (3))
+against the oracle on the pieces put side by side, through the C boundary: shapes that stay on the
+single-pass kernels, rows that leave them (second list, whole-row continuation, exact path: their
+workgroup gathers the row first), shapes that the single-pass kernels do not serve, and the
+benchmark shape against the unsharded call."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_22033_amd as sip
+import workloads
+from oracle import sip_oracle as O
+from tests import sip_harness as H
+from tests.test_gpu_random import _histories, _logits, _params
+
+pytestmark = pytest.mark.gpu
+DEV = H.DEV
+
+
+def _split(logits_dev: torch.Tensor, t: int, V_shard: int, pad: int):
+    """t separate allocations [B, V_shard + pad] (the pad is poisoned: it must never be read as data)."""
+    out = []
+    for i in range(t):
+        if logits_dev.dtype == torch.float32:
+            x = torch.full((logits_dev.shape[0], V_shard + pad), float("nan"), dtype=torch.float32, device=DEV)
+        else:
+            x = torch.full((logits_dev.shape[0], V_shard + pad), float("nan"), dtype=torch.bfloat16, device=DEV)
+        x[:, :V_shard] = logits_dev[:, i * V_shard:(i + 1) * V_shard]
+        out.append(x)
+    return out
+
+
+def _run_sharded(w, t, seed, step, k, pad=0):
+    d = H.to_device(w)
+    V_shard = w.V // t
+    assert V_shard * t == w.V
+    shards = _split(d.logits, t, V_shard, pad)
+    need = sip.sip_workspace_bytes_sharded(w.B, V_shard, t, sip.binding.dtype_code(d.logits),
+                                           0 if d.tokens is None else d.tokens.numel(), k)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    ids, lpi, lp = sip.sip_sample_sharded(shards, d.params, d.indptr, d.tokens, seed, step, k, V_shard=V_shard,
+                                          workspace=ws)
+    torch.cuda.synchronize()
+    path = ws[:4 * w.B].view(torch.int32).cpu().numpy().copy()
+    return (ids.cpu().numpy(), None if lpi is None else lpi.cpu().numpy(), None if lp is None else lp.cpu().numpy()), path
+
+
+CASES = [(0, "gauss", 2, 16384, False), (1, "heavy", 4, 20000, True), (2, "flat", 3, 17000, False),
+         (3, "quantised", 8, 16384, False), (4, "peaked", 8, 19008, True), (5, "sorted", 2, 40000, False),
+         (6, "gauss", 5, 33336, True), (7, "heavy", 1, 50000, False)]
+
+
+@pytest.mark.parametrize("seed,kind,t,V_shard,bf16", CASES)
+def test_sharded_random_configuration(seed, kind, t, V_shard, bf16):
+    rng = np.random.default_rng(2000 + seed)
+    V = t * V_shard
+    B = int(rng.choice([3, 8, 13]))
+    z = _logits(rng, B, V, kind)
+    logits = workloads.f32_to_bf16_bits(z) if bf16 else z
+    k_lp = int(rng.choice([0, 5, 20]))
+    w = H.custom(f"sharded[{seed},{kind},t={t},{'bf16' if bf16 else 'f32'}] B={B} V={V}", logits, _params(rng, B, V),
+                 _histories(rng, B, V, z), k_logprobs=k_lp)
+    st = H.ParityStats()
+    paths = {}
+    for step in (0, 1):
+        out, path = _run_sharded(w, t, 11 + seed, step, k_lp, pad=8 * (seed % 2))
+        st.merge(H.compare(w, out, 11 + seed, step, k_logprobs=k_lp))
+        for c in path.tolist():
+            paths[c] = paths.get(c, 0) + 1
+    print(f"[sharded] {w.name}: row paths {paths} flagged={st.flagged} mismatch={st.flagged_mismatch} "
+          f"max|dlogprob|={st.max_lp_err:.2e}")
+    assert st.rows == 2 * B
+
+
+def test_rows_that_leave_the_single_pass_path_gather_their_row_first():
+    """Plain temperature sampling (whole-row draw), a nucleus far below the list (whole-row cut), a
+    huge top-k (exact path), in one sharded call."""
+    rng = np.random.default_rng(5)
+    t, V_shard, B = 4, 20000, 6
+    V = t * V_shard
+    z = rng.normal(0, 1.0, (B, V)).astype(np.float32)
+    p = {"temperature": np.array([1.0, 1.5, 0.9, 1.0, 0.0, 1.2], np.float32),
+         "top_k": np.array([0, 0, V - 10, 0, 0, 30000], np.int32),
+         "top_p": np.array([1.0, 0.999, 1.0, 0.97, 1.0, 1.0], np.float32),
+         "presence_penalty": np.full(B, 0.4, np.float32)}
+    hs = [rng.integers(0, V, 50).tolist() for _ in range(B)]
+    w = H.custom("sharded leave-the-path", z, p, hs, k_logprobs=5)
+    out, path = _run_sharded(w, t, 3, 0, 5)
+    st = H.compare(w, out, 3, 0)
+    print(f"[sharded] {w.name}: paths {path.tolist()} flagged={st.flagged} max|dlogprob|={st.max_lp_err:.2e}")
+    assert set(path.tolist()) - {1}, "no row left the single-pass path: the test does not test what it says"
+
+
+@pytest.mark.parametrize("t,V_shard,bf16", [(4, 1000, False), (2, 8192, True), (8, 40000, False)])
+def test_shapes_outside_the_single_pass_kernels(t, V_shard, bf16):
+    rng = np.random.default_rng(t * V_shard)
+    B, V = 4, t * V_shard
+    z = _logits(rng, B, V, "gauss")
+    logits = workloads.f32_to_bf16_bits(z) if bf16 else z
+    w = H.custom(f"sharded exact t={t} V_shard={V_shard}", logits, _params(rng, B, V), _histories(rng, B, V, z), 5)
+    out, path = _run_sharded(w, t, 1, 0, 5)
+    H.compare(w, out, 1, 0)
+    assert (path == 14).all()
+
+
+@pytest.mark.parametrize("t", [2, 4, 8])
+def test_benchmark_shape_sharded_equals_unsharded(t):
+    """B=256, V=152064 fp32 as t pieces: same tokens and best-n ids as the unsharded call, logprobs
+    within the library's tolerance of it, all rows on the single-pass path."""
+    w = workloads.make(2)
+    d = H.to_device(w)
+    ids0, lpi0, lp0 = sip.sip_sample(d.logits, d.params, d.indptr, d.tokens, 5, 9, w.k_logprobs, V=w.V)
+    out, path = _run_sharded(w, t, 5, 9, w.k_logprobs)
+    torch.cuda.synchronize()
+    assert np.isin(path, (1, 15, 16)).all()
+    assert np.array_equal(out[0], ids0.cpu().numpy()) and np.array_equal(out[1], lpi0.cpu().numpy())
+    ref = lp0.cpu().numpy().astype(np.float64)
+    assert (np.abs(out[2] - ref) <= 2 * (H.LP_ABS + H.LP_REL * np.abs(ref))).all()
+    st = H.compare(w, out, 5, 9, rows=range(0, w.B, 16))
+    assert st.rows == 16

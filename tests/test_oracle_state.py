@@ -141,3 +141,17 @@ def test_microbatches_on_disjoint_slots_of_one_state_do_not_see_each_other():
     for m in (0, 1):
         for i in range(B):
             assert both.history(m * B + i).tolist() == own[m].history(i).tolist()
+
+
+def test_shards_are_vocabulary_ranges_in_rank_order():
+    # two pieces of two ids each: the largest logit sits in piece 1, column 0 -> vocabulary id 2;
+    # a history token 3 is column 1 of piece 1
+    pieces = [np.array([[0.0, 5.0]], np.float32), np.array([[9.0, 8.5]], np.float32)]
+    greedy = {"temperature": np.zeros(1, np.float32)}
+    assert O.sample_sharded(pieces, greedy, None, None, 0, 0, 0)[0].token == 2
+    pen = dict(greedy, presence_penalty=np.full(1, 1.0, np.float32))
+    r = O.sample_sharded(pieces, pen, np.array([0, 1]), np.array([2], np.int32), 0, 0, 3)[0]
+    assert r.token == 3 and r.top_ids.tolist() == [3, 2, 1]          # 9 - 1 = 8 < 8.5
+    whole = O.sample_batch(np.array([[0.0, 5.0, 9.0, 8.5]], np.float32), pen, np.array([0, 1]),
+                           np.array([2], np.int32), 0, 0, 3)[0]
+    assert whole.token == r.token and whole.logprob == r.logprob
