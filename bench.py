@@ -141,6 +141,43 @@ def decode_on_state(w, d, bufs, sip, dev, stream, args, csr_ws_bytes):
             "stateless_with_host_round_trip_ms_per_step": ms_host, "stateless_steps_timed": n_host}
 
 
+def sharded_leg(w, d, bufs, sip, dev, stream, args):
+    """The same steps with the logits handed over as t vocabulary pieces (separate allocations),
+    as the workers of a tensor-parallel last stage hold them (Sec. 5.1 (3))."""
+    import torch
+    out = {}
+    nnz = 0 if d.tokens is None else d.tokens.numel()
+    dt_code = sip.SIP_F32 if w.dtype == "f32" else sip.SIP_BF16
+    k = w.k_logprobs
+    out_ids = torch.empty(w.B, dtype=torch.int32, device=dev)
+    out_lp_ids = torch.empty(w.B, 1 + k, dtype=torch.int32, device=dev)
+    out_lp = torch.empty(w.B, 1 + k, dtype=torch.float32, device=dev)
+    steps = max(20, args.steps // 2)
+    for t in (2, 4, 8):
+        if w.V % t or (w.V // t * (4 if w.dtype == "f32" else 2)) % 16:
+            continue
+        Vs = w.V // t
+        pieces = [[buf[:, i * Vs:(i + 1) * Vs].contiguous() for i in range(t)] for buf in bufs]
+        ws = torch.empty(sip.sip_workspace_bytes_sharded(w.B, Vs, t, dt_code, nnz, k), dtype=torch.uint8, device=dev)
+        with torch.cuda.stream(stream):
+            def step(i):
+                sip.sip_sample_sharded(pieces[i % len(bufs)], d.params, d.indptr, d.tokens, 0, i, k, out_ids=out_ids,
+                                       out_lp_ids=out_lp_ids, out_lp=out_lp, workspace=ws, V_shard=Vs, stream=stream)
+            for i in range(args.warmup):
+                step(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                step(args.warmup + i)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / steps
+        path = ws[:4 * w.B].view(torch.int32).cpu().numpy()
+        out[f"t={t}"] = {"ms_per_step": ms, "value": w.B / (ms * 1e-3), "steps": steps,
+                         "rows_on_single_pass_path_last_step": int(np.isin(path, (1, 15, 16)).sum())}
+        del pieces, ws
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -249,6 +286,8 @@ def main() -> int:
 
     state_leg = decode_on_state(w, d, bufs, sip, dev, stream, args, ws.numel()) if nnz else None
 
+    shard_leg = sharded_leg(w, d, bufs, sip, dev, stream, args)
+
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -284,6 +323,7 @@ def main() -> int:
                      "rows_on_single_pass_path_last_step": single_pass_rows},
         "cpu_baseline": cpu,
         "decode_on_device_state": state_leg,
+        "vocabulary_sharded_logits": shard_leg,
     }
     print(json.dumps(res))
     return 0

@@ -4,6 +4,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <cmath>
 #include <atomic>
 
 #include "../../include/sip.h"
@@ -43,7 +44,18 @@ Plan make_plan(int32_t B, int32_t V, int dtype, int t = 0) {
   constexpr int kResident = 256 * 4;
   int want = B * 4 <= kResident ? kResident / B : (B * 2 <= kResident ? kResident / B : 4);
   want = std::max(1, std::min({want, sip::kMaxChunks, std::max(1, n_tiles / 2)}));
-  want = std::max(1, want / pieces) * pieces;          // a chunk lies inside one piece: a multiple of their number
+  if (want >= pieces) {
+    want = want / pieces * pieces;                     // a chunk is part of one piece: a multiple of their number
+  } else {
+    // a chunk is several whole pieces: the divisor of their number nearest to `want` (by ratio)
+    int best = pieces;
+    for (int dv = 1; dv <= pieces; ++dv)
+      if (pieces % dv == 0) {
+        const double r0 = std::fabs(std::log((double)best / want)), r1 = std::fabs(std::log((double)dv / want));
+        if (r1 < r0 || (r1 == r0 && dv > best)) best = dv;
+      }
+    want = best;
+  }
   p.S = want;                                          // <= n_tiles / 2: every chunk holds at least two tiles
   p.cap_w = sip::kQueueCap;
   p.nc_cap = sip::kFinalThreads * sip::kCandLong;     // the finishing kernel holds the list in registers

@@ -149,8 +149,12 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   if (tid <= S) {
     int cb = chunk_begin(tid, V, S, kWave * (DT == SIP_F32 ? 4 : 8));
     if (SH && S == a.S) {                       // first attempt on sharded logits: chunks lie inside the shards
-      const int S_sh = S / a.t_shards, sh = tid / S_sh;
-      cb = sh * a.V_shard + chunk_begin(tid - sh * S_sh, a.V_shard, S_sh, kWave * (DT == SIP_F32 ? 4 : 8));
+      if (S >= a.t_shards) {
+        const int S_sh = S / a.t_shards, sh = tid / S_sh;
+        cb = sh * a.V_shard + chunk_begin(tid - sh * S_sh, a.V_shard, S_sh, kWave * (DT == SIP_F32 ? 4 : 8));
+      } else {                                  // a chunk is t_shards / S whole shards
+        cb = tid * (a.t_shards / S) * a.V_shard;
+      }
     }
     fs.cbeg[tid] = cb;
   }

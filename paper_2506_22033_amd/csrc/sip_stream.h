@@ -163,15 +163,19 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   // SH (vocabulary-sharded logits): the row's chunks are dealt out to the shards, S / t_shards
   // each, and a chunk lies inside its shard; c0, c1 and every element index below are then
   // relative to the shard, `ibase` being the shard's first vocabulary id.
-  const int S_sh = SH ? a.S / a.t_shards : a.S;
-  const int sh = SH ? ch / S_sh : 0;
-  const int lc = SH ? ch - sh * S_sh : ch;
+  // With more chunks than shards a chunk is a part of one shard (np = 1 piece); with fewer, it is
+  // np whole shards in a row, streamed one after the other.
+  const bool split = !SH || a.S >= a.t_shards;       // uniform
+  const int S_sh = !SH ? a.S : (split ? a.S / a.t_shards : 1);
+  const int np = (SH && !split) ? a.t_shards / a.S : 1;
+  const int sh = !SH ? 0 : (split ? ch / S_sh : ch * np);
+  const int lc = !SH ? ch : (split ? ch - sh * S_sh : 0);
   const int Vl = SH ? a.V_shard : V;
   const uint32_t ibase = SH ? (uint32_t)(sh * Vl) : 0u;
   const int c0 = chunk_begin(lc, Vl, S_sh, kWave * EPL);
   const int c1 = chunk_begin(lc + 1, Vl, S_sh, kWave * EPL);
   if (c0 >= c1) return;                              // host guarantees every chunk is non-empty
-  const char* row = SH ? shard_base(a, sh) + (size_t)b * (size_t)a.shard_stride * ESZ
+  const char* row = SH ? shard_base(a, sh) + (size_t)b * (size_t)a.shard_stride * ESZ      // (moves on with the pieces)
                        : reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * ESZ;
 
   // Loads are unconditional (a select on the loaded value would make the wave wait for it at
@@ -337,6 +341,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   uint32_t qn = 0;                          // wave-uniform: candidates seen (entries beyond the queue are dropped)
   float acc = 0.0f;                         // this thread's bulk mass, fixed order of additions
 
+  uint32_t ib = ibase;                      // SH: first vocabulary id of the piece being processed
   auto process = [&](const uint4& q, int e0, bool guard) {
     float z[EPL];
     unpack(q, z);
@@ -353,7 +358,8 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
       if (mask) {
         const uint32_t pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
                                       __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-        if (hit && pos < (uint32_t)kQueueCap) queue[pos] = make_uint2(__float_as_uint(z[i]), (uint32_t)(e0 + i));
+        if (hit && pos < (uint32_t)kQueueCap)
+          queue[pos] = make_uint2(__float_as_uint(z[i]), (uint32_t)(e0 + i) + (SH ? ib : 0u));
         qn += (uint32_t)__popcll(mask);
       }
       float e = bulk_term(z[i], ref);
@@ -375,7 +381,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   SIP_SMARK(3);
   // kStreamBufs register buffers in rotation: while one tile is processed the loads of the
   // others are in flight
-  {
+  if (!SH) {
     int tcur = c0;
     bool more = true;
     while (more) {
@@ -391,14 +397,38 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
         }
       }
     }
+  } else {
+    // the same rotation over np pieces: every piece is [c0, c1) of its shard; the requests run
+    // ahead of the processing across the piece boundaries (`row` is what load_tile reads from)
+    int c_pj = 0, tcur = c0;                         // tile being processed
+    int n_pj = 0;                                    // piece of the next tile to request, `tnext` its first element
+    auto roll = [&]() {
+      if (tnext >= c1) {
+        ++n_pj; tnext = c0;
+        if (n_pj < np) row = shard_base(a, sh + n_pj) + (size_t)b * (size_t)a.shard_stride * ESZ;
+      }
+    };
+    roll();
+    bool more = true;
+    while (more) {
+#pragma unroll
+      for (int k = 0; k < kStreamBufs; ++k) {
+        if (c_pj < np) {
+          process_tile(buf[k], tcur);
+          if (n_pj < np) { load_tile(tnext, buf[k]); tnext += TILE; roll(); }
+          tcur += TILE;
+          if (tcur >= c1) { ++c_pj; tcur = c0; ib += (uint32_t)Vl; }
+        } else {
+          more = false;
+        }
+      }
+    }
   }
   SIP_SMARK(4);
   // the queue goes out to the wave's segment in one burst (no global stores inside the loop:
   // they would force every wait on a tile load to drain the whole memory queue)
   for (uint32_t i = lane; i < min(qn, min(cap, (uint32_t)kQueueCap)); i += kWave) {
-    uint2 q = queue[i];
-    if (SH) q.y += ibase;                            // vocabulary id from the index inside the shard
-    seg[i] = q;
+    seg[i] = queue[i];
   }
 
   // ---- chunk summary

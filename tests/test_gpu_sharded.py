@@ -103,6 +103,22 @@ def test_shapes_outside_the_single_pass_kernels(t, V_shard, bf16):
     assert (path == 14).all()
 
 
+@pytest.mark.parametrize("t,V_shard,B,bf16", [(8, 16384, 160, True), (6, 20000, 300, False), (3, 17000, 600, False)])
+def test_large_batches_stream_several_whole_pieces_per_workgroup(t, V_shard, B, bf16):
+    """With fewer chunks per row than pieces (large B) a workgroup streams several pieces one after
+    the other; every 8th row is compared with the oracle."""
+    rng = np.random.default_rng(B)
+    V = t * V_shard
+    z = _logits(rng, B, V, "gauss")
+    logits = workloads.f32_to_bf16_bits(z) if bf16 else z
+    w = H.custom(f"sharded several pieces t={t} B={B}", logits, _params(rng, B, V), _histories(rng, B, V, z), 5)
+    out, path = _run_sharded(w, t, 2, 0, 5)
+    st = H.compare(w, out, 2, 0, rows=range(0, B, 8))
+    codes, cnt = np.unique(path, return_counts=True)
+    print(f"[sharded] {w.name}: row paths {dict(zip(codes.tolist(), cnt.tolist()))} flagged={st.flagged} "
+          f"max|dlogprob|={st.max_lp_err:.2e}")
+
+
 @pytest.mark.parametrize("t", [2, 4, 8])
 def test_benchmark_shape_sharded_equals_unsharded(t):
     """B=256, V=152064 fp32 as t pieces: same tokens and best-n ids as the unsharded call, logprobs
