@@ -157,7 +157,7 @@ def sharded_leg(w, d, bufs, sip, dev, stream, args):
         if w.V % t or (w.V // t * (4 if w.dtype == "f32" else 2)) % 16:
             continue
         Vs = w.V // t
-        pieces = [[buf[:, i * Vs:(i + 1) * Vs].contiguous() for i in range(t)] for buf in bufs]
+        pieces = [sip.ShardTable([buf[:, i * Vs:(i + 1) * Vs].contiguous() for i in range(t)], Vs) for buf in bufs]
         ws = torch.empty(sip.sip_workspace_bytes_sharded(w.B, Vs, t, dt_code, nnz, k), dtype=torch.uint8, device=dev)
         with torch.cuda.stream(stream):
             def step(i):

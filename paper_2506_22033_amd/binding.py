@@ -279,6 +279,26 @@ def sip_workspace_bytes_sharded(B: int, V_shard: int, t: int, dtype: int, hist_n
     return int(load().sip_workspace_bytes_sharded(B, V_shard, t, dtype, hist_nnz, k_logprobs))
 
 
+class ShardTable:
+    """The host array of piece pointers that sip_sample_sharded takes, checked and built once for
+    pieces that are used call after call.  Keeps the tensors alive."""
+
+    def __init__(self, shards, V_shard: Optional[int] = None):
+        first = shards[0]
+        for x in shards:
+            if (not x.is_cuda or x.dim() != 2 or x.stride(1) != 1 or x.dtype != first.dtype
+                    or x.shape[0] != first.shape[0] or x.stride(0) != first.stride(0)):
+                raise TypeError("shards must be 2-D device tensors with contiguous rows, one dtype, one shape")
+        self.tensors = list(shards)
+        self.t = len(shards)
+        self.B = first.shape[0]
+        self.V_shard = first.shape[1] if V_shard is None else int(V_shard)
+        self.stride = first.stride(0)
+        self.dtype = dtype_code(first)
+        self.device = first.device
+        self.table = (ctypes.c_void_p * self.t)(*[x.data_ptr() for x in shards])
+
+
 def sip_sample_sharded(shards, params: Optional[Dict[str, Optional[torch.Tensor]]],
                        hist_indptr: Optional[torch.Tensor], hist_tokens: Optional[torch.Tensor],
                        seed: int, step: int, k_logprobs: int, *,
@@ -287,18 +307,10 @@ def sip_sample_sharded(shards, params: Optional[Dict[str, Optional[torch.Tensor]
                        V_shard: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None
                        ) -> Tuple[torch.Tensor, Optional[torch.Tensor], Optional[torch.Tensor]]:
     """sip_sample on logits that come as ``t`` vocabulary pieces: ``shards`` is a sequence of 2-D
-    device tensors [B, >= V_shard] of one dtype and one row stride."""
+    device tensors [B, >= V_shard] of one dtype and one row stride, or a ShardTable made of them."""
     lib = load()
-    t = len(shards)
-    first = shards[0]
-    for x in shards:
-        if (not x.is_cuda or x.dim() != 2 or x.stride(1) != 1 or x.dtype != first.dtype
-                or x.shape[0] != first.shape[0] or x.stride(0) != first.stride(0)):
-            raise TypeError("shards must be 2-D device tensors with contiguous rows, one dtype, one shape")
-    B = first.shape[0]
-    V_shard = first.shape[1] if V_shard is None else int(V_shard)
-    dt = dtype_code(first)
-    dev = first.device
+    st = shards if isinstance(shards, ShardTable) else ShardTable(shards, V_shard)
+    t, B, V_shard, dt, dev = st.t, st.B, st.V_shard, st.dtype, st.device
     nnz = 0
     if hist_indptr is not None and hist_tokens is not None:
         if hist_indptr.dtype != torch.int64 or hist_tokens.dtype != torch.int32 or hist_indptr.numel() != B + 1:
@@ -315,8 +327,7 @@ def sip_sample_sharded(shards, params: Optional[Dict[str, Optional[torch.Tensor]
         need = sip_workspace_bytes_sharded(B, V_shard, t, dt, nnz, k_logprobs)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     sp = make_params(params, B)
-    table = (ctypes.c_void_p * t)(*[x.data_ptr() for x in shards])
-    status = lib.sip_sample_sharded(table, t, B, V_shard, first.stride(0), dt, ctypes.byref(sp),
+    status = lib.sip_sample_sharded(st.table, t, B, V_shard, st.stride, dt, ctypes.byref(sp),
                                     _ptr(hist_indptr) if nnz else None, _ptr(hist_tokens) if nnz else None, nnz,
                                     seed, step, _ptr(out_ids), _ptr(out_lp_ids), _ptr(out_lp), k_logprobs,
                                     _ptr(workspace), _nbytes(workspace), _stream_handle(dev, stream))

@@ -162,6 +162,14 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
     for (int i = 0; i < sh.t; ++i) a.shard[i] = sh.base[i];
     a.t_shards = sh.t; a.V_shard = sh.V_shard; a.shard_stride = sh.stride;
   }
+  a.inv_V_shard = 1.0f / (float)a.V_shard;
+  {
+    const int epl = dtype == SIP_F32 ? 4 : 8, unit = sip::kWave * epl;
+    const int nsb = sip::kSampleSize / (sip::kStreamThreads * epl) * sip::kStreamWaves;   // sample blocks per row
+    a.smp_bps = (nsb + a.t_shards - 1) / a.t_shards;
+    a.smp_inv = (65536 + a.smp_bps - 1) / a.smp_bps;
+    a.smp_step = a.V_shard / a.smp_bps / unit * unit;
+  }
   if (params) a.p = *params; else a.p = sip_params{};
   a.indptr = reinterpret_cast<const long long*>(h.indptr);
   a.tokens = h.tokens;

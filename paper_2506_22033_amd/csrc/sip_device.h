@@ -59,6 +59,11 @@ struct Args {
   const void* shard[8];
   int t_shards, V_shard;
   long long shard_stride;
+  float inv_V_shard;                   // 1 / V_shard
+  // where the row's sample blocks lie (the streaming kernel's threshold estimate): block sb is the
+  // (sb % smp_bps)-th of shard sb / smp_bps, smp_step elements after the one before it;
+  // smp_inv = ceil(2^16 / smp_bps) turns the division into a multiplication (sb < 64)
+  int smp_bps, smp_inv, smp_step;
   int L_max, slots;
 };
 
@@ -134,10 +139,12 @@ __device__ __forceinline__ void state_append_row(const Args& a, int b, int ndist
 // A row is cut into S chunks of whole units of `unit` elements (what one wave reads with one
 // 16-byte load per lane), the chunk sizes differing by at most one unit.  First element of
 // chunk ch; chunk_begin(S) is V.
+// (32-bit arithmetic on purpose: V <= 2^19 and ch <= 17, and a 64-bit division by S is a long
+// routine on the device.)
 __host__ __device__ inline int chunk_begin(int ch, int V, int S, int unit) {
-  const long long n = ((long long)V + unit - 1) / unit;
-  const long long e = (long long)ch * n / S * unit;
-  return (int)(e < V ? e : V);
+  const unsigned int n = ((unsigned int)V + (unsigned int)unit - 1u) / (unsigned int)unit;
+  const unsigned int e = (unsigned int)ch * n / (unsigned int)S * (unsigned int)unit;
+  return (int)(e < (unsigned int)V ? e : (unsigned int)V);
 }
 
 // ApplyPenalty for one seen token: repetition, then frequency, then presence, one fp32

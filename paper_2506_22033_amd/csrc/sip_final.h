@@ -62,6 +62,7 @@ struct FastShared {
   int has_pen_out;
   int retry_ok_out;                     // a second, longer list can hold the nucleus (lower bound on its length)
   uint32_t rq_n;                         // candidates found by the second pass
+  const char* shard_row[8];             // sharded logits: this row's piece in every shard
   int ndist_out;                        // distinct history tokens of the row, -1 while not counted (thread 0 only)
   int bin_k, bin_n, bin_p, bin_low, bin_d;
   uint32_t above_k, above_n;
@@ -158,6 +159,8 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     }
     fs.cbeg[tid] = cb;
   }
+  if (SH && tid < a.t_shards)
+    fs.shard_row[tid] = shard_base(a, tid) + (size_t)b * (size_t)a.shard_stride * (DT == SIP_F32 ? 4 : 2);
   if (tid < S) {
     const ChunkOut co = a.chunks[(size_t)b * a.S + tid];
     fs.Tc[tid] = co.Tc; fs.R[tid] = co.R; fs.bulk[tid] = co.bulk;
@@ -319,10 +322,9 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
         raw[r] = load_elem<DT>(row, (int)idx[CR + r]);
       } else {                                  // the token's shard, then its place inside it
         const int v = (int)idx[CR + r];
-        int sh = min((int)((float)v * (1.0f / (float)a.V_shard)), a.t_shards - 1);
+        int sh = min((int)((float)v * a.inv_V_shard), a.t_shards - 1);
         sh += (v >= (sh + 1) * a.V_shard) - (v < sh * a.V_shard);
-        raw[r] = load_elem<DT>(shard_base(a, sh) + (size_t)b * (size_t)a.shard_stride * (DT == SIP_F32 ? 4 : 2),
-                               v - sh * a.V_shard);
+        raw[r] = load_elem<DT>(fs.shard_row[sh], v - sh * a.V_shard);
       }
     }
   // ---- (3) multiplicities of the history tokens

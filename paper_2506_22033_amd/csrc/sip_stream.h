@@ -225,12 +225,10 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
       const int e0 = (int)(((long long)sb * V / NSB) / (kWave * EPL)) * (kWave * EPL) + lane * EPL;
       smp[j] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);    // e0 + EPL <= V since V >= 16384
     } else {
-      // the same NSB blocks for every chunk of the row, dealt out to the shards in order and
-      // spread evenly inside each (V_shard >= 16384 as well, so a block fits)
-      const int ssh = sb * a.t_shards / NSB;
-      const int first = (ssh * NSB + a.t_shards - 1) / a.t_shards;          // first block of that shard
-      const int nb = ((ssh + 1) * NSB + a.t_shards - 1) / a.t_shards - first;
-      const int e0 = (int)(((long long)(sb - first) * Vl / nb) / (kWave * EPL)) * (kWave * EPL) + lane * EPL;
+      // the same NSB blocks for every chunk of the row, smp_bps to a shard (the last shard may get
+      // fewer), evenly spread inside it; V_shard >= 16384 as well, so a block fits
+      const int ssh = (sb * a.smp_inv) >> 16;                                // sb / smp_bps
+      const int e0 = (sb - ssh * a.smp_bps) * a.smp_step + lane * EPL;
       const char* srow = shard_base(a, ssh) + (size_t)b * (size_t)a.shard_stride * ESZ;
       smp[j] = *reinterpret_cast<const uint4*>(srow + (size_t)e0 * ESZ);
     }
