@@ -178,6 +178,45 @@ def sharded_leg(w, d, bufs, sip, dev, stream, args):
     return out
 
 
+def handoff_leg(w, d, bufs, sip, dev, stream, args, ws):
+    """Latency of one step as the scheduler sees it -- enqueue, then the ids in host memory -- with
+    the ids published into pinned memory behind a polled ticket, against the usual stream
+    synchronisation plus device-to-host copy."""
+    import torch
+    k = w.k_logprobs
+    out_ids = torch.empty(w.B, dtype=torch.int32, device=dev)
+    out_lp_ids = torch.empty(w.B, 1 + k, dtype=torch.int32, device=dev)
+    out_lp = torch.empty(w.B, 1 + k, dtype=torch.float32, device=dev)
+    host_ids = torch.zeros(w.B, dtype=torch.int32).pin_memory()
+    host_copy = torch.zeros(w.B, dtype=torch.int32).pin_memory()
+    flag = torch.zeros(1, dtype=torch.int64).pin_memory()
+    n = max(20, args.steps // 2)
+    res = {}
+    with torch.cuda.stream(stream):
+        def sample(i):
+            sip.sip_sample(bufs[i % len(bufs)], d.params, d.indptr, d.tokens, 0, i, k, out_ids=out_ids,
+                           out_lp_ids=out_lp_ids, out_lp=out_lp, workspace=ws, V=w.V, stream=stream)
+        for mode in ("ticket", "synchronize_and_copy"):
+            for i in range(10):
+                sample(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(n):
+                sample(i)
+                if mode == "ticket":
+                    sip.sip_publish_ids(out_ids, host_ids, flag, i + 1, stream=stream)
+                    sip.sip_wait_ids(flag, i + 1)
+                else:
+                    host_copy.copy_(out_ids, non_blocking=True)
+                    stream.synchronize()
+            res[mode + "_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / n
+            torch.cuda.synchronize()
+            flag.zero_()
+        res["ids_equal"] = bool((host_ids == host_copy).all())       # both hold the ids of step n - 1
+    res["steps"] = n
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -286,6 +325,7 @@ def main() -> int:
 
     state_leg = decode_on_state(w, d, bufs, sip, dev, stream, args, ws.numel()) if nnz else None
 
+    hand_leg = handoff_leg(w, d, bufs, sip, dev, stream, args, ws)
     shard_leg = sharded_leg(w, d, bufs, sip, dev, stream, args)
 
     if args.calibrate_copy:
@@ -324,6 +364,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "decode_on_device_state": state_leg,
         "vocabulary_sharded_logits": shard_leg,
+        "host_handoff": hand_leg,
     }
     print(json.dumps(res))
     return 0

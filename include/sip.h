@@ -38,7 +38,8 @@ typedef enum {
   SIP_ERR_INVALID_ARG = 1, /* NULL required pointer, non-positive size, misaligned rows, ... */
   SIP_ERR_UNSUPPORTED = 2, /* shape outside what the kernels are built for (see SIP_MAX_*) */
   SIP_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned or smaller than sip_workspace_bytes() */
-  SIP_ERR_HIP = 4          /* a HIP runtime call (kernel launch) failed */
+  SIP_ERR_HIP = 4,         /* a HIP runtime call (kernel launch) failed */
+  SIP_ERR_TIMEOUT = 5      /* sip_wait_ids(): the ticket did not appear in time */
 } sip_status;
 
 #define SIP_MAX_V (1 << 19)        /* largest vocabulary the kernels support            */
@@ -207,6 +208,32 @@ sip_status sip_sample_state(const void* logits, int32_t B, int32_t V, int64_t ro
                             int32_t L_max, const int32_t* slot_of_row, uint64_t seed, uint64_t step,
                             int32_t* out_ids, int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * ---- Hand-off of the ids to the host without a stream synchronisation --------------------------
+ * The scheduler of a pipelined server needs the B ids of a batch as soon as they exist, to send
+ * them back to the first stage (Sec. 5.1: the sampler returns its output asynchronously; Sec. 6
+ * "BIC-O": through a ring of slots that the consumer polls), while the device goes on with the
+ * next batch.  sip_publish_ids(), enqueued after a sampling call on the same stream, copies the
+ * ids into pinned host memory and then stores `ticket` into a host flag; a host thread waits for
+ * the ticket with sip_wait_ids() -- plain loads, no hipStreamSynchronize, no hipMemcpy -- and
+ * finds all B ids in place.  Tickets of successive calls on one flag must increase.
+ *
+ *  ids        device [B]: the out_ids of the sampling call.
+ *  host_ids   [B] and host_flag: pinned host memory that the device can address (hipHostMalloc;
+ *  host_flag  for such memory the host pointer is the device pointer); 4- and 8-byte aligned.
+ *             The caller initialises the flag below its first ticket (say 0) before the first call.
+ * A ring of (host_ids, host_flag) pairs lets several batches be in flight.
+ */
+sip_status sip_publish_ids(const int32_t* ids, int32_t B, int32_t* host_ids, uint64_t* host_flag, uint64_t ticket,
+                           void* hip_stream);
+
+/*
+ * HOST function: spin until *host_flag >= ticket (acquire), at most timeout_ns nanoseconds
+ * (UINT64_MAX: no limit).  SIP_OK: the ids published with that ticket are visible to the calling
+ * thread.  SIP_ERR_TIMEOUT otherwise.  Touches no HIP call.
+ */
+sip_status sip_wait_ids(const uint64_t* host_flag, uint64_t ticket, uint64_t timeout_ns);
 
 /*
  * Profiling aid.  Arms a one-shot hook on the calling host thread: the next sip_sample() call

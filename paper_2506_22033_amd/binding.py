@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsip.so")
 
 SIP_F32, SIP_BF16 = 0, 1
-SIP_OK, SIP_ERR_INVALID_ARG, SIP_ERR_UNSUPPORTED, SIP_ERR_WORKSPACE, SIP_ERR_HIP = range(5)
+SIP_OK, SIP_ERR_INVALID_ARG, SIP_ERR_UNSUPPORTED, SIP_ERR_WORKSPACE, SIP_ERR_HIP, SIP_ERR_TIMEOUT = range(6)
 SIP_MAX_V = 1 << 19
 SIP_MAX_K_LOGPROBS = 64
 SIP_MAX_SLOTS = 1 << 20
@@ -68,6 +68,11 @@ def load() -> ctypes.CDLL:
             ctypes.c_int, ctypes.POINTER(SipParams), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
             ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        lib.sip_publish_ids.restype = ctypes.c_int
+        lib.sip_publish_ids.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_uint64, ctypes.c_void_p]
+        lib.sip_wait_ids.restype = ctypes.c_int
+        lib.sip_wait_ids.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64]
         lib.sip_state_bytes.restype = ctypes.c_size_t
         lib.sip_state_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
         lib.sip_state_init.restype = ctypes.c_int
@@ -334,3 +339,30 @@ def sip_sample_sharded(shards, params: Optional[Dict[str, Optional[torch.Tensor]
     if status != SIP_OK:
         raise SipError(status)
     return out_ids, out_lp_ids, out_lp
+
+
+# ---- hand-off of the ids to the host
+
+def sip_publish_ids(ids: torch.Tensor, host_ids: torch.Tensor, host_flag: torch.Tensor, ticket: int,
+                    stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Enqueue the copy of ``ids`` (device int32 [B]) into ``host_ids`` (pinned int32 [>= B]) followed
+    by the store of ``ticket`` into ``host_flag`` (pinned, one 64-bit word)."""
+    if not ids.is_cuda or ids.dtype != torch.int32:
+        raise TypeError("ids must be a device int32 tensor")
+    if (host_ids.is_cuda or not host_ids.is_pinned() or host_ids.dtype != torch.int32 or host_ids.numel() < ids.numel()
+            or host_flag.is_cuda or not host_flag.is_pinned() or host_flag.element_size() != 8):
+        raise TypeError("host_ids (int32) and host_flag (one 64-bit word) must be pinned host tensors")
+    status = load().sip_publish_ids(_ptr(ids), ids.numel(), _ptr(host_ids), _ptr(host_flag), ticket,
+                                    _stream_handle(ids.device, stream))
+    if status != SIP_OK:
+        raise SipError(status)
+
+
+def sip_wait_ids(host_flag: torch.Tensor, ticket: int, timeout_ns: int = 2 ** 64 - 1) -> bool:
+    """Spin on the host until the flag reaches ``ticket``; False on time-out.  No HIP call."""
+    status = load().sip_wait_ids(_ptr(host_flag), ticket, timeout_ns)
+    if status == SIP_OK:
+        return True
+    if status == SIP_ERR_TIMEOUT:
+        return False
+    raise SipError(status)

@@ -6,11 +6,13 @@
 #include <algorithm>
 #include <cmath>
 #include <atomic>
+#include <chrono>
 
 #include "../../include/sip.h"
 #include "sip_device.h"
 #include "sip_exact.h"
 #include "sip_final.h"
+#include "sip_handoff.h"
 #include "sip_state.h"
 #include "sip_stream.h"
 
@@ -333,6 +335,31 @@ sip_status sip_sample_state(const void* logits, int32_t B, int32_t V, int64_t ro
                      k_logprobs, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
+sip_status sip_publish_ids(const int32_t* ids, int32_t B, int32_t* host_ids, uint64_t* host_flag, uint64_t ticket,
+                           void* hip_stream) {
+  if (!ids || !host_ids || !host_flag || B <= 0) return SIP_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(host_flag) & 7u) != 0 || (reinterpret_cast<uintptr_t>(host_ids) & 3u) != 0)
+    return SIP_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(sip::publish_kernel, dim3(1), dim3(sip::kPublishThreads), 0,
+                     static_cast<hipStream_t>(hip_stream), ids, B, host_ids,
+                     reinterpret_cast<unsigned long long*>(host_flag), (unsigned long long)ticket);
+  return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
+}
+
+sip_status sip_wait_ids(const uint64_t* host_flag, uint64_t ticket, uint64_t timeout_ns) {
+  if (!host_flag || (reinterpret_cast<uintptr_t>(host_flag) & 7u) != 0) return SIP_ERR_INVALID_ARG;
+  const auto t0 = std::chrono::steady_clock::now();
+  unsigned spins = 0;
+  for (;;) {
+    if (__atomic_load_n(host_flag, __ATOMIC_ACQUIRE) >= ticket) return SIP_OK;
+    __builtin_ia32_pause();
+    if ((++spins & 1023u) == 0 && timeout_ns != UINT64_MAX) {
+      const auto dt = std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - t0);
+      if ((uint64_t)dt.count() >= timeout_ns) return SIP_ERR_TIMEOUT;
+    }
+  }
+}
+
 const char* sip_status_string(sip_status status) {
   switch (status) {
     case SIP_OK: return "ok";
@@ -340,6 +367,7 @@ const char* sip_status_string(sip_status status) {
     case SIP_ERR_UNSUPPORTED: return "unsupported shape";
     case SIP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SIP_ERR_HIP: return "HIP runtime error";
+    case SIP_ERR_TIMEOUT: return "timed out";
   }
   return "unknown status";
 }

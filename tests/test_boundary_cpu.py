@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    seen = {sip.sip_status_string(s) for s in range(5)}
-    assert len(seen) == 5 and "ok" in seen
+    seen = {sip.sip_status_string(s) for s in range(6)}
+    assert len(seen) == 6 and "ok" in seen
     assert sip.sip_status_string(99) == "unknown status"
 
 
@@ -174,6 +174,37 @@ def test_sharded_workspace_query():
     assert sip.sip_workspace_bytes_sharded(4, 20000, 0, sip.SIP_F32, 0, 5) == 0
     assert sip.sip_workspace_bytes_sharded(4, 20000, 9, sip.SIP_F32, 0, 5) == 0
     assert sip.sip_workspace_bytes_sharded(4, sip.SIP_MAX_V, 2, sip.SIP_F32, 0, 5) == 0
+
+
+def test_wait_for_a_ticket_on_the_host():
+    """sip_wait_ids is plain host code: flag already there, flag that never comes (time-out), flag
+    set by another thread while the call spins."""
+    import threading
+    import time
+    import numpy as np
+    lib = sip.load()
+    flag = np.zeros(1, dtype=np.uint64)
+    addr = flag.ctypes.data
+    flag[0] = 7
+    assert lib.sip_wait_ids(addr, 7, 0) == binding.SIP_OK
+    assert lib.sip_wait_ids(addr, 3, 0) == binding.SIP_OK                      # tickets only grow: a later one serves
+    t0 = time.perf_counter()
+    assert lib.sip_wait_ids(addr, 8, 2_000_000) == binding.SIP_ERR_TIMEOUT      # 2 ms
+    assert 0.001 < time.perf_counter() - t0 < 0.5
+    threading.Timer(0.01, lambda: flag.__setitem__(0, 8)).start()
+    assert lib.sip_wait_ids(addr, 8, 5_000_000_000) == binding.SIP_OK
+    assert lib.sip_wait_ids(None, 1, 0) == binding.SIP_ERR_INVALID_ARG
+    assert lib.sip_wait_ids(addr + 4, 1, 0) == binding.SIP_ERR_INVALID_ARG       # not 8-byte aligned
+    assert sip.sip_status_string(binding.SIP_ERR_TIMEOUT) == "timed out"
+
+
+def test_publish_rejects_bad_arguments_on_the_host():
+    lib = sip.load()
+    ok = dict(ids=0x10000, B=4, host_ids=0x20000, flag=0x30000)
+    for over in (dict(ids=None), dict(host_ids=None), dict(flag=None), dict(B=0), dict(flag=0x30004),
+                 dict(host_ids=0x20002)):
+        a = dict(ok, **over)
+        assert lib.sip_publish_ids(a["ids"], a["B"], a["host_ids"], a["flag"], 1, None) == binding.SIP_ERR_INVALID_ARG
 
 
 def test_binding_refuses_host_tensors():
