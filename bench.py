@@ -225,6 +225,9 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=2, help="0..4 = C1..C5 (default 2 = C3, the headline)")
     ap.add_argument("--cpu-rows", type=int, default=16384, help="row-samples the oracle is timed on (0 = skip)")
     ap.add_argument("--check", action="store_true", help="also compare step 0 with the oracle on 16 rows")
+    ap.add_argument("--legs", choices=("all", "none"), default="all",
+                    help="'none': only the headline measurement, without the extra legs (decode on a device-resident "
+                         "state, host hand-off, vocabulary-sharded logits) -- what the profiles are taken with")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run a plain 256 MiB device copy 4 times (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -323,10 +326,11 @@ def main() -> int:
     achieved = alg / (dom_ms * 1e-3) / 1e9
     whole_call = alg / (launch_ms * 1e-3) / 1e9
 
-    state_leg = decode_on_state(w, d, bufs, sip, dev, stream, args, ws.numel()) if nnz else None
+    extra = args.legs == "all"
+    state_leg = decode_on_state(w, d, bufs, sip, dev, stream, args, ws.numel()) if (nnz and extra) else None
 
-    hand_leg = handoff_leg(w, d, bufs, sip, dev, stream, args, ws)
-    shard_leg = sharded_leg(w, d, bufs, sip, dev, stream, args)
+    hand_leg = handoff_leg(w, d, bufs, sip, dev, stream, args, ws) if extra else None
+    shard_leg = sharded_leg(w, d, bufs, sip, dev, stream, args) if extra else None
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)

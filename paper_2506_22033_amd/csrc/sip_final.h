@@ -745,7 +745,10 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
           const unsigned long long lack = limit > have ? limit - have : 0ull;
           // (and a list that holds less than three quarters of the nucleus' mass is taken as a sign
           // that the rest is far longer than this bound)
-          fs.retry_ok_out = e_c > 0 && lack / e_c + total_seg < 10000ull && have >= limit - (limit >> 2);
+          // With min-p on, the kept set ends at the min-p threshold at the latest, which is known
+          // exactly by now: a second list cut there settles the row if it fits (the caller checks).
+          fs.retry_ok_out = minp_on ||
+                            (e_c > 0 && lack / e_c + total_seg < 10000ull && have >= limit - (limit >> 2));
         }
         return kWholeRowCut;
       }

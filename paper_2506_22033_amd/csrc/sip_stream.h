@@ -1,7 +1,7 @@
 // Single pass over the logits: the only kernel that touches all B*V elements.
 //
 // A row is cut into S chunks, one 512-thread workgroup each.  The workgroup never learns the
-// row's maximum; instead it picks, from a 4096-element sample spread over the row, a value
+// row's maximum; instead it picks, from a 8192-element sample spread over the row, a value
 // threshold Tc such that only the top ~1-3 % of the row lies at or above it, and then streams
 // its chunk once:
 //   * elements >= Tc ("candidates") are collected, value and index, in per-wave LDS queues
@@ -28,7 +28,7 @@ static_assert(kStreamWaves == 8, "ChunkOut::cnt holds one count per wave");
 constexpr int kStreamLoads = 2;             // 16-byte loads per thread per tile
 constexpr int kStreamBufs = 2;              // tiles held in registers: one being processed, the others in flight
 constexpr int kSampleBins = 8192;           // 13-bit keys: sign, exponent, 4 mantissa bits
-constexpr int kSampleSize = 4096;           // elements of a row the threshold is estimated from
+constexpr int kSampleSize = 8192;           // elements of a row the threshold is estimated from
 constexpr int kQueueCap = 512;              // entries of one wave's LDS candidate queue
 constexpr float kBulkScale = 1073741824.0f; // 2^30
 
@@ -54,6 +54,17 @@ __device__ __forceinline__ RowParams load_row_params(const Args& a, int b) {
   return r;
 }
 
+// The threshold of a row whose list is to hold `target` entries is the j-th largest value of a
+// sample, j = target * (sample size) / V.  While j stays small (<= kTailRank) the whole sample of
+// kSampleSize elements is used and a thread only keeps track of its three largest values;
+// a longer list is estimated well enough from every other sample block, through a histogram of
+// all of their values.
+constexpr int kTailRank = 256;
+__device__ __forceinline__ bool whole_sample(int target, int V) {
+  // ceil(target * kSampleSize / V) <= kTailRank, without the division (target <= 2^14, V <= 2^19)
+  return (uint32_t)target * (uint32_t)kSampleSize <= (uint32_t)kTailRank * (uint32_t)V;
+}
+
 // How many of the row's largest elements the candidate list should hold; 0 = this row
 // cannot be finished from a candidate list (k is too large) and takes the exact multi-pass
 // path instead.
@@ -71,6 +82,7 @@ __device__ __forceinline__ int candidate_target(const RowParams& r, const Args& 
     // for 3.5 such deviations more than k (whatever top-p and min-p do afterwards happens
     // inside those k)
     t = k + 256 + (int)(3.5f * sqrtf((float)k * (float)a.V * (1.0f / (float)kSampleSize)));
+    if (!whole_sample(t, a.V)) t = k + 256 + (int)(3.5f * sqrtf((float)k * (float)a.V * (2.0f / (float)kSampleSize)));
   } else {
     // a nucleus with nothing else to bound it tends to be longer than one cut by min-p, so it
     // starts from a longer list -- as long as still fits the 8 entries per thread of the
@@ -214,13 +226,14 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     tnext += TILE;
   }
 
-  // ---- threshold: the same 4096-element sample (1 KB blocks spread evenly over the row) is
+  // ---- threshold: the same 8192-element sample (1 KB blocks spread evenly over the row) is
   // read by every chunk of the row, so all chunks agree on Tc = the j-th largest sample value
-  // rounded down to an 18-bit key (found in two levels: 13 bits, then 5 more), j / 4096 = target / V
+  // rounded down to an 18-bit key (found in two levels: 13 bits, then 5 more), j / 8192 = target / V
+  // (for long lists: half of the blocks, j / 4096 = target / V; see whole_sample())
   uint4 smp[SLOADS];
 #pragma unroll
   for (int j = 0; j < SLOADS; ++j) {
-    const int sb = j * kStreamWaves + wave;
+    const int sb = wave * SLOADS + j;                  // even j: every other block of the row
     if (!SH) {
       const int e0 = (int)(((long long)sb * V / NSB) / (kWave * EPL)) * (kWave * EPL) + lane * EPL;
       smp[j] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);    // e0 + EPL <= V since V >= 16384
@@ -237,30 +250,42 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   if (tid < 32) sub_hist[tid] = 0;
   __syncthreads();
   SIP_SMARK(1);
-  long long want = ((long long)target * kSampleSize + V - 1) / V;
-  if (want < 2) want = 2;
-  if (want > kSampleSize) want = kSampleSize;
-  const uint32_t j = (uint32_t)want;
   // Only the upper tail of the sample matters.  When j is small, a thread enters just the
-  // three largest of its keys: far fewer LDS atomics, and hardly any on the same word.
+  // three largest of its values: far fewer LDS atomics, and hardly any on the same word.
   // (Should one thread hold more than three of the j largest, the threshold comes out a
   // little low, which only lengthens the candidate list.)
-  const bool tail_only = j <= 128;                   // workgroup-uniform
+  const bool tail_only = whole_sample(target, V);    // workgroup-uniform
+  const int n_smp = tail_only ? kSampleSize : kSampleSize / 2;
+  uint32_t want = ((uint32_t)target * (uint32_t)n_smp + (uint32_t)V - 1u) / (uint32_t)V;     // < 2^32: target <= 2^14
+  if (want < 2u) want = 2u;
+  if (want > (uint32_t)n_smp) want = (uint32_t)n_smp;
+  const uint32_t j = want;
   uint32_t t0 = 0, t1 = 0, t2 = 0;                   // full keys of this thread's three largest sample values
   {
+    if (tail_only) {
+      // the three largest as floats, one maximum and two medians per value
+      float f0 = -INFINITY, f1 = -INFINITY, f2 = -INFINITY;
 #pragma unroll
-    for (int l = 0; l < SLOADS; ++l) {
-      float z[EPL];
-      unpack(smp[l], z);
+      for (int l = 0; l < SLOADS; ++l) {
+        float z[EPL];
+        unpack(smp[l], z);
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        const uint32_t kf = key_of(z[i]);
-        if (tail_only) {
-          const uint32_t a1 = min(t0, kf); t0 = max(t0, kf);
-          const uint32_t a2 = min(t1, a1); t1 = max(t1, a1);
-          t2 = max(t2, a2);
-        } else {
-          const uint32_t k13 = kf >> 19;
+        for (int i = 0; i < EPL; ++i) {
+          const float x = z[i];
+          f2 = __builtin_amdgcn_fmed3f(f1, f2, x);
+          f1 = __builtin_amdgcn_fmed3f(f0, f1, x);
+          f0 = fmaxf(f0, x);
+        }
+      }
+      t0 = key_of(f0); t1 = key_of(f1); t2 = key_of(f2);
+    } else {
+#pragma unroll
+      for (int l = 0; l < SLOADS; l += 2) {
+        float z[EPL];
+        unpack(smp[l], z);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+          const uint32_t k13 = key_of(z[i]) >> 19;
           atomicAdd(&hist[k13 >> 1], (k13 & 1u) ? 0x10000u : 1u);
         }
       }
@@ -309,7 +334,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
       enter(t0); enter(t1); enter(t2);
     } else {
 #pragma unroll
-      for (int l = 0; l < SLOADS; ++l) {
+      for (int l = 0; l < SLOADS; l += 2) {
         float z[EPL];
         unpack(smp[l], z);
 #pragma unroll
