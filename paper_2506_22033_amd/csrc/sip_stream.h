@@ -55,14 +55,16 @@ __device__ __forceinline__ RowParams load_row_params(const Args& a, int b) {
 }
 
 // The threshold of a row whose list is to hold `target` entries is the j-th largest value of a
-// sample, j = target * (sample size) / V.  While j stays small (<= kTailRank) the whole sample of
-// kSampleSize elements is used and a thread only keeps track of its three largest values;
-// a longer list is estimated well enough from every other sample block, through a histogram of
-// all of their values.
+// sample, j = target * (sample size) / V, so the list comes out at target * (1 +- 1/sqrt(j)).
+// Lists of kWholeFrom entries and more are the ones that may outgrow the 4096 entries of the
+// finishing kernel's faster variants (twice the time for that row), so they are estimated from
+// the whole sample of kSampleSize elements as long as that keeps j small (<= kTailRank: a thread
+// then only tracks its three largest values); every other list from every other sample block.
 constexpr int kTailRank = 256;
+constexpr int kWholeFrom = 2048;
 __device__ __forceinline__ bool whole_sample(int target, int V) {
   // ceil(target * kSampleSize / V) <= kTailRank, without the division (target <= 2^14, V <= 2^19)
-  return (uint32_t)target * (uint32_t)kSampleSize <= (uint32_t)kTailRank * (uint32_t)V;
+  return target >= kWholeFrom && (uint32_t)target * (uint32_t)kSampleSize <= (uint32_t)kTailRank * (uint32_t)V;
 }
 
 // How many of the row's largest elements the candidate list should hold; 0 = this row
@@ -230,10 +232,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   // read by every chunk of the row, so all chunks agree on Tc = the j-th largest sample value
   // rounded down to an 18-bit key (found in two levels: 13 bits, then 5 more), j / 8192 = target / V
   // (for long lists: half of the blocks, j / 4096 = target / V; see whole_sample())
+  const bool whole = whole_sample(target, V);        // workgroup-uniform, like everything about the threshold
   uint4 smp[SLOADS];
 #pragma unroll
   for (int j = 0; j < SLOADS; ++j) {
     const int sb = wave * SLOADS + j;                  // even j: every other block of the row
+    if ((j & 1) && !whole) { smp[j] = make_uint4(0u, 0u, 0u, 0u); continue; }
     if (!SH) {
       const int e0 = (int)(((long long)sb * V / NSB) / (kWave * EPL)) * (kWave * EPL) + lane * EPL;
       smp[j] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);    // e0 + EPL <= V since V >= 16384
@@ -254,12 +258,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   // three largest of its values: far fewer LDS atomics, and hardly any on the same word.
   // (Should one thread hold more than three of the j largest, the threshold comes out a
   // little low, which only lengthens the candidate list.)
-  const bool tail_only = whole_sample(target, V);    // workgroup-uniform
-  const int n_smp = tail_only ? kSampleSize : kSampleSize / 2;
+  const int n_smp = whole ? kSampleSize : kSampleSize / 2;
   uint32_t want = ((uint32_t)target * (uint32_t)n_smp + (uint32_t)V - 1u) / (uint32_t)V;     // < 2^32: target <= 2^14
   if (want < 2u) want = 2u;
   if (want > (uint32_t)n_smp) want = (uint32_t)n_smp;
   const uint32_t j = want;
+  const bool tail_only = whole || j <= (uint32_t)(kTailRank / 2);
   uint32_t t0 = 0, t1 = 0, t2 = 0;                   // full keys of this thread's three largest sample values
   {
     if (tail_only) {
@@ -267,6 +271,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
       float f0 = -INFINITY, f1 = -INFINITY, f2 = -INFINITY;
 #pragma unroll
       for (int l = 0; l < SLOADS; ++l) {
+        if (!whole && (l & 1)) continue;
         float z[EPL];
         unpack(smp[l], z);
 #pragma unroll
