@@ -217,6 +217,38 @@ def handoff_leg(w, d, bufs, sip, dev, stream, args, ws):
     return res
 
 
+def in_flight_leg(w, d, bufs, sip, dev, args):
+    """Consecutive batches alternate between n streams, each with its own workspace and outputs, as
+    the microbatches of a pipeline of depth n would: the finishing kernel of one batch (latency-bound)
+    overlaps the streaming kernel of the next (HBM-bound)."""
+    import torch
+    k = w.k_logprobs
+    nnz = 0 if d.tokens is None else d.tokens.numel()
+    dt_code = sip.SIP_F32 if w.dtype == "f32" else sip.SIP_BF16
+    out = {}
+    for ns in (2, 3):
+        streams = [torch.cuda.Stream(device=dev) for _ in range(ns)]
+        wss = [torch.empty(max(256, sip.sip_workspace_bytes(w.B, w.V, dt_code, nnz, k)), dtype=torch.uint8, device=dev)
+               for _ in range(ns)]
+        outs = [(torch.empty(w.B, dtype=torch.int32, device=dev), torch.empty(w.B, 1 + k, dtype=torch.int32, device=dev),
+                 torch.empty(w.B, 1 + k, dtype=torch.float32, device=dev)) for _ in range(ns)]
+
+        def step(i):
+            j = i % ns
+            sip.sip_sample(bufs[i % len(bufs)], d.params, d.indptr, d.tokens, 0, i, k, out_ids=outs[j][0],
+                           out_lp_ids=outs[j][1], out_lp=outs[j][2], workspace=wss[j], V=w.V, stream=streams[j])
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        out[f"streams={ns}"] = {"ms_per_step": ms, "value": w.B / (ms * 1e-3), "unit": "rows/s"}
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -331,6 +363,7 @@ def main() -> int:
 
     hand_leg = handoff_leg(w, d, bufs, sip, dev, stream, args, ws) if extra else None
     shard_leg = sharded_leg(w, d, bufs, sip, dev, stream, args) if extra else None
+    flight_leg = in_flight_leg(w, d, bufs, sip, dev, args) if extra else None
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -369,6 +402,7 @@ def main() -> int:
         "decode_on_device_state": state_leg,
         "vocabulary_sharded_logits": shard_leg,
         "host_handoff": hand_leg,
+        "batches_in_flight": flight_leg,
     }
     print(json.dumps(res))
     return 0
