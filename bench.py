@@ -58,23 +58,47 @@ def cpu_baseline(w, max_rows: int) -> dict:
     with ThreadPoolExecutor(cores) as ex:
         list(ex.map(one, jobs))
     dt = time.perf_counter() - t0
+    n1 = min(64, len(jobs))                                         # and on one thread, a second or so
+    t1 = time.perf_counter()
+    for job in jobs[:n1]:
+        one(job)
+    dt1 = time.perf_counter() - t1
     return {"value": len(jobs) / dt, "unit": "rows/s", "cores": cores, "kind": "oracle",
             "sample": f"{len(jobs)} row-samples of {w.name} (rows 0..{min(max_rows, w.B) - 1}, "
-                      f"steps 0..{(max_rows - 1) // w.B}), {dt:.2f} s wall on {cores} threads"}
+                      f"steps 0..{(max_rows - 1) // w.B}), {dt:.2f} s wall on {cores} threads",
+            "single_thread_value": n1 / dt1, "single_thread_sample": f"{n1} row-samples, {dt1:.2f} s"}
 
 
-def read_traffic(name: str):
+def read_traffic(name: str, key: str = "traffic_bytes_per_launch:"):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a
     summary for this workload has been recorded under profiles/."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{name}.txt")
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith("traffic_bytes_per_launch:"):
+                if line.startswith(key):
                     return float(line.split(":", 1)[1])
     except OSError:
         pass
     return None
+
+
+def measured_read_rate(bufs, sip, dev, stream) -> float:
+    """GB/s of a bare streaming read of the logits buffers in the streaming kernel's launch shape
+    (sip_probe_read), median of 20 launches by the dispatch's own time stamps."""
+    import torch
+    ws = torch.empty(4096, dtype=torch.float32, device=dev)
+    times = []
+    with torch.cuda.stream(stream):
+        for i in range(25):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream); e1.record(stream)
+            torch.cuda.synchronize()
+            sip.sip_probe_read(bufs[i % len(bufs)], 1024, ws, e0.cuda_event, e1.cuda_event, stream=stream)
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+    nbytes = bufs[0].numel() * bufs[0].element_size()
+    return nbytes / (float(np.median(times[5:])) * 1e-3) / 1e9
 
 
 def decode_on_state(w, d, bufs, sip, dev, stream, args, csr_ws_bytes):
@@ -356,6 +380,8 @@ def main() -> int:
         stream_ms = final_ms = None
         dominant, dom_ms = "exact_kernel", launch_ms
     achieved = alg / (dom_ms * 1e-3) / 1e9
+    probe_gbs = measured_read_rate(bufs, sip, dev, stream)
+    fetch = read_traffic(w.name, "stream_kernel_fetch_bytes_per_launch:")
     whole_call = alg / (launch_ms * 1e-3) / 1e9
 
     extra = args.legs == "all"
@@ -394,6 +420,8 @@ def main() -> int:
                      "kernel": dominant, "kernel_ms_hip_events": dom_ms,
                      "recorded_hip_event_pair_around_trivial_kernel_ms": event_floor_ms,
                      "algorithmic_bytes_per_launch": alg,
+                     "measured_bare_read_GBps": probe_gbs, "frac_of_measured_bare_read": achieved / probe_gbs,
+                     "passes_over_logits": None if fetch is None else fetch / (w.B * w.V * esz),
                      "finishing_kernel_ms_hip_events": final_ms,
                      "whole_call_ms_hip_events": launch_ms, "whole_call_GBps": whole_call,
                      "whole_call_frac": whole_call / HBM_PEAK_GBS,

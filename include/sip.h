@@ -247,6 +247,19 @@ sip_status sip_wait_ids(const uint64_t* host_flag, uint64_t ticket, uint64_t tim
  */
 void sip_profile_kernel_events(void* stream_start, void* stream_stop, void* final_start, void* final_stop);
 
+/*
+ * Measurement aid: enqueue a bare streaming read of `bytes` bytes (a multiple of 16 is read) at
+ * `src` (device, 16-byte aligned) in the launch shape of the streaming kernel -- `workgroups`
+ * workgroups of 512 threads, each on one contiguous piece, 16-byte loads -- that only adds up
+ * what it reads.  What this takes is what the memory system gives a kernel of that shape on
+ * this machine: the figure the streaming kernel's time is set against beside the published
+ * peak.  `workspace`: device, at least 4 * workgroups bytes (one partial sum per workgroup is
+ * written).  start_event / stop_event: hipEvent_t handles that take the dispatch's own begin
+ * and end time stamps, or NULL.
+ */
+sip_status sip_probe_read(const void* src, size_t bytes, int32_t workgroups, void* workspace,
+                          size_t workspace_bytes, void* start_event, void* stop_event, void* hip_stream);
+
 /* Host string for a status code (static storage, never NULL). */
 const char* sip_status_string(sip_status status);
 

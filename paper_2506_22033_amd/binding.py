@@ -73,6 +73,9 @@ def load() -> ctypes.CDLL:
                                         ctypes.c_uint64, ctypes.c_void_p]
         lib.sip_wait_ids.restype = ctypes.c_int
         lib.sip_wait_ids.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64]
+        lib.sip_probe_read.restype = ctypes.c_int
+        lib.sip_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_void_p,
+                                       ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.sip_state_bytes.restype = ctypes.c_size_t
         lib.sip_state_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
         lib.sip_state_init.restype = ctypes.c_int
@@ -366,3 +369,14 @@ def sip_wait_ids(host_flag: torch.Tensor, ticket: int, timeout_ns: int = 2 ** 64
     if status == SIP_ERR_TIMEOUT:
         return False
     raise SipError(status)
+
+
+def sip_probe_read(src: torch.Tensor, workgroups: int, workspace: torch.Tensor, start_event: Optional[int] = None,
+                   stop_event: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Enqueue the bare streaming read of ``src`` (see include/sip.h)."""
+    if not src.is_cuda or not src.is_contiguous() or not workspace.is_cuda:
+        raise TypeError("src must be a contiguous device tensor and workspace a device tensor")
+    status = load().sip_probe_read(_ptr(src), _nbytes(src), workgroups, _ptr(workspace), _nbytes(workspace),
+                                   start_event, stop_event, _stream_handle(src.device, stream))
+    if status != SIP_OK:
+        raise SipError(status)

@@ -360,6 +360,18 @@ sip_status sip_wait_ids(const uint64_t* host_flag, uint64_t ticket, uint64_t tim
   }
 }
 
+sip_status sip_probe_read(const void* src, size_t bytes, int32_t workgroups, void* workspace,
+                          size_t workspace_bytes, void* start_event, void* stop_event, void* hip_stream) {
+  if (!src || bytes < 16 || workgroups <= 0 || workgroups > 65536) return SIP_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(src) & 15u) != 0) return SIP_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < (size_t)workgroups * sizeof(float)) return SIP_ERR_WORKSPACE;
+  hipExtLaunchKernelGGL(sip::probe_read_kernel, dim3(workgroups), dim3(sip::kProbeThreads), 0,
+                        static_cast<hipStream_t>(hip_stream), static_cast<hipEvent_t>(start_event),
+                        static_cast<hipEvent_t>(stop_event), 0, static_cast<const uint4*>(src), bytes / 16,
+                        (int)workgroups, static_cast<float*>(workspace));
+  return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
+}
+
 const char* sip_status_string(sip_status status) {
   switch (status) {
     case SIP_OK: return "ok";

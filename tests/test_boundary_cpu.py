@@ -207,6 +207,16 @@ def test_publish_rejects_bad_arguments_on_the_host():
         assert lib.sip_publish_ids(a["ids"], a["B"], a["host_ids"], a["flag"], 1, None) == binding.SIP_ERR_INVALID_ARG
 
 
+def test_probe_read_rejects_bad_arguments_on_the_host():
+    lib = sip.load()
+    ok = dict(src=0x10000, nbytes=1 << 20, wgs=64, ws=0x20000, ws_bytes=4096)
+    for over, want in ((dict(src=None), binding.SIP_ERR_INVALID_ARG), (dict(src=0x10008), binding.SIP_ERR_INVALID_ARG),
+                       (dict(nbytes=8), binding.SIP_ERR_INVALID_ARG), (dict(wgs=0), binding.SIP_ERR_INVALID_ARG),
+                       (dict(ws=None), binding.SIP_ERR_WORKSPACE), (dict(ws_bytes=255), binding.SIP_ERR_WORKSPACE)):
+        a = dict(ok, **over)
+        assert lib.sip_probe_read(a["src"], a["nbytes"], a["wgs"], a["ws"], a["ws_bytes"], None, None, None) == want
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError):
