@@ -248,6 +248,55 @@ sip_status sip_wait_ids(const uint64_t* host_flag, uint64_t ticket, uint64_t tim
 void sip_profile_kernel_events(void* stream_start, void* stream_stop, void* final_start, void* final_stop);
 
 /*
+ * ---- Everything in one call ---------------------------------------------------------------------
+ * The entry points above each take one combination of where the logits are (one matrix / t
+ * pieces) and where the histories are (CSR / state).  sip_sample_call() takes a description of
+ * the call and allows every combination, with the hand-off to the host behind it if asked for:
+ * what a tensor-parallel last stage of a pipeline does every iteration.  A HOST struct; zero it
+ * and fill in what applies.  Meaning, alignment and error behaviour of every field as in the
+ * entry point it comes from.
+ */
+typedef struct {
+  /* logits: either one matrix ... */
+  const void* logits;                /* [B, row_stride]; used when t_shards == 0                       */
+  int64_t row_stride;
+  int32_t V;                         /* used when t_shards == 0 (otherwise V = t_shards * V_shard)     */
+  /* ... or t_shards pieces (sip_sample_sharded) */
+  const void* const* shard_logits;   /* host array of t_shards device pointers                         */
+  int32_t t_shards, V_shard;
+  int64_t shard_stride;
+  int32_t B;
+  sip_dtype dtype;
+  const sip_params* params;          /* NULL = every feature off                                       */
+  /* histories: either a CSR ... */
+  const int64_t* hist_indptr;
+  const int32_t* hist_tokens;
+  int64_t hist_nnz;
+  /* ... or a device-resident state (sip_sample_state); state != NULL excludes the CSR */
+  void* state;
+  size_t state_bytes;
+  int32_t slots, L_max;
+  const int32_t* slot_of_row;
+  uint64_t seed, step;
+  int32_t* out_ids;
+  int32_t* out_lp_ids;
+  float* out_lp;
+  int32_t k_logprobs;
+  /* hand-off (sip_publish_ids); both NULL = none */
+  int32_t* host_ids;
+  uint64_t* host_flag;
+  uint64_t ticket;
+  void* workspace;                   /* at least sip_call_workspace_bytes(call) bytes                  */
+  size_t workspace_bytes;
+  void* hip_stream;
+} sip_call;
+
+/* Workspace the call needs (workspace / workspace_bytes / outputs of `call` are not looked at);
+ * 0 if the description is invalid. */
+size_t sip_call_workspace_bytes(const sip_call* call);
+sip_status sip_sample_call(const sip_call* call);
+
+/*
  * Measurement aid: enqueue a bare streaming read of `bytes` bytes (a multiple of 16 is read) at
  * `src` (device, 16-byte aligned) in the launch shape of the streaming kernel -- `workgroups`
  * workgroups of 512 threads, each on one contiguous piece, 16-byte loads -- that only adds up

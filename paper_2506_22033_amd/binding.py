@@ -33,6 +33,22 @@ class SipParams(ctypes.Structure):
     _fields_ = [(name, ctypes.c_void_p) for name in PARAM_FIELDS]
 
 
+class SipCall(ctypes.Structure):
+    """sip_call of include/sip.h, field for field."""
+    _fields_ = [("logits", ctypes.c_void_p), ("row_stride", ctypes.c_int64), ("V", ctypes.c_int32),
+                ("shard_logits", ctypes.POINTER(ctypes.c_void_p)), ("t_shards", ctypes.c_int32),
+                ("V_shard", ctypes.c_int32), ("shard_stride", ctypes.c_int64), ("B", ctypes.c_int32),
+                ("dtype", ctypes.c_int), ("params", ctypes.POINTER(SipParams)),
+                ("hist_indptr", ctypes.c_void_p), ("hist_tokens", ctypes.c_void_p), ("hist_nnz", ctypes.c_int64),
+                ("state", ctypes.c_void_p), ("state_bytes", ctypes.c_size_t), ("slots", ctypes.c_int32),
+                ("L_max", ctypes.c_int32), ("slot_of_row", ctypes.c_void_p),
+                ("seed", ctypes.c_uint64), ("step", ctypes.c_uint64),
+                ("out_ids", ctypes.c_void_p), ("out_lp_ids", ctypes.c_void_p), ("out_lp", ctypes.c_void_p),
+                ("k_logprobs", ctypes.c_int32),
+                ("host_ids", ctypes.c_void_p), ("host_flag", ctypes.c_void_p), ("ticket", ctypes.c_uint64),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("hip_stream", ctypes.c_void_p)]
+
+
 class SipError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
@@ -76,6 +92,10 @@ def load() -> ctypes.CDLL:
         lib.sip_probe_read.restype = ctypes.c_int
         lib.sip_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_void_p,
                                        ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.sip_call_workspace_bytes.restype = ctypes.c_size_t
+        lib.sip_call_workspace_bytes.argtypes = [ctypes.POINTER(SipCall)]
+        lib.sip_sample_call.restype = ctypes.c_int
+        lib.sip_sample_call.argtypes = [ctypes.POINTER(SipCall)]
         lib.sip_state_bytes.restype = ctypes.c_size_t
         lib.sip_state_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
         lib.sip_state_init.restype = ctypes.c_int
@@ -380,3 +400,67 @@ def sip_probe_read(src: torch.Tensor, workgroups: int, workspace: torch.Tensor, 
                                    start_event, stop_event, _stream_handle(src.device, stream))
     if status != SIP_OK:
         raise SipError(status)
+
+
+# ---- everything in one call
+
+def sip_sample_call(*, logits: Optional[torch.Tensor] = None, shards=None, V: Optional[int] = None,
+                    params: Optional[Dict[str, Optional[torch.Tensor]]] = None,
+                    hist_indptr: Optional[torch.Tensor] = None, hist_tokens: Optional[torch.Tensor] = None,
+                    state: Optional[torch.Tensor] = None, slots: int = 0, L_max: int = 0,
+                    slot_of_row: Optional[torch.Tensor] = None, seed: int = 0, step: int = 0, k_logprobs: int = 0,
+                    out_ids: Optional[torch.Tensor] = None, out_lp_ids: Optional[torch.Tensor] = None,
+                    out_lp: Optional[torch.Tensor] = None, host_ids: Optional[torch.Tensor] = None,
+                    host_flag: Optional[torch.Tensor] = None, ticket: int = 0,
+                    workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None
+                    ) -> Tuple[torch.Tensor, Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """sip_sample_call of include/sip.h: logits as one matrix (``logits``, ``V``) or as pieces
+    (``shards``: a ShardTable or a sequence of tensors), histories as a CSR or in a ``state``,
+    and the hand-off to ``host_ids`` / ``host_flag`` behind it if both are given."""
+    lib = load()
+    c = SipCall()
+    keep = []
+    if shards is not None:
+        st = shards if isinstance(shards, ShardTable) else ShardTable(shards, V)
+        keep.append(st)
+        c.shard_logits = ctypes.cast(st.table, ctypes.POINTER(ctypes.c_void_p))
+        c.t_shards, c.V_shard, c.shard_stride = st.t, st.V_shard, st.stride
+        B, dt, dev = st.B, st.dtype, st.device
+    else:
+        if logits is None or not logits.is_cuda or logits.dim() != 2 or logits.stride(1) != 1:
+            raise TypeError("logits must be a 2-D device tensor with contiguous rows")
+        B, dt, dev = logits.shape[0], dtype_code(logits), logits.device
+        c.logits, c.row_stride, c.V = _ptr(logits), logits.stride(0), logits.shape[1] if V is None else int(V)
+    c.B, c.dtype = B, dt
+    sp = make_params(params, B)
+    c.params = ctypes.pointer(sp)
+    if state is not None:
+        c.state, c.state_bytes, c.slots, c.L_max, c.slot_of_row = _ptr(state), _nbytes(state), slots, L_max, _ptr(slot_of_row)
+    elif hist_indptr is not None and hist_tokens is not None and hist_tokens.numel():
+        if hist_indptr.dtype != torch.int64 or hist_tokens.dtype != torch.int32 or hist_indptr.numel() != B + 1:
+            raise TypeError("hist_indptr must be int64 with B + 1 entries and hist_tokens int32")
+        c.hist_indptr, c.hist_tokens, c.hist_nnz = _ptr(hist_indptr), _ptr(hist_tokens), hist_tokens.numel()
+    c.seed, c.step, c.k_logprobs = seed, step, k_logprobs
+    if out_ids is None:
+        out_ids = torch.empty(B, dtype=torch.int32, device=dev)
+    if k_logprobs >= 0:
+        if out_lp_ids is None:
+            out_lp_ids = torch.empty(B, 1 + k_logprobs, dtype=torch.int32, device=dev)
+        if out_lp is None:
+            out_lp = torch.empty(B, 1 + k_logprobs, dtype=torch.float32, device=dev)
+    c.out_ids, c.out_lp_ids, c.out_lp = _ptr(out_ids), _ptr(out_lp_ids), _ptr(out_lp)
+    if host_ids is not None or host_flag is not None:
+        if host_ids is None or host_flag is None or not host_ids.is_pinned() or not host_flag.is_pinned():
+            raise TypeError("host_ids and host_flag must both be given, as pinned host tensors")
+        c.host_ids, c.host_flag, c.ticket = _ptr(host_ids), _ptr(host_flag), ticket
+    if workspace is None:
+        need = int(lib.sip_call_workspace_bytes(ctypes.byref(c)))
+        if need == 0:
+            raise SipError(SIP_ERR_INVALID_ARG)
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    c.workspace, c.workspace_bytes = _ptr(workspace), _nbytes(workspace)
+    c.hip_stream = _stream_handle(dev, stream)
+    status = lib.sip_sample_call(ctypes.byref(c))
+    if status != SIP_OK:
+        raise SipError(status)
+    return out_ids, out_lp_ids, out_lp

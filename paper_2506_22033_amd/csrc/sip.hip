@@ -335,6 +335,59 @@ sip_status sip_sample_state(const void* logits, int32_t B, int32_t V, int64_t ro
                      k_logprobs, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
+namespace {
+// Checks of a sip_call that sample_impl does not make, and its two sources.
+sip_status call_sources(const sip_call* c, HistSource& h, ShardSource& sh, int32_t& V) {
+  if (!c || c->B <= 0) return SIP_ERR_INVALID_ARG;
+  if (c->t_shards < 0 || c->t_shards > SIP_MAX_SHARDS) return SIP_ERR_INVALID_ARG;
+  if (c->t_shards > 0) {
+    if (c->V_shard <= 0 || !c->shard_logits) return SIP_ERR_INVALID_ARG;
+    if ((int64_t)c->V_shard * c->t_shards > SIP_MAX_V) return SIP_ERR_UNSUPPORTED;
+    sh.base = c->shard_logits; sh.t = c->t_shards; sh.V_shard = c->V_shard; sh.stride = c->shard_stride;
+    V = c->V_shard * c->t_shards;
+  } else {
+    V = c->V;
+  }
+  if (c->state) {
+    if (c->hist_indptr || c->hist_tokens || c->hist_nnz != 0) return SIP_ERR_INVALID_ARG;   // one source of history
+    if (!state_shape_ok(c->slots, c->L_max) || !c->slot_of_row) return SIP_ERR_INVALID_ARG;
+    if (!state_ok(c->state, c->state_bytes, c->slots, c->L_max)) return SIP_ERR_WORKSPACE;
+    h.state = sip::state_view(c->state, c->slots, c->L_max);
+    h.tokens = h.state.tokens; h.nnz = (int64_t)c->B * c->L_max;
+    h.slot = c->slot_of_row; h.L_max = c->L_max; h.slots = c->slots;
+  } else {
+    if (c->hist_nnz < 0 || (c->hist_nnz > 0 && (!c->hist_indptr || !c->hist_tokens))) return SIP_ERR_INVALID_ARG;
+    h.indptr = c->hist_indptr; h.tokens = c->hist_tokens; h.nnz = c->hist_nnz;
+  }
+  if ((c->host_ids != nullptr) != (c->host_flag != nullptr)) return SIP_ERR_INVALID_ARG;
+  if (c->host_flag && ((reinterpret_cast<uintptr_t>(c->host_flag) & 7u) != 0 ||
+                       (reinterpret_cast<uintptr_t>(c->host_ids) & 3u) != 0))
+    return SIP_ERR_INVALID_ARG;
+  return SIP_OK;
+}
+}  // namespace
+
+size_t sip_call_workspace_bytes(const sip_call* c) {
+  HistSource h; ShardSource sh; int32_t V = 0;
+  if (call_sources(c, h, sh, V) != SIP_OK) return 0;
+  if (!shape_ok(c->B, V, (int)c->dtype, h.nnz, c->k_logprobs)) return 0;
+  if (V > SIP_MAX_V || c->k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
+  const size_t esz = c->dtype == SIP_F32 ? 4 : 2;
+  return make_layout(c->B, make_plan(c->B, V, (int)c->dtype, sh.t), h.nnz, sh.t ? (size_t)V * esz : 0).total;
+}
+
+sip_status sip_sample_call(const sip_call* c) {
+  HistSource h; ShardSource sh; int32_t V = 0;
+  const sip_status ok = call_sources(c, h, sh, V);
+  if (ok != SIP_OK) return ok;
+  hipStream_t stream = static_cast<hipStream_t>(c->hip_stream);
+  const sip_status st = sample_impl(c->logits, c->B, V, c->row_stride, c->dtype, c->params, h, c->seed, c->step,
+                                    c->out_ids, c->out_lp_ids, c->out_lp, c->k_logprobs, c->workspace,
+                                    c->workspace_bytes, stream, sh);
+  if (st != SIP_OK || !c->host_flag) return st;
+  return sip_publish_ids(c->out_ids, c->B, c->host_ids, c->host_flag, c->ticket, c->hip_stream);
+}
+
 sip_status sip_publish_ids(const int32_t* ids, int32_t B, int32_t* host_ids, uint64_t* host_flag, uint64_t ticket,
                            void* hip_stream) {
   if (!ids || !host_ids || !host_flag || B <= 0) return SIP_ERR_INVALID_ARG;

@@ -217,6 +217,48 @@ def test_probe_read_rejects_bad_arguments_on_the_host():
         assert lib.sip_probe_read(a["src"], a["nbytes"], a["wgs"], a["ws"], a["ws_bytes"], None, None, None) == want
 
 
+def _a_call(**over):
+    c = binding.SipCall()
+    c.logits, c.row_stride, c.V, c.B, c.dtype = 0x10000, 20000, 20000, 4, sip.SIP_F32
+    c.out_ids, c.out_lp_ids, c.out_lp, c.k_logprobs = 0x20000, 0x30000, 0x40000, 5
+    c.workspace, c.workspace_bytes = 0x50000, 1 << 30
+    for k, v in over.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_call_description_is_checked_on_the_host():
+    lib = sip.load()
+    two = (ctypes.c_void_p * 2)(0x60000, 0x70000)
+    pieces = dict(logits=None, shard_logits=ctypes.cast(two, ctypes.POINTER(ctypes.c_void_p)), t_shards=2,
+                  V_shard=20000, shard_stride=20000)
+    state = dict(state=0x80000, state_bytes=1 << 20, slots=8, L_max=64, slot_of_row=0x90000)
+    cases = [
+        (dict(B=0), binding.SIP_ERR_INVALID_ARG),
+        (dict(t_shards=9), binding.SIP_ERR_INVALID_ARG),
+        (dict(t_shards=2, V_shard=20000), binding.SIP_ERR_INVALID_ARG),                    # pieces announced, no table
+        (dict(pieces, V_shard=binding.SIP_MAX_V), binding.SIP_ERR_UNSUPPORTED),
+        (dict(state, hist_nnz=4), binding.SIP_ERR_INVALID_ARG),                            # two sources of history
+        (dict(state, slot_of_row=None), binding.SIP_ERR_INVALID_ARG),
+        (dict(state, state_bytes=100), binding.SIP_ERR_WORKSPACE),
+        (dict(hist_nnz=4), binding.SIP_ERR_INVALID_ARG),
+        (dict(host_ids=0xA0000), binding.SIP_ERR_INVALID_ARG),                             # hand-off needs both
+        (dict(host_ids=0xA0000, host_flag=0xB0004), binding.SIP_ERR_INVALID_ARG),
+        (dict(logits=None), binding.SIP_ERR_INVALID_ARG),
+        (dict(workspace_bytes=16), binding.SIP_ERR_WORKSPACE),
+        (dict(pieces, **state, workspace_bytes=4 * 40000 * 4), binding.SIP_ERR_WORKSPACE),  # rows to gather + side tables
+    ]
+    for over, want in cases:
+        assert lib.sip_sample_call(ctypes.byref(_a_call(**over))) == want, over
+    assert lib.sip_sample_call(None) == binding.SIP_ERR_INVALID_ARG
+    # the workspace query follows the description
+    plain = lib.sip_call_workspace_bytes(ctypes.byref(_a_call()))
+    assert plain == sip.sip_workspace_bytes(4, 20000, sip.SIP_F32, 0, 5)
+    both = lib.sip_call_workspace_bytes(ctypes.byref(_a_call(**dict(pieces, **state))))
+    assert both == sip.sip_workspace_bytes_sharded(4, 20000, 2, sip.SIP_F32, 4 * 64, 5)
+    assert lib.sip_call_workspace_bytes(ctypes.byref(_a_call(B=0))) == 0
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError):

@@ -1,0 +1,77 @@
+"""sip_sample_call: the combinations that no other entry point offers -- logits as vocabulary
+pieces AND histories in a device-resident state AND the ids handed to the host behind the call --
+against the oracle's decode state on the pieces put side by side; and the plain combinations
+against the entry points they come from, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_22033_amd as sip
+import workloads
+from oracle import sip_oracle as O
+from tests import sip_harness as H
+from tests.test_gpu_state import DeviceState, _follow, _params
+
+pytestmark = pytest.mark.gpu
+DEV = H.DEV
+
+
+@pytest.mark.parametrize("t,V_shard,bf16", [(4, 20000, False), (2, 16384, True), (3, 1000, False)])
+def test_decode_on_pieces_with_state_and_hand_off(t, V_shard, bf16):
+    rng = np.random.default_rng(t * 7 + V_shard)
+    V, B, slots, L_max, T, k = t * V_shard, 5, 8, 48, 5, 3
+    slot_of_row = [3, 0, 7, -1, 5]
+    ost, dst = O.DecodeState(slots, L_max, V), DeviceState(slots, L_max)
+    prompts = {3: rng.integers(0, V, 20).tolist(), 0: [], 7: rng.integers(0, V, 40).tolist(), 5: [1, 1, 2]}
+    for s, p in prompts.items():
+        ost.assign(s, p)
+    dst.assign(list(prompts), [prompts[s] for s in prompts])
+    slot_dev = torch.tensor(slot_of_row, dtype=torch.int32, device=DEV)
+    host_ids = torch.full((B,), -1, dtype=torch.int32).pin_memory()
+    flag = torch.zeros(1, dtype=torch.int64).pin_memory()
+    stats = H.ParityStats()
+    for it in range(T):
+        z = rng.normal(0, 2.5, (B, V)).astype(np.float32)
+        for b, s in enumerate(slot_of_row):
+            if 0 <= s < slots and ost.length[s]:
+                z[b, ost.history(s)[-5:]] += 6.0
+        logits = workloads.f32_to_bf16_bits(z) if bf16 else z
+        pieces = [np.ascontiguousarray(logits[:, i * V_shard:(i + 1) * V_shard]) for i in range(t)]
+        dpieces = [H.logits_to_device(x) for x in pieces]
+        p = _params(rng, B, V)
+        dparams = {kk: torch.from_numpy(v).to(DEV) for kk, v in p.items()}
+        before = ost.length.copy()
+        ids, lpi, lp = sip.sip_sample_call(shards=dpieces, V=V_shard, params=dparams, state=dst.buf, slots=slots,
+                                           L_max=L_max, slot_of_row=slot_dev, seed=5, step=100, k_logprobs=k,
+                                           host_ids=host_ids, host_flag=flag, ticket=it + 1)
+        assert sip.sip_wait_ids(flag, it + 1, 10_000_000_000)
+        got = host_ids.numpy().copy()                                       # before any synchronisation
+        torch.cuda.synchronize()
+        assert np.array_equal(got, ids.cpu().numpy())
+        ref = O.sample_state(O.join_shards(pieces), p, ost, slot_of_row, 5, 100, k)
+        stats.merge(H.check_rows(f"call t={t} iteration {it}", range(B), ref, (got, lpi.cpu().numpy(), lp.cpu().numpy()), k))
+        for b, s in enumerate(slot_of_row):
+            if 0 <= s < slots and ost.length[s] > before[s] and got[b] != ref[b].token:
+                _follow(ost, s, int(got[b]))
+    tick, ovf, length, tokens = dst.read()
+    assert tick == T and ovf == 0 and np.array_equal(length, ost.length)
+    for s in range(slots):
+        assert np.array_equal(tokens[s, :length[s]], ost.history(s))
+    print(f"[call] t={t} V_shard={V_shard}: {stats.rows} rows flagged={stats.flagged} max|dlogprob|={stats.max_lp_err:.2e}")
+
+
+def test_plain_combinations_equal_the_entry_points_they_come_from():
+    w = workloads.make(2, B=16, V=40000, H=200)
+    d = H.to_device(w)
+    k = w.k_logprobs
+    a = sip.sip_sample(d.logits, d.params, d.indptr, d.tokens, 3, 4, k, V=w.V)
+    b = sip.sip_sample_call(logits=d.logits, V=w.V, params=d.params, hist_indptr=d.indptr, hist_tokens=d.tokens,
+                            seed=3, step=4, k_logprobs=k)
+    Vs = w.V // 2
+    pieces = [d.logits[:, :Vs].contiguous(), d.logits[:, Vs:w.V].contiguous()]
+    c = sip.sip_sample_sharded(pieces, d.params, d.indptr, d.tokens, 3, 4, k, V_shard=Vs)
+    e = sip.sip_sample_call(shards=pieces, V=Vs, params=d.params, hist_indptr=d.indptr, hist_tokens=d.tokens,
+                            seed=3, step=4, k_logprobs=k)
+    torch.cuda.synchronize()
+    for x, y in ((a, b), (c, e)):
+        assert torch.equal(x[0], y[0]) and torch.equal(x[1], y[1]) and torch.equal(x[2].view(torch.int32), y[2].view(torch.int32))
