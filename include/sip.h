@@ -137,7 +137,7 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
  *  workspace     at least sip_workspace_bytes_sharded(...) bytes: it includes room for B whole
  *                rows, used only by rows that leave the single-pass path (their workgroup puts
  *                the row together there first) and by shapes the single-pass kernels do not
- *                serve (V or V_shard below 16384, V above 262144).
+ *                serve (V below 16384 or above 262144, V_shard below 8192).
  * Everything else as for sip_sample().
  */
 size_t sip_workspace_bytes_sharded(int32_t B, int32_t V_shard, int32_t t, sip_dtype dtype, int64_t hist_nnz,

@@ -30,13 +30,14 @@ struct Plan {
 
 constexpr int kFastMinV = 16384;
 constexpr int kFastMaxV = 262144;
+constexpr int kFastMinPiece = 8192;      // smallest vocabulary shard: its sample blocks (at most 32 of 256 elements) must fit
 
 // `t` > 0: the logits come in t vocabulary shards of V / t elements (0: one piece).
 Plan make_plan(int32_t B, int32_t V, int dtype, int t = 0) {
   Plan p{};
   const int pieces = t > 0 ? t : 1;
   const int Vp = V / pieces;                           // elements per piece
-  p.fast = V >= kFastMinV && V <= kFastMaxV && Vp >= kFastMinV && pieces <= sip::kMaxChunks;
+  p.fast = V >= kFastMinV && V <= kFastMaxV && Vp >= kFastMinPiece && pieces <= sip::kMaxChunks;
   if (!p.fast) return p;
   const int tile = sip::kStreamThreads * sip::kStreamLoads * (dtype == SIP_F32 ? 4 : 8);
   const int n_tiles = (Vp + tile - 1) / tile * pieces;

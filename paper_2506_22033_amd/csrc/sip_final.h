@@ -159,8 +159,12 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     }
     fs.cbeg[tid] = cb;
   }
-  if (SH && tid < a.t_shards)
-    fs.shard_row[tid] = shard_base(a, tid) + (size_t)b * (size_t)a.shard_stride * (DT == SIP_F32 ? 4 : 2);
+  if (SH && tid == 0) {                   // constant indices: the piece pointers come through scalar loads
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (i < a.t_shards)
+        fs.shard_row[i] = reinterpret_cast<const char*>(a.shard[i]) + (size_t)b * (size_t)a.shard_stride * (DT == SIP_F32 ? 4 : 2);
+  }
   if (tid < S) {
     const ChunkOut co = a.chunks[(size_t)b * a.S + tid];
     fs.Tc[tid] = co.Tc; fs.R[tid] = co.R; fs.bulk[tid] = co.bulk;

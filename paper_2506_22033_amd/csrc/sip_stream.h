@@ -243,8 +243,11 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
       smp[j] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);    // e0 + EPL <= V since V >= 16384
     } else {
       // the same NSB blocks for every chunk of the row, smp_bps to a shard (the last shard may get
-      // fewer), evenly spread inside it; V_shard >= 16384 as well, so a block fits
-      const int ssh = (sb * a.smp_inv) >> 16;                                // sb / smp_bps
+      // fewer), evenly spread inside it; V_shard >= 8192, so a block fits
+      // (wave-uniform, and said so: with a per-lane index the table of piece pointers would be read
+      // through a vector load from the kernel-argument segment, and waiting for that one also waits
+      // for the tiles requested above)
+      const int ssh = __builtin_amdgcn_readfirstlane((sb * a.smp_inv) >> 16);   // sb / smp_bps
       const int e0 = (sb - ssh * a.smp_bps) * a.smp_step + lane * EPL;
       const char* srow = shard_base(a, ssh) + (size_t)b * (size_t)a.shard_stride * ESZ;
       smp[j] = *reinterpret_cast<const uint4*>(srow + (size_t)e0 * ESZ);

@@ -45,7 +45,8 @@ def _run_sharded(w, t, seed, step, k, pad=0):
     return (ids.cpu().numpy(), None if lpi is None else lpi.cpu().numpy(), None if lp is None else lp.cpu().numpy()), path
 
 
-CASES = [(0, "gauss", 2, 16384, False), (1, "heavy", 4, 20000, True), (2, "flat", 3, 17000, False),
+CASES = [(8, "gauss", 8, 16032, True), (9, "heavy", 4, 8192, False), (10, "peaked", 8, 8200, True),
+         (0, "gauss", 2, 16384, False), (1, "heavy", 4, 20000, True), (2, "flat", 3, 17000, False),
          (3, "quantised", 8, 16384, False), (4, "peaked", 8, 19008, True), (5, "sorted", 2, 40000, False),
          (6, "gauss", 5, 33336, True), (7, "heavy", 1, 50000, False)]
 
@@ -91,7 +92,7 @@ def test_rows_that_leave_the_single_pass_path_gather_their_row_first():
     assert set(path.tolist()) - {1}, "no row left the single-pass path: the test does not test what it says"
 
 
-@pytest.mark.parametrize("t,V_shard,bf16", [(4, 1000, False), (2, 8192, True), (8, 40000, False)])
+@pytest.mark.parametrize("t,V_shard,bf16", [(4, 1000, False), (2, 4096, True), (8, 40000, False)])
 def test_shapes_outside_the_single_pass_kernels(t, V_shard, bf16):
     rng = np.random.default_rng(t * V_shard)
     B, V = 4, t * V_shard
