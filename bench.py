@@ -69,6 +69,35 @@ def cpu_baseline(w, max_rows: int) -> dict:
             "single_thread_value": n1 / dt1, "single_thread_sample": f"{n1} row-samples, {dt1:.2f} s"}
 
 
+def cpu_columnwise(w, steps: int = 5) -> dict:
+    """A second host figure: the CPU sampler in the paper's own layout (Sec. 5.1: column-wise Z^T,
+    frequency table kept incrementally, workers on parts of the batch; oracle/columnwise), checked
+    against the oracle in tests/.  A few decode steps on the same workload."""
+    from oracle.columnwise import ColumnwiseSampler
+    cores = min(16, os.cpu_count() or 1)
+    cw = ColumnwiseSampler(w.B, w.V, threads=cores)
+    if w.hist_indptr is not None:
+        for b in range(w.B):
+            cw.set_history(b, w.hist_tokens[w.hist_indptr[b]:w.hist_indptr[b + 1]])
+    t_load = t_samp = 0.0
+    for i in range(steps + 1):
+        t0 = time.perf_counter()
+        cw.load_logits(w.logits)
+        t1 = time.perf_counter()
+        ids, _, _ = cw.sample(w.params, 0, i, w.k_logprobs)
+        t2 = time.perf_counter()
+        cw.push_tokens(ids)
+        if i:                                                     # the first step warms the tables up
+            t_load += t1 - t0
+            t_samp += t2 - t1
+    cw.close()
+    return {"value": steps * w.B / (t_load + t_samp), "unit": "rows/s", "cores": cores,
+            "kind": "CPU sampler in the paper's column-wise layout (oracle/columnwise), not the oracle",
+            "value_without_transposition": steps * w.B / t_samp,
+            "sample": f"{steps} decode steps of {w.name}: {1e3 * t_samp / steps:.1f} ms sampling + "
+                      f"{1e3 * t_load / steps:.1f} ms transposing the logits into Z^T per step on {cores} threads"}
+
+
 def read_traffic(name: str, key: str = "traffic_bytes_per_launch:"):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a
     summary for this workload has been recorded under profiles/."""
@@ -295,6 +324,7 @@ def main() -> int:
 
     w = workloads.make(args.workload)
     cpu = cpu_baseline(w, args.cpu_rows) if args.cpu_rows > 0 else None
+    cpu_cw = cpu_columnwise(w) if (args.cpu_rows > 0 and args.legs == "all") else None
 
     import torch
     import paper_2506_22033_amd as sip
@@ -427,6 +457,7 @@ def main() -> int:
                      "whole_call_frac": whole_call / HBM_PEAK_GBS,
                      "rows_on_single_pass_path_last_step": single_pass_rows},
         "cpu_baseline": cpu,
+        "cpu_columnwise": cpu_cw,
         "decode_on_device_state": state_leg,
         "vocabulary_sharded_logits": shard_leg,
         "host_handoff": hand_leg,
