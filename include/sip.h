@@ -309,6 +309,15 @@ sip_status sip_sample_call(const sip_call* call);
 sip_status sip_probe_read(const void* src, size_t bytes, int32_t workgroups, void* workspace,
                           size_t workspace_bytes, void* start_event, void* stop_event, void* hip_stream);
 
+/*
+ * Diagnostic, HOST only: into how many chunks (workgroups of the streaming kernel) a row of this
+ * shape is cut; t_shards = 0 for logits in one matrix, else V = t_shards * V_shard.  0 = the shape
+ * is served by the exact multi-pass kernel alone, -1 = invalid arguments.  A row's chunks are
+ * whole units of 64 16-byte loads, dealt out evenly (to each vocabulary piece, if there are
+ * pieces); none is empty.
+ */
+int32_t sip_plan_chunks(int32_t B, int32_t V, sip_dtype dtype, int32_t t_shards);
+
 /* Host string for a status code (static storage, never NULL). */
 const char* sip_status_string(sip_status status);
 

@@ -96,6 +96,8 @@ def load() -> ctypes.CDLL:
         lib.sip_call_workspace_bytes.argtypes = [ctypes.POINTER(SipCall)]
         lib.sip_sample_call.restype = ctypes.c_int
         lib.sip_sample_call.argtypes = [ctypes.POINTER(SipCall)]
+        lib.sip_plan_chunks.restype = ctypes.c_int32
+        lib.sip_plan_chunks.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_int32]
         lib.sip_state_bytes.restype = ctypes.c_size_t
         lib.sip_state_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
         lib.sip_state_init.restype = ctypes.c_int

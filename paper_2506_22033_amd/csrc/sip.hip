@@ -426,6 +426,13 @@ sip_status sip_probe_read(const void* src, size_t bytes, int32_t workgroups, voi
   return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
 }
 
+int32_t sip_plan_chunks(int32_t B, int32_t V, sip_dtype dtype, int32_t t_shards) {
+  if (B <= 0 || V <= 0 || (dtype != SIP_F32 && dtype != SIP_BF16) || t_shards < 0 || t_shards > SIP_MAX_SHARDS) return -1;
+  if (t_shards > 0 && V % t_shards != 0) return -1;
+  const Plan p = make_plan(B, V, (int)dtype, t_shards);
+  return p.fast ? p.S : 0;
+}
+
 const char* sip_status_string(sip_status status) {
   switch (status) {
     case SIP_OK: return "ok";

@@ -259,6 +259,46 @@ def test_call_description_is_checked_on_the_host():
     assert lib.sip_call_workspace_bytes(ctypes.byref(_a_call(B=0))) == 0
 
 
+def _chunk_begin(ch, V, S, unit):
+    """A row is cut into S chunks of whole units, sizes differing by at most one unit (the rule
+    the header states for sip_plan_chunks)."""
+    n = (V + unit - 1) // unit
+    return min(ch * n // S * unit, V)
+
+
+def test_every_chunk_of_every_plan_is_non_empty():
+    """The streaming kernel's workgroups each need something to stream (an empty chunk would leave
+    its summary unwritten): sweep batch sizes, vocabularies, dtypes and piece counts."""
+    lib = sip.load()
+    seen_fast = 0
+    for dtype, epl in ((sip.SIP_F32, 4), (sip.SIP_BF16, 8)):
+        unit = 64 * epl
+        for t in (0, 1, 2, 3, 4, 5, 6, 7, 8):
+            for V_piece in (8192, 8200, 9000, 16032, 16384, 19008, 32768, 65536, 100000 // 8 * 8, 262144):
+                V = V_piece * max(t, 1)
+                for B in (1, 2, 3, 4, 7, 16, 63, 64, 100, 128, 129, 255, 256, 257, 300, 512, 513, 1024, 2048, 5000):
+                    S = lib.sip_plan_chunks(B, V, dtype, t)
+                    assert S >= 0, (B, V, dtype, t)
+                    if S == 0:
+                        assert V < 16384 or V > 262144 or V_piece < 8192
+                        continue
+                    seen_fast += 1
+                    assert 1 <= S <= 16
+                    pieces = max(t, 1)
+                    if S >= pieces:
+                        assert S % pieces == 0
+                        per = S // pieces
+                        for lc in range(per):                  # chunks inside one piece
+                            assert _chunk_begin(lc, V_piece, per, unit) < _chunk_begin(lc + 1, V_piece, per, unit)
+                        assert _chunk_begin(per, V_piece, per, unit) == V_piece
+                    else:
+                        assert pieces % S == 0                 # a chunk is whole pieces
+    assert seen_fast > 1000
+    assert lib.sip_plan_chunks(0, 20000, sip.SIP_F32, 0) == -1
+    assert lib.sip_plan_chunks(4, 20001, sip.SIP_F32, 2) == -1
+    assert lib.sip_plan_chunks(4, 20000, sip.SIP_F32, 9) == -1
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError):
