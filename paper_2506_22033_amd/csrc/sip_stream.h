@@ -232,12 +232,14 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   // read by every chunk of the row, so all chunks agree on Tc = the j-th largest sample value
   // rounded down to an 18-bit key (found in two levels: 13 bits, then 5 more), j / 8192 = target / V
   // (for long lists: half of the blocks, j / 4096 = target / V; see whole_sample())
+  // All blocks are requested, whether or not the row's rank calls for the whole sample: a branch
+  // around a load makes the compiler wait for that load where the branches meet, one exposed
+  // memory latency per block.
   const bool whole = whole_sample(target, V);        // workgroup-uniform, like everything about the threshold
   uint4 smp[SLOADS];
 #pragma unroll
   for (int j = 0; j < SLOADS; ++j) {
     const int sb = wave * SLOADS + j;                  // even j: every other block of the row
-    if ((j & 1) && !whole) { smp[j] = make_uint4(0u, 0u, 0u, 0u); continue; }
     if (!SH) {
       const int e0 = (int)(((long long)sb * V / NSB) / (kWave * EPL)) * (kWave * EPL) + lane * EPL;
       smp[j] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * ESZ);    // e0 + EPL <= V since V >= 16384
