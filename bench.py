@@ -318,8 +318,8 @@ def main() -> int:
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (rows are independent; see DESIGN.md for how the "
-              "path would shard) -- run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (rows are independent, so more GPUs would each take a part "
+              "of the batch with no exchange) -- run with --gpus 1", file=sys.stderr)
         return 2
 
     w = workloads.make(args.workload)
