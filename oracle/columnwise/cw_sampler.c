@@ -228,9 +228,7 @@ static void finish_column(const cand_t* g, int ng, float m, double Zsum, float t
     }
     /* draw over the kept set in ascending vocabulary order: g is in that order already */
     const float s_last = n3 > 0 ? srt[n3 - 1].s : m;
-    double S3 = 0.0;
-    for (int i = 0; i < n3; ++i) S3 += 0.0 * e[i];                    /* (order of the sum: by index, below) */
-    S3 = 0.0;
+    double S3 = 0.0;                                                  /* summed in index order, like the CDF below */
     for (int i = 0; i < ng; ++i)
       if (g[i].s >= s_last) S3 += exp((double)g[i].s - (double)m);
     const double target = u * S3;
