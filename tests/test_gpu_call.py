@@ -75,3 +75,48 @@ def test_plain_combinations_equal_the_entry_points_they_come_from():
     torch.cuda.synchronize()
     for x, y in ((a, b), (c, e)):
         assert torch.equal(x[0], y[0]) and torch.equal(x[1], y[1]) and torch.equal(x[2].view(torch.int32), y[2].view(torch.int32))
+
+
+def test_many_rows_many_paths_on_pieces_with_state():
+    """48 rows with the whole range of parameters (greedy, huge top-k, nucleus below the list, plain
+    temperature sampling: every way a row can leave the single-pass path, each of which gathers the
+    row from its pieces first) decoding on a state for three iterations."""
+    from tests.test_gpu_random import _params as wide_params
+    rng = np.random.default_rng(77)
+    t, V_shard, B, slots, L_max, T, k = 4, 20000, 48, 64, 40, 3, 5
+    V = t * V_shard
+    slot_of_row = rng.permutation(slots)[:B].tolist()
+    ost, dst = O.DecodeState(slots, L_max, V), DeviceState(slots, L_max)
+    prompts = {s: rng.integers(0, V, int(rng.choice([0, 5, 30]))).tolist() for s in slot_of_row}
+    for s, p in prompts.items():
+        ost.assign(s, p)
+    dst.assign(list(prompts), [prompts[s] for s in prompts])
+    slot_dev = torch.tensor(slot_of_row, dtype=torch.int32, device=DEV)
+    stats, paths = H.ParityStats(), {}
+    for it in range(T):
+        z = rng.normal(0, 2.0, (B, V)).astype(np.float32)
+        pieces = [np.ascontiguousarray(z[:, i * V_shard:(i + 1) * V_shard]) for i in range(t)]
+        p = wide_params(rng, B, V)
+        full = {kk: p.get(kk) for kk in ("temperature", "top_k", "top_p", "min_p", "repetition_penalty",
+                                        "frequency_penalty", "presence_penalty")}
+        dparams = {kk: torch.from_numpy(v).to(DEV) for kk, v in full.items() if v is not None}
+        before = ost.length.copy()
+        ws = torch.empty(sip.sip_workspace_bytes_sharded(B, V_shard, t, sip.SIP_F32, B * L_max, k), dtype=torch.uint8, device=DEV)
+        ids, lpi, lp = sip.sip_sample_call(shards=[H.logits_to_device(x) for x in pieces], V=V_shard, params=dparams,
+                                           state=dst.buf, slots=slots, L_max=L_max, slot_of_row=slot_dev, seed=1,
+                                           step=0, k_logprobs=k, workspace=ws)
+        torch.cuda.synchronize()
+        for c in ws[:4 * B].view(torch.int32).cpu().tolist():
+            paths[c] = paths.get(c, 0) + 1
+        out = (ids.cpu().numpy(), lpi.cpu().numpy(), lp.cpu().numpy())
+        ref = O.sample_state(z, full, ost, slot_of_row, 1, 0, k)
+        stats.merge(H.check_rows(f"call many paths iteration {it}", range(B), ref, out, k))
+        for b, s in enumerate(slot_of_row):
+            if ost.length[s] > before[s] and out[0][b] != ref[b].token:
+                _follow(ost, s, int(out[0][b]))
+    tick, ovf, length, tokens = dst.read()
+    assert tick == T and np.array_equal(length, ost.length)
+    for s in range(slots):
+        assert np.array_equal(tokens[s, :length[s]], ost.history(s))
+    print(f"[call] many paths: {stats.rows} rows, paths {paths}, flagged={stats.flagged} mismatch={stats.flagged_mismatch}")
+    assert len(set(paths) - {1}) >= 2, "the parameters were meant to send rows down several paths"
