@@ -101,7 +101,7 @@ def cpu_columnwise(w, steps: int = 5) -> dict:
 def read_traffic(name: str, key: str = "traffic_bytes_per_launch:"):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a
     summary for this workload has been recorded under profiles/."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{name}.txt")
+    path = os.path.join(ROOT, "profiles", f"stream_final_hbm_traffic_{name}.txt")
     try:
         with open(path) as f:
             for line in f:
