@@ -1,5 +1,5 @@
 """ctypes front end of cw_sampler.c, the CPU sampler in the paper's column-wise layout (Sec. 5.1).
-BASELINE / TEST INFRASTRUCTURE ONLY, like everything under oracle/: imported by tests/ and by
+BASELINE / TEST INFRASTRUCTURE ONLY, not the oracle (that is oracle/): imported by tests/ and by
 bench.py's CPU leg.  ``build()`` compiles it with gcc; ``load()`` builds it if it is missing."""
 from __future__ import annotations
 

@@ -71,9 +71,9 @@ def cpu_baseline(w, max_rows: int) -> dict:
 
 def cpu_columnwise(w, steps: int = 5) -> dict:
     """A second host figure: the CPU sampler in the paper's own layout (Sec. 5.1: column-wise Z^T,
-    frequency table kept incrementally, workers on parts of the batch; oracle/columnwise), checked
+    frequency table kept incrementally, workers on parts of the batch; baselines/columnwise), checked
     against the oracle in tests/.  A few decode steps on the same workload."""
-    from oracle.columnwise import ColumnwiseSampler
+    from baselines.columnwise import ColumnwiseSampler
     cores = min(16, os.cpu_count() or 1)
     cw = ColumnwiseSampler(w.B, w.V, threads=cores)
     if w.hist_indptr is not None:
@@ -92,7 +92,7 @@ def cpu_columnwise(w, steps: int = 5) -> dict:
             t_samp += t2 - t1
     cw.close()
     return {"value": steps * w.B / (t_load + t_samp), "unit": "rows/s", "cores": cores,
-            "kind": "CPU sampler in the paper's column-wise layout (oracle/columnwise), not the oracle",
+            "kind": "CPU sampler in the paper's column-wise layout (baselines/columnwise), not the oracle",
             "value_without_transposition": steps * w.B / t_samp,
             "sample": f"{steps} decode steps of {w.name}: {1e3 * t_samp / steps:.1f} ms sampling + "
                       f"{1e3 * t_load / steps:.1f} ms transposing the logits into Z^T per step on {cores} threads"}

@@ -9,6 +9,7 @@
 #include <chrono>
 
 #include "../../include/sip.h"
+#include "../../include/sip_diag.h"
 #include "sip_device.h"
 #include "sip_exact.h"
 #include "sip_final.h"

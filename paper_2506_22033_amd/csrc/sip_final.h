@@ -90,18 +90,6 @@ __device__ __forceinline__ float load_elem(const char* row, int v) {
   return __uint_as_float((uint32_t)reinterpret_cast<const unsigned short*>(row)[v] << 16);
 }
 
-// Development aid: with -DSIP_TIMING workgroup 0 records a 100 MHz timestamp at each mark
-// behind the per-row path codes in the workspace.
-#ifdef SIP_TIMING
-#define SIP_MARK(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) \
-    { reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1))[i] = wall_clock64(); \
-      reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1))[32 + i] = clock64(); } } while (0)
-#define SIP_MARK_T(i, t) do { if (blockIdx.x == 0 && threadIdx.x == (t)) \
-    { reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1))[i] = wall_clock64(); } } while (0)
-#else
-#define SIP_MARK(i) do { } while (0)
-#define SIP_MARK_T(i, t) do { } while (0)
-#endif
 
 // One attempt at finishing row b from its candidate list.  CR / SR = candidate entries /
 // distinct history tokens a thread can hold in registers: the list, once read, never goes to
@@ -135,7 +123,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   const char* row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * (DT == SIP_F32 ? 4 : 2);
   auto scaled_s = [&](float z) { return rp.greedy ? z : __fdiv_rn(z, rp.tau); };
 
-  SIP_MARK(0);
   // ---- (0) chunk summaries, history extent; clear the LDS tables meanwhile
   const HistRange hr = hist_range(a, b);
   const long long lo = hr.lo, hi = hr.hi;
@@ -195,7 +182,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   scale_pair(rp, c_row, c_lo);
   __syncthreads();
 
-  SIP_MARK(1);
   // ---- (1) prefix of the segment sizes (wave 0); presence bitmap of the history (everyone)
   if (wave == 0) {
     const uint32_t c0 = 2 * lane < nseg ? fs.segoff[2 * lane] : 0u;
@@ -234,7 +220,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   if (total_seg > (uint32_t)a.nc_cap) return 5;                               // uniform
   if (total_seg > (uint32_t)(NT * CR)) return kNeedLongList;                  // uniform
 
-  SIP_MARK(2);
   // ---- (2) The two dependent global reads of this kernel -- the candidate segments and the raw
   // logits of the history tokens -- are issued as early as their addresses are known and
   // consumed as late as possible, with the LDS work in between.
@@ -305,7 +290,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     }
     __syncthreads();
   }
-  SIP_MARK(11);
   // Register entries: 0..CR-1 candidates, CR..NE-1 history tokens.  idx == kNoIdx: no entry.
   uint32_t idx[NE], key[NE];                 // key[] holds the bits of z' until (5) turns them into keys
   // (2c) request the raw logits of this thread's history tokens
@@ -374,7 +358,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   }
   __syncthreads();
 
-  SIP_MARK(4);
   // ---- (4) penalised values of the history entries; maximum of the list (lowest index on ties)
   long long corr = 0;               // mass the streaming pass counted for elements that carry a penalty
   uint32_t bkey = 0, bidx = kNoIdx;
@@ -457,7 +440,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   // which register rounds hold anything at all (workgroup-uniform)
   auto live = [&](int r) { return r < CR ? r < per : (uint32_t)((r - CR) * NT) < ndist; };
 
-  SIP_MARK(5);
   // ---- (5) keys, masses, value histogram (count and mass per bin)
   unsigned long long Ereg[NS];
   short breg[NS];
@@ -490,7 +472,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     if constexpr (STORE) return (int)breg[r]; else return bin_of(value_of(key[r]), key[r]);
   };
   __syncthreads();
-  SIP_MARK(13);
   const bool k_act = !rp.greedy && rp.top_k >= 2 && rp.top_k < V;
   const uint32_t n_top = (uint32_t)max(0, min(a.k_lp, V));
   unsigned long long S_cand;
@@ -556,7 +537,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   const float f2 = (float)frexp((double)S0, &e2);
   const double lnZ = ((double)__builtin_amdgcn_logf(f2) + (double)(e2 - kFixShift)) * ln2;
 
-  SIP_MARK(6);
   // ---- (6) gather the bin of the k-th largest and everything at or above the bin of the n-th best
   if (k_act || n_top > 0) {
     mask_t mk = 0, mt = 0;            // bit r: register entry r lies in the bin of the k-th / belongs to the top list
@@ -587,9 +567,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     __syncthreads();
     if (fs.n_memb > (uint32_t)kMembers || fs.n_top > (uint32_t)kTopList) return 9;   // uniform
   }
-  SIP_MARK(24);
   // best-n (upper half of the workgroup) and the k-th largest (lower half) side by side
-  SIP_MARK_T(29, 256);
   // The gathered list holds every element at or above the bin of the n-th best, so an entry's
   // rank in this list is its rank in the row.  Up to 64 entries are ranked by one wave out of
   // its own registers; longer lists by half the workgroup out of LDS.
@@ -627,7 +605,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       }
     }
   }
-  SIP_MARK_T(30, 256);
   uint32_t key_k = 0;
   unsigned long long S1 = S0;
   if (k_act) {
@@ -667,7 +644,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   int token = best_i;
   uint32_t token_key = key_of(m);
   if (!rp.greedy) {
-    SIP_MARK(7);
     // ---- (7) top-p
     // every element missing from the list fails min-p  <=>  the completeness threshold itself fails it
     const bool minp_bounds = minp_on && !(__fsub_rn(s_c, m) >= t_minp);
@@ -690,7 +666,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       }
       __syncthreads();
       const int bin_p = fs.bin_p;
-      SIP_MARK(14);
       if (bin_p >= kBins) return 10;                                          // uniform (p <= 0)
       {
         mask_t mp = 0;
@@ -710,7 +685,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       }
       __syncthreads();
       const uint32_t nm = (uint32_t)__builtin_amdgcn_readfirstlane((int)fs.n_memb2);
-      SIP_MARK(15);
       if (nm > (uint32_t)kMembers) return 9;                                  // uniform
       if (nm <= (uint32_t)kWave) {
         if (wave == 0) {
@@ -762,7 +736,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       whole_row = true;                                                       // no filter at all: every token is kept
     }
 
-    SIP_MARK(8);
     if (whole_row) {
       if (tid == 0) { fs.limit_out = 0; fs.lnz_out = lnZ; fs.has_pen_out = has_pen; }
       return kWholeRow;                                                       // uniform: finished by the caller
@@ -782,7 +755,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
         }
       }
       __syncthreads();
-      SIP_MARK(25);
       unsigned long long target;
       {
         const int b0 = kBinsPerThread * tid;                 // ascending index order
@@ -807,7 +779,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       }
       __syncthreads();
       const int bin_d = fs.bin_d;
-      SIP_MARK(26);
       if (bin_d < 0) return 13;                                               // uniform (no kept mass)
       {
         mask_t md = 0;
@@ -826,7 +797,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       }
       __syncthreads();
       const uint32_t nm = (uint32_t)__builtin_amdgcn_readfirstlane((int)fs.n_memb3);
-      SIP_MARK(27);
       if (nm > (uint32_t)kMembers) return 9;                                  // uniform
       if (nm <= (uint32_t)kWave) {
         if (wave == 0) {
@@ -857,7 +827,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     }
   }
 
-  SIP_MARK(9);
   // ---- (9) the token and its logprob.  Past this point nothing can fail.
   if (tid == 0) {
     a.out_ids[b] = token;
@@ -867,16 +836,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       a.out_lp[(size_t)b * cols] = (float)((double)value_of(token_key) - (double)m - lnZ);
     }
   }
-  SIP_MARK(10);
-#ifdef SIP_TIMING
-#ifndef SIP_DBG_ROW
-#define SIP_DBG_ROW 0
-#endif
-  if (blockIdx.x == SIP_DBG_ROW && tid == 0) {
-    long long* dbg = reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1));
-    dbg[24] = fs.n_top; dbg[25] = fs.n_memb; dbg[26] = fs.n_memb2; dbg[27] = fs.n_memb3; dbg[28] = total_seg; dbg[31] = ndist; dbg[29] = CR; dbg[30] = SR;
-  }
-#endif
   return 1;
 }
 
@@ -990,9 +949,6 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   __shared__ ExactShared ex;
   __shared__ FastShared fs;
   const int b = blockIdx.x;
-#ifdef SIP_TIMING
-  const long long t_begin = wall_clock64();
-#endif
   const RowParams rp = load_row_params(a, b);
   int how = 2;                                   // 2: not eligible for the single-pass path
   int code = 0;
@@ -1062,12 +1018,7 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
     if (SH && !gathered) { gather_row<DT>(a, b); gathered = true; }
     exact_row<DT>(a, b, reinterpret_cast<uint32_t*>(dynraw), ex);
   }
-#ifdef SIP_TIMING
-  // development aid: the row's time in this kernel, in 10 ns ticks, above the path code
-  if (threadIdx.x == 0) a.row_path[b] = (code ? code : how) | ((int)(wall_clock64() - t_begin) << 8);
-#else
   if (threadIdx.x == 0) a.row_path[b] = code ? code : how;
-#endif
   if (a.slot) {                                  // device-resident history: the row's id joins it
     __syncthreads();
     if (threadIdx.x == 0) state_append_row(a, b, target != 0 ? fs.ndist_out : -1);

@@ -132,12 +132,6 @@ __device__ __forceinline__ unsigned long long bulk_units(float acc) {
   return acc > 0.0f ? (unsigned long long)(acc * kBulkScale) : 0ull;
 }
 
-#ifdef SIP_TIMING
-#define SIP_SMARK(i) do { if (blockIdx.x == SIP_TIMING_BLOCK && threadIdx.x == 0) \
-    reinterpret_cast<long long*>(a.row_path + ((a.B + 1) & ~1))[16 + i] = wall_clock64(); } while (0)
-#else
-#define SIP_SMARK(i) do { } while (0)
-#endif
 
 template <int DT, bool SH>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
@@ -158,9 +152,6 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   __shared__ uint32_t sub_hist[32];                 // that bin, split by the next 5 key bits
 
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
-#ifdef SIP_TIMING
-  const long long t_wg_begin = wall_clock64();
-#endif
   // Workgroups are handed to the 8 XCDs round-robin by their id.  The chunks of one row read
   // the same sample, so they are renumbered to land on the same XCD (and its L2): id i works
   // on logical chunk (i % 8) * (n / 8) + i / 8 when n, the grid size, is a multiple of 8.
@@ -219,7 +210,6 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
 
   // the first tiles of the chunk are requested before anything else so that they travel
   // while the threshold is being worked out
-  SIP_SMARK(0);
   uint4 buf[kStreamBufs][kStreamLoads];
   int tnext = c0;                                    // first element of the next tile to request
 #pragma unroll
@@ -258,7 +248,6 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   for (int i = tid; i < kSampleBins / 2; i += kStreamThreads) hist[i] = 0;
   if (tid < 32) sub_hist[tid] = 0;
   __syncthreads();
-  SIP_SMARK(1);
   // Only the upper tail of the sample matters.  When j is small, a thread enters just the
   // three largest of its values: far fewer LDS atomics, and hardly any on the same word.
   // (Should one thread hold more than three of the j largest, the threshold comes out a
@@ -361,7 +350,6 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     }
     __syncthreads();
   }
-  SIP_SMARK(2);
   const uint32_t kb = key_thr << 14;
   const float Tc = value_of(kb);
   const BulkRef ref = make_bulk_ref(Tc, rp);
@@ -411,7 +399,6 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     }
   };
 
-  SIP_SMARK(3);
   // kStreamBufs register buffers in rotation: while one tile is processed the loads of the
   // others are in flight
   if (!SH) {
@@ -457,7 +444,6 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
       }
     }
   }
-  SIP_SMARK(4);
   // the queue goes out to the wave's segment in one burst (no global stores inside the loop:
   // they would force every wait on a tile load to drain the whole memory queue)
   for (uint32_t i = lane; i < min(qn, min(cap, (uint32_t)kQueueCap)); i += kWave) {
@@ -477,14 +463,6 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     o.R = R;
     a.chunks[wg] = o;
   }
-  SIP_SMARK(5);
-#ifdef SIP_TIMING
-  // development aid: begin and end time of this workgroup in the last slot of its first segment
-  if (tid == 0) {
-    uint2* slot = a.cand + ((size_t)wg * kStreamWaves) * (size_t)a.cap_w + (a.cap_w - 1);
-    *slot = make_uint2((uint32_t)t_wg_begin, (uint32_t)wall_clock64());
-  }
-#endif
 }
 
 }  // namespace sip

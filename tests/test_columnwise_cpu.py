@@ -1,4 +1,4 @@
-"""The CPU sampler in the paper's column-wise layout (oracle/columnwise, a baseline for bench.py)
+"""The CPU sampler in the paper's column-wise layout (baselines/columnwise, a baseline for bench.py)
 against the oracle: same tokens except on rows the oracle flags as near-boundary, same best-n,
 logprobs within the library's tolerance -- over several decode iterations, so that its
 incrementally kept frequency table is what the penalties come from.  No GPU."""
@@ -7,7 +7,7 @@ import pytest
 
 import workloads
 from oracle import sip_oracle as O
-from oracle.columnwise import ColumnwiseSampler
+from baselines.columnwise import ColumnwiseSampler
 
 LP_ABS, LP_REL = 1e-5, 2.0 ** -22
 

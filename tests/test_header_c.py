@@ -27,6 +27,11 @@ def test_header_compiles_as_c99_without_warnings():
     assert out.split() == ["0", str(binding.SIP_ERR_TIMEOUT)]
 
 
+def test_diagnostic_header_compiles_as_c99_without_warnings():
+    out = _run_c('#include "sip_diag.h"\n#include <stdio.h>\nint main(void) { printf("%d\\n", (int)SIP_OK); return 0; }\n')
+    assert out.split() == ["0"]
+
+
 def test_ctypes_mirrors_have_the_layout_of_the_c_structs():
     lines = ['#include "sip.h"', "#include <stdio.h>", "#include <stddef.h>", "int main(void) {",
              '  printf("params %zu\\n", sizeof(sip_params));', '  printf("call %zu\\n", sizeof(sip_call));']
