@@ -39,7 +39,8 @@ typedef enum {
   SIP_ERR_UNSUPPORTED = 2, /* shape outside what the kernels are built for (see SIP_MAX_*) */
   SIP_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned or smaller than sip_workspace_bytes() */
   SIP_ERR_HIP = 4,         /* a HIP runtime call (kernel launch) failed */
-  SIP_ERR_TIMEOUT = 5      /* sip_wait_ids(): the ticket did not appear in time */
+  SIP_ERR_TIMEOUT = 5,     /* sip_wait_ids(): the ticket did not appear in time */
+  SIP_ERR_SCRATCH = 6      /* sip_sample_noalloc(): the call needs more scratch than the built-in array holds */
 } sip_status;
 
 #define SIP_MAX_V (1 << 19)        /* largest vocabulary the kernels support            */
@@ -283,6 +284,40 @@ typedef struct {
  * 0 if the description is invalid. */
 size_t sip_call_workspace_bytes(const sip_call* call);
 sip_status sip_sample_call(const sip_call* call);
+
+/*
+ * One-time set-up for the calling thread's current device: raises the dynamic-LDS limit of the
+ * kernels that need more than the default and looks up the address of the built-in scratch
+ * array of sip_sample_noalloc().  Every entry point does this by itself on its first call on a
+ * device, but that first call then contains HIP calls that a stream capture cannot record:
+ * call sip_init() once per device (with that device current) before capturing a graph whose
+ * first node would otherwise be the library's first call on the device.  Idempotent and
+ * thread-safe.  SIP_ERR_HIP if the runtime refuses.
+ */
+sip_status sip_init(void);
+
+/*
+ * ---- For callers that cannot allocate ---------------------------------------------------------
+ * sip_sample() with the workspace taken from an array that is part of the library's device code
+ * instead of from the caller: for callers that cannot call hipMalloc where they sample (code
+ * under stream capture, tight serving loops, harnesses that forbid allocation).  Arguments,
+ * results and error behaviour are those of sip_sample(); the call makes no hipMalloc / hipFree
+ * and no allocating library call.
+ *
+ *  - The array holds sip_noalloc_scratch_bytes() bytes on every device the library runs on, for
+ *    the life of the process.  A call whose sip_workspace_bytes() exceeds that is rejected on the
+ *    host with SIP_ERR_SCRATCH before anything is enqueued.
+ *  - All calls on one device share that device's array: calls that overlap in time on one device
+ *    (different streams without an ordering between them) race.  Calls on one stream are safe.
+ *  - The per-row path codes (see sip_workspace_bytes) are not available to the caller.
+ */
+size_t sip_noalloc_scratch_bytes(void);
+sip_status sip_sample_noalloc(const void* logits, int32_t B, int32_t V, int64_t row_stride, sip_dtype dtype,
+                              const sip_params* params,
+                              const int64_t* hist_indptr, const int32_t* hist_tokens, int64_t hist_nnz,
+                              uint64_t seed, uint64_t step,
+                              int32_t* out_ids, int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs,
+                              void* hip_stream);
 
 /* Host string for a status code (static storage, never NULL). */
 const char* sip_status_string(sip_status status);

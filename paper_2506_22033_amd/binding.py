@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsip.so")
 
 SIP_F32, SIP_BF16 = 0, 1
-SIP_OK, SIP_ERR_INVALID_ARG, SIP_ERR_UNSUPPORTED, SIP_ERR_WORKSPACE, SIP_ERR_HIP, SIP_ERR_TIMEOUT = range(6)
+SIP_OK, SIP_ERR_INVALID_ARG, SIP_ERR_UNSUPPORTED, SIP_ERR_WORKSPACE, SIP_ERR_HIP, SIP_ERR_TIMEOUT, SIP_ERR_SCRATCH = range(7)
 SIP_MAX_V = 1 << 19
 SIP_MAX_K_LOGPROBS = 64
 SIP_MAX_SLOTS = 1 << 20
@@ -75,6 +75,16 @@ def load() -> ctypes.CDLL:
             ctypes.POINTER(SipParams), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
             ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        lib.sip_init.restype = ctypes.c_int
+        lib.sip_init.argtypes = []
+        lib.sip_noalloc_scratch_bytes.restype = ctypes.c_size_t
+        lib.sip_noalloc_scratch_bytes.argtypes = []
+        lib.sip_sample_noalloc.restype = ctypes.c_int
+        lib.sip_sample_noalloc.argtypes = [
+            ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int,
+            ctypes.POINTER(SipParams), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+            ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int32, ctypes.c_void_p]
         lib.sip_workspace_bytes_sharded.restype = ctypes.c_size_t
         lib.sip_workspace_bytes_sharded.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
                                                     ctypes.c_int64, ctypes.c_int32]
@@ -209,6 +219,43 @@ def sip_sample(logits: torch.Tensor, params: Optional[Dict[str, Optional[torch.T
     if status != SIP_OK:
         raise SipError(status)
     return out_ids, out_lp_ids, out_lp
+
+
+def sip_init() -> None:
+    """One-time set-up of the library on torch's current device (see include/sip.h)."""
+    status = load().sip_init()
+    if status != SIP_OK:
+        raise SipError(status)
+
+
+def sip_noalloc_scratch_bytes() -> int:
+    return int(load().sip_noalloc_scratch_bytes())
+
+
+def sip_sample_noalloc(logits: torch.Tensor, params: Optional[Dict[str, Optional[torch.Tensor]]],
+                       hist_indptr: Optional[torch.Tensor], hist_tokens: Optional[torch.Tensor],
+                       seed: int, step: int, k_logprobs: int, *, out_ids: torch.Tensor,
+                       out_lp_ids: Optional[torch.Tensor] = None, out_lp: Optional[torch.Tensor] = None,
+                       V: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """sip_sample_noalloc of include/sip.h: the caller supplies every output; nothing is allocated
+    here either (no tensor is created)."""
+    lib = load()
+    if not logits.is_cuda or logits.dim() != 2 or logits.stride(1) != 1:
+        raise TypeError("logits must be a 2-D device tensor with contiguous rows")
+    B = logits.shape[0]
+    V = logits.shape[1] if V is None else int(V)
+    nnz = 0
+    if hist_indptr is not None and hist_tokens is not None:
+        if hist_indptr.dtype != torch.int64 or hist_tokens.dtype != torch.int32 or hist_indptr.numel() != B + 1:
+            raise TypeError("hist_indptr must be int64 with B + 1 entries and hist_tokens int32")
+        nnz = hist_tokens.numel()
+    sp = make_params(params, B)
+    status = lib.sip_sample_noalloc(_ptr(logits), B, V, logits.stride(0), dtype_code(logits), ctypes.byref(sp),
+                                    _ptr(hist_indptr) if nnz else None, _ptr(hist_tokens) if nnz else None, nnz,
+                                    seed, step, _ptr(out_ids), _ptr(out_lp_ids), _ptr(out_lp), k_logprobs,
+                                    _stream_handle(logits.device, stream))
+    if status != SIP_OK:
+        raise SipError(status)
 
 
 # ---- device-resident sampler state

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <atomic>
 #include <chrono>
+#include <mutex>
 
 #include "../../include/sip.h"
 #include "../../include/sip_diag.h"
@@ -73,17 +74,46 @@ struct Layout {
 
 thread_local hipEvent_t g_prof[4] = {nullptr, nullptr, nullptr, nullptr};   // one-shot, see sip_profile_kernel_events()
 
-// Kernels that use more than the default 64 KB of dynamic LDS have to be told so once.
+// Kernels that use more than the default 64 KB of dynamic LDS have to be told so once per device.
 constexpr int kMaxDynLds = 144 * 1024;
-bool allow_big_lds(const void* kernel, int slot) {
-  static std::atomic<bool> done[8];
-  if (done[slot].load(std::memory_order_acquire)) return true;
-  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds) != hipSuccess) {
-    (void)hipGetLastError();
-    return false;
-  }
-  done[slot].store(true, std::memory_order_release);
-  return true;
+constexpr int kMaxDevices = 64;
+
+// Built-in scratch of sip_sample_noalloc(): one copy per device, at that device's own address.
+// In host code the name below is only a handle for hipGetSymbolAddress; the address the kernels
+// get is the one looked up in device_setup().
+constexpr size_t kNoallocBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoallocBytes];
+
+struct DeviceSetup {
+  std::atomic<int> state{0};                // 0: not done, 1: done
+  void* scratch_ptr = nullptr;
+};
+DeviceSetup g_dev[kMaxDevices];
+std::mutex g_dev_mutex;
+
+// Per-device set-up (see sip_init in the header).  Returns the device's entry, or nullptr.
+DeviceSetup* device_setup() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+  DeviceSetup& d = g_dev[dev];
+  if (d.state.load(std::memory_order_acquire) == 1) return &d;
+  std::lock_guard<std::mutex> lock(g_dev_mutex);
+  if (d.state.load(std::memory_order_acquire) == 1) return &d;
+  const void* big[] = {
+      reinterpret_cast<const void*>(sip::exact_kernel<SIP_F32, false>), reinterpret_cast<const void*>(sip::exact_kernel<SIP_BF16, false>),
+      reinterpret_cast<const void*>(sip::exact_kernel<SIP_F32, true>),  reinterpret_cast<const void*>(sip::exact_kernel<SIP_BF16, true>),
+      reinterpret_cast<const void*>(sip::final_kernel<SIP_F32, false>), reinterpret_cast<const void*>(sip::final_kernel<SIP_BF16, false>),
+      reinterpret_cast<const void*>(sip::final_kernel<SIP_F32, true>),  reinterpret_cast<const void*>(sip::final_kernel<SIP_BF16, true>)};
+  for (const void* k : big)
+    if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+  void* p = nullptr;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return nullptr; }
+  d.scratch_ptr = p;
+  d.state.store(1, std::memory_order_release);
+  return &d;
 }
 
 bool shape_ok(int32_t B, int32_t V, int dtype, int64_t nnz, int32_t k_lp) {
@@ -201,14 +231,13 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
 template <bool SH>
 sip_status launch(const sip::Args& a_in, int32_t B, int dtype, const Plan& plan, bool state, sip::StateHeader* head,
                   hipStream_t stream) {
+  if (!device_setup()) return SIP_ERR_HIP;
   sip::Args a = a_in;
   const size_t words = ((size_t)a.V + 31) / 32;
-  const int slot0 = (SH ? 4 : 0) + (dtype == SIP_F32 ? 0 : 1);
   if (!plan.fast) {
     // every row takes the exact multi-pass path
     const size_t dyn = 2 * words * sizeof(uint32_t);
     auto kern = dtype == SIP_F32 ? sip::exact_kernel<SIP_F32, SH> : sip::exact_kernel<SIP_BF16, SH>;
-    if (!allow_big_lds(reinterpret_cast<const void*>(kern), slot0)) return SIP_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3(B), dim3(sip::kExactThreads), dyn, stream, a);
     if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
     if (state) {
@@ -221,7 +250,6 @@ sip_status launch(const sip::Args& a_in, int32_t B, int dtype, const Plan& plan,
   auto k_stream = dtype == SIP_F32 ? sip::stream_kernel<SIP_F32, SH> : sip::stream_kernel<SIP_BF16, SH>;
   auto k_final = dtype == SIP_F32 ? sip::final_kernel<SIP_F32, SH> : sip::final_kernel<SIP_BF16, SH>;
   const size_t dyn = std::max(plan.final_lds, 2 * words * sizeof(uint32_t));
-  if (!allow_big_lds(reinterpret_cast<const void*>(k_final), slot0 + 2)) return SIP_ERR_HIP;
   hipEvent_t ev[4];
   for (int i = 0; i < 4; ++i) { ev[i] = g_prof[i]; g_prof[i] = nullptr; }
   if (ev[0] || ev[1])       // the events take the dispatch's own begin / end time stamps
@@ -265,6 +293,28 @@ sip_status sip_sample(const void* logits, int32_t B, int32_t V, int64_t row_stri
   h.indptr = hist_indptr; h.tokens = hist_tokens; h.nnz = hist_nnz;
   return sample_impl(logits, B, V, row_stride, dtype, params, h, seed, step, out_ids, out_lp_ids, out_lp,
                      k_logprobs, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+sip_status sip_init(void) { return device_setup() ? SIP_OK : SIP_ERR_HIP; }
+
+size_t sip_noalloc_scratch_bytes(void) { return kNoallocBytes; }
+
+sip_status sip_sample_noalloc(const void* logits, int32_t B, int32_t V, int64_t row_stride, sip_dtype dtype,
+                              const sip_params* params, const int64_t* hist_indptr, const int32_t* hist_tokens,
+                              int64_t hist_nnz, uint64_t seed, uint64_t step, int32_t* out_ids,
+                              int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs, void* hip_stream) {
+  if (hist_nnz > 0 && (!hist_indptr || !hist_tokens)) return SIP_ERR_INVALID_ARG;
+  if (!shape_ok(B, V, (int)dtype, hist_nnz, k_logprobs)) return SIP_ERR_INVALID_ARG;
+  if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return SIP_ERR_UNSUPPORTED;
+  const size_t need = make_layout(B, make_plan(B, V, (int)dtype), hist_nnz).total;
+  if (need > kNoallocBytes) return SIP_ERR_SCRATCH;
+  DeviceSetup* d = device_setup();                 // the current device's copy of the array
+  if (!d) return SIP_ERR_HIP;
+  // Nothing in the workspace has to start at zero: every kernel writes what it later reads.
+  HistSource h;
+  h.indptr = hist_indptr; h.tokens = hist_tokens; h.nnz = hist_nnz;
+  return sample_impl(logits, B, V, row_stride, dtype, params, h, seed, step, out_ids, out_lp_ids, out_lp,
+                     k_logprobs, d->scratch_ptr, kNoallocBytes, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t sip_workspace_bytes_sharded(int32_t B, int32_t V_shard, int32_t t, sip_dtype dtype, int64_t hist_nnz,
@@ -442,6 +492,7 @@ const char* sip_status_string(sip_status status) {
     case SIP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SIP_ERR_HIP: return "HIP runtime error";
     case SIP_ERR_TIMEOUT: return "timed out";
+    case SIP_ERR_SCRATCH: return "call needs more scratch than the library's built-in array holds";
   }
   return "unknown status";
 }

@@ -33,8 +33,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    seen = {sip.sip_status_string(s) for s in range(6)}
-    assert len(seen) == 6 and "ok" in seen
+    seen = {sip.sip_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
     assert sip.sip_status_string(99) == "unknown status"
 
 
