@@ -15,16 +15,18 @@ extern "C" {
 #endif
 
 /*
- * Profiling aid.  Arms a one-shot hook on the calling host thread: the next sip_sample() call
- * (or sip_sample_state() call) made by this thread that takes the single-pass path launches its two kernels with the given
+ * Profiling aid.  Arms a one-shot hook on the calling host thread: the next sampling call made
+ * by this thread that takes the single-pass path launches its three kernels with the given
  * hipEvent_t handles (created by the caller with timing enabled) attached to the kernel
  * dispatches themselves: `stream_start` / `stream_stop` take the begin and end time stamps of
- * the streaming kernel -- the one pass over the logits, Sec. 5.1's dense row-wise work --
- * and `final_start` / `final_stop` those of the finishing kernel, so that a caller reads each
- * kernel's duration with hipEventElapsedTime without any extra packet between them.  Either
- * pair may be NULL; all NULL disarms.  No effect on results.
+ * the streaming kernel -- the one pass over the logits, Sec. 5.1's dense row-wise work --,
+ * `finish_*` those of the finishing kernel (one workgroup per row on the list the pass left) and
+ * `rescue_*` those of the kernel behind it that takes the rows the list did not settle, so that a
+ * caller reads each kernel's duration with hipEventElapsedTime without any extra packet between
+ * them.  Any pointer may be NULL; all NULL disarms.  No effect on results.
  */
-void sip_profile_kernel_events(void* stream_start, void* stream_stop, void* final_start, void* final_stop);
+void sip_profile_kernel_events(void* stream_start, void* stream_stop, void* finish_start, void* finish_stop,
+                               void* rescue_start, void* rescue_stop);
 
 /*
  * Measurement aid: enqueue a bare streaming read of `bytes` bytes (a multiple of 16 is read) at

@@ -126,7 +126,7 @@ def load() -> ctypes.CDLL:
         lib.sip_status_string.restype = ctypes.c_char_p
         lib.sip_status_string.argtypes = [ctypes.c_int]
         lib.sip_profile_kernel_events.restype = None
-        lib.sip_profile_kernel_events.argtypes = [ctypes.c_void_p] * 4
+        lib.sip_profile_kernel_events.argtypes = [ctypes.c_void_p] * 6
         lib.sip_version.restype = ctypes.c_int
         lib.sip_version.argtypes = []
         _lib = lib
@@ -138,9 +138,10 @@ def sip_version() -> int:
 
 
 def sip_profile_kernel_events(stream_start: Optional[int], stream_stop: Optional[int],
-                              final_start: Optional[int] = None, final_stop: Optional[int] = None) -> None:
+                              finish_start: Optional[int] = None, finish_stop: Optional[int] = None,
+                              rescue_start: Optional[int] = None, rescue_stop: Optional[int] = None) -> None:
     """Arm the one-shot profiling hook with raw hipEvent_t handles (all None disarms)."""
-    load().sip_profile_kernel_events(stream_start, stream_stop, final_start, final_stop)
+    load().sip_profile_kernel_events(stream_start, stream_stop, finish_start, finish_stop, rescue_start, rescue_stop)
 
 
 def sip_status_string(status: int) -> str:

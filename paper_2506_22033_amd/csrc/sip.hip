@@ -14,6 +14,7 @@
 #include "sip_device.h"
 #include "sip_exact.h"
 #include "sip_final.h"
+#include "sip_finish.h"
 #include "sip_handoff.h"
 #include "sip_state.h"
 #include "sip_stream.h"
@@ -26,7 +27,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // Launch shape of the single-pass path; a function of (B, V, dtype) only.
 struct Plan {
   bool fast;       // false: vocabulary outside what the single-pass kernels are built for
-  int S, cap_w, nc_cap;
+  int S, cap_c, nc_cap;
   size_t final_lds;
 };
 
@@ -61,22 +62,37 @@ Plan make_plan(int32_t B, int32_t V, int dtype, int t = 0) {
       }
     want = best;
   }
+  // the streaming kernel marks a chunk's history tokens in an LDS bitmap of kChunkBitsMax bits:
+  // cut finer (first at the piece boundaries, then inside the pieces) until a chunk fits
+  {
+    const int unit = sip::kWave * (dtype == SIP_F32 ? 4 : 8);
+    const int n_units = (Vp + unit - 1) / unit;
+    auto max_chunk = [&](int S) {
+      return S >= pieces ? (n_units + S / pieces - 1) / (S / pieces) * unit : pieces / S * Vp;
+    };
+    while (max_chunk(want) > sip::kChunkBitsMax) {
+      const int next = want >= pieces ? want + pieces : pieces;
+      if (next > sip::kMaxChunks) { p.fast = false; return p; }
+      want = next;
+    }
+  }
   p.S = want;                                          // <= n_tiles / 2: every chunk holds at least two tiles
-  p.cap_w = sip::kQueueCap;
+  p.cap_c = sip::kChunkCap;
   p.nc_cap = sip::kFinalThreads * sip::kCandLong;     // the finishing kernel holds the list in registers
   p.final_lds = sip::final_lds_fixed(V);
   return p;
 }
 
 struct Layout {
-  size_t row_path, side_z, side_c, chunks, cand, gather, total;
+  size_t row_path, rescue, side_z, side_c, chunks, cand, gather, total;
 };
 
-thread_local hipEvent_t g_prof[4] = {nullptr, nullptr, nullptr, nullptr};   // one-shot, see sip_profile_kernel_events()
+thread_local hipEvent_t g_prof[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};   // one-shot, see sip_profile_kernel_events()
 
 // Kernels that use more than the default 64 KB of dynamic LDS have to be told so once per device.
 constexpr int kMaxDynLds = 144 * 1024;
 constexpr int kMaxDevices = 64;
+constexpr int kRescueGrid = 256;         // workgroups of the rescue kernel (one per compute unit)
 
 // Built-in scratch of sip_sample_noalloc(): one copy per device, at that device's own address.
 // In host code the name below is only a handle for hipGetSymbolAddress; the address the kernels
@@ -102,8 +118,8 @@ DeviceSetup* device_setup() {
   const void* big[] = {
       reinterpret_cast<const void*>(sip::exact_kernel<SIP_F32, false>), reinterpret_cast<const void*>(sip::exact_kernel<SIP_BF16, false>),
       reinterpret_cast<const void*>(sip::exact_kernel<SIP_F32, true>),  reinterpret_cast<const void*>(sip::exact_kernel<SIP_BF16, true>),
-      reinterpret_cast<const void*>(sip::final_kernel<SIP_F32, false>), reinterpret_cast<const void*>(sip::final_kernel<SIP_BF16, false>),
-      reinterpret_cast<const void*>(sip::final_kernel<SIP_F32, true>),  reinterpret_cast<const void*>(sip::final_kernel<SIP_BF16, true>)};
+      reinterpret_cast<const void*>(sip::rescue_kernel<SIP_F32, false>), reinterpret_cast<const void*>(sip::rescue_kernel<SIP_BF16, false>),
+      reinterpret_cast<const void*>(sip::rescue_kernel<SIP_F32, true>),  reinterpret_cast<const void*>(sip::rescue_kernel<SIP_BF16, true>)};
   for (const void* k : big)
     if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds) != hipSuccess) {
       (void)hipGetLastError();
@@ -124,13 +140,15 @@ bool shape_ok(int32_t B, int32_t V, int dtype, int64_t nnz, int32_t k_lp) {
 Layout make_layout(int32_t B, const Plan& p, int64_t nnz, size_t gather_row_bytes = 0) {
   Layout l;
   size_t off = 0;
-  l.row_path = off; off += align_up((size_t)B * sizeof(int) + 8 + 64 * 8);   // first, so that callers can find it
+  l.row_path = off; off += align_up((size_t)2 * B * sizeof(int));            // first, so that callers can find it: path
+                                                                             // codes, then the finishing kernel's own codes
+  l.rescue = off; off += align_up((size_t)(B + 1) * sizeof(int));            // count, then row numbers
   l.side_z = off; off += align_up((size_t)nnz * sizeof(float));
   l.side_c = off; off += align_up((size_t)nnz * sizeof(unsigned int));
   l.chunks = off;
   if (p.fast) off += align_up((size_t)B * p.S * sizeof(sip::ChunkOut));
   l.cand = off;
-  if (p.fast) off += align_up((size_t)B * p.S * sip::kStreamWaves * (size_t)p.cap_w * sizeof(uint2));
+  if (p.fast) off += align_up((size_t)B * p.S * (size_t)p.cap_c * sizeof(uint2));
   l.gather = off; off += align_up((size_t)B * gather_row_bytes);
   l.total = off ? off : kAlign;
   return l;
@@ -221,7 +239,10 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
   a.side_c = reinterpret_cast<unsigned int*>(ws + lay.side_c);
   a.chunks = reinterpret_cast<sip::ChunkOut*>(ws + lay.chunks);
   a.cand = reinterpret_cast<uint2*>(ws + lay.cand);
-  a.S = plan.S; a.cap_w = plan.cap_w; a.nc_cap = plan.nc_cap;
+  a.S = plan.S; a.cap_c = plan.cap_c; a.nc_cap = plan.nc_cap;
+  a.row_why = a.row_path + B;
+  a.rescue_n = reinterpret_cast<int*>(ws + lay.rescue);
+  a.rescue_rows = a.rescue_n + 1;
 
   sip::StateHeader* head = h.slot ? h.state.head : nullptr;
   return sh.t ? launch<true>(a, B, (int)dtype, plan, h.slot != nullptr, head, stream)
@@ -248,19 +269,23 @@ sip_status launch(const sip::Args& a_in, int32_t B, int dtype, const Plan& plan,
   }
   a.tick_bias = state ? 1 : 0;             // the streaming kernel counts the call, the finishing kernel knows
   auto k_stream = dtype == SIP_F32 ? sip::stream_kernel<SIP_F32, SH> : sip::stream_kernel<SIP_BF16, SH>;
-  auto k_final = dtype == SIP_F32 ? sip::final_kernel<SIP_F32, SH> : sip::final_kernel<SIP_BF16, SH>;
+  auto k_rescue = dtype == SIP_F32 ? sip::rescue_kernel<SIP_F32, SH> : sip::rescue_kernel<SIP_BF16, SH>;
   const size_t dyn = std::max(plan.final_lds, 2 * words * sizeof(uint32_t));
-  hipEvent_t ev[4];
-  for (int i = 0; i < 4; ++i) { ev[i] = g_prof[i]; g_prof[i] = nullptr; }
-  if (ev[0] || ev[1])       // the events take the dispatch's own begin / end time stamps
+  hipEvent_t ev[6];
+  for (int i = 0; i < 6; ++i) { ev[i] = g_prof[i]; g_prof[i] = nullptr; }
+  const bool timed = ev[0] || ev[1] || ev[2] || ev[3] || ev[4] || ev[5];
+  // three launches: the pass over the logits; one workgroup per row on what it left; and a small
+  // fixed grid for the rows (normally none) that need more than that
+  const int n_rescue_wg = std::min<int>(B, kRescueGrid);
+  if (timed) {               // the events take the dispatches' own begin / end time stamps
     hipExtLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, ev[0], ev[1], 0, a);
-  else
+    hipExtLaunchKernelGGL(sip::finish_kernel, dim3(B), dim3(sip::kFinThreads), 0, stream, ev[2], ev[3], 0, a);
+    hipExtLaunchKernelGGL(k_rescue, dim3(n_rescue_wg), dim3(sip::kFinalThreads), dyn, stream, ev[4], ev[5], 0, a);
+  } else {
     hipLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, a);
-  if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
-  if (ev[2] || ev[3])
-    hipExtLaunchKernelGGL(k_final, dim3(B), dim3(sip::kFinalThreads), dyn, stream, ev[2], ev[3], 0, a);
-  else
-    hipLaunchKernelGGL(k_final, dim3(B), dim3(sip::kFinalThreads), dyn, stream, a);
+    hipLaunchKernelGGL(sip::finish_kernel, dim3(B), dim3(sip::kFinThreads), 0, stream, a);
+    hipLaunchKernelGGL(k_rescue, dim3(n_rescue_wg), dim3(sip::kFinalThreads), dyn, stream, a);
+  }
   if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
   return SIP_OK;
 }
@@ -497,11 +522,14 @@ const char* sip_status_string(sip_status status) {
   return "unknown status";
 }
 
-void sip_profile_kernel_events(void* stream_start, void* stream_stop, void* final_start, void* final_stop) {
+void sip_profile_kernel_events(void* stream_start, void* stream_stop, void* finish_start, void* finish_stop,
+                               void* rescue_start, void* rescue_stop) {
   g_prof[0] = static_cast<hipEvent_t>(stream_start);
   g_prof[1] = static_cast<hipEvent_t>(stream_stop);
-  g_prof[2] = static_cast<hipEvent_t>(final_start);
-  g_prof[3] = static_cast<hipEvent_t>(final_stop);
+  g_prof[2] = static_cast<hipEvent_t>(finish_start);
+  g_prof[3] = static_cast<hipEvent_t>(finish_stop);
+  g_prof[4] = static_cast<hipEvent_t>(rescue_start);
+  g_prof[5] = static_cast<hipEvent_t>(rescue_stop);
 }
 
 int sip_version(void) { return 100; }

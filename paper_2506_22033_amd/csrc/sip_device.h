@@ -11,12 +11,20 @@ constexpr int kWave = 64;
 constexpr int kFixShift = 40;          // masses are carried as integers in units of 2^-40 of the row maximum's mass
 constexpr float kFixScale = 1099511627776.0f;   // 2^40
 
-// What the streaming workgroup of one chunk leaves behind.
+// Bit 31 of a list entry's index: the token occurs in the row's history and the row has a penalty
+// switched on, so the entry's value is the raw logit that the penalty still has to be applied to.
+constexpr uint32_t kTagBit = 0x80000000u;
+constexpr uint32_t kCntOverflow = 0xFFFFFFFFu;   // ChunkOut::cnt of a chunk whose queue overflowed
+
+// What the streaming workgroup of one chunk leaves behind.  Its list (the chunk's segment in
+// Args::cand) holds every element with z >= Tc and every element whose token is in the row's
+// history (tagged, see kTagBit); `bulk` is the softmax mass of all other elements.
 struct ChunkOut {
-  unsigned long long bulk;  // sum over non-candidates of 2^(z*c - R), in units of 2^-30
-  float Tc;                 // every element of the chunk with z >= Tc is in a segment
+  unsigned long long bulk;  // sum over the elements not in the list of 2^(z*c - R), in units of 2^-30
+  float Tc;                 // every element of the chunk with z >= Tc is in the segment
   int R;                    // integer reference exponent of `bulk`
-  unsigned int cnt[8];      // candidates found by each of the chunk's 8 waves (may exceed cap_w: overflow)
+  unsigned int cnt;         // entries in the chunk's segment, or kCntOverflow
+  unsigned int pad[3];
 };
 
 // Everything one call needs, passed by value to the kernels.
@@ -38,11 +46,14 @@ struct Args {
   unsigned int* side_c;   // [nnz]  its multiplicity
   // workspace and launch shape of the single-pass path
   ChunkOut* chunks;         // [B * S]
-  uint2* cand;              // [B * S * 4 * cap_w]  (value bits, index)
+  uint2* cand;              // [B * S * cap_c]  (value bits, index | tag): one segment per chunk
   int S;                    // chunks per row
-  int cap_w;                // candidate slots per wave segment
-  int nc_cap;               // candidates the finishing kernel can hold in LDS
+  int cap_c;                // list entries per chunk segment
+  int nc_cap;               // longest list any finishing path can hold
   int* row_path;            // [B] diagnostic: 1 = finished by the single-pass path, >1 = exact path (reason)
+  int* row_why;             // [B] diagnostic: 1, or why the finishing kernel handed the row to the rescue kernel
+  int* rescue_n;            // rows the finishing kernel could not settle from the list ...
+  int* rescue_rows;         // [B] ... and which; the rescue kernel takes them from here
   // Device-resident history (sip_sample_state): `slot` != nullptr replaces the CSR above.  Row b's
   // history is tokens[slot[b] * L_max .. + st_len[slot[b]]); `tokens` then points at the state's
   // token table and nnz = slots * L_max.

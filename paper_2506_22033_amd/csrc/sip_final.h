@@ -32,7 +32,7 @@ constexpr int kBins = 2048;
 constexpr int kBinsPerThread = kBins / kFinalThreads;
 constexpr int kMembers = 256;        // entries of one bin that can be resolved by all-pairs comparison
 constexpr int kSideMax = 4096;       // distinct history tokens per row the fast path handles
-constexpr int kMaxChunks = 128 / kStreamWaves;   // one wave takes the prefix of all segment sizes, two per lane
+constexpr int kMaxChunks = 16;       // chunks (= list segments) per row
 constexpr int kTopList = kFinalThreads / 2 < 256 ? kFinalThreads / 2 : 256;        // entries at or above the bin of the n-th best (half a workgroup ranks them)
 constexpr int kTokRegs = 8;          // history tokens a thread keeps in registers between phases
 constexpr int kWordRegs = 16;        // bitmap words a thread owns (2^18 / 32 / kFinalThreads)
@@ -46,12 +46,9 @@ constexpr int kCandLong = 24;        // candidate entries per thread of the larg
 struct FastShared {
   float Tc[kMaxChunks];
   int R[kMaxChunks];
-  float r0[kMaxChunks];                 // fractional part of the chunk's reference exponent
-  int cbeg[kMaxChunks + 1];             // first element of each chunk
   unsigned long long bulk[kMaxChunks];
-  uint32_t segoff[kMaxChunks * kStreamWaves + 1];
+  uint32_t segoff[kMaxChunks + 1];
   unsigned long long r64[kFinalWaves];
-  long long rcorr[kFinalWaves];
   uint32_t r32[kFinalWaves];
   uint32_t rkey[kFinalWaves];
   uint32_t ridx[kFinalWaves];
@@ -102,7 +99,7 @@ __device__ __forceinline__ float load_elem(const char* row, int v) {
 // by the path that takes the row over.
 template <int DT, int CR, int SR, bool SH>
 __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
-                                        FastShared& fs, const int S, const int cap_w) {
+                                        FastShared& fs, const int S, const int cap_c) {
   constexpr int NT = kFinalThreads;
   constexpr int NE = CR + SR;                               // register entries per thread
   constexpr bool STORE = CR <= 8;
@@ -127,24 +124,12 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   const HistRange hr = hist_range(a, b);
   const long long lo = hr.lo, hi = hr.hi;
   const bool has_pen = (hi > lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
-  const int nseg = S * kStreamWaves;
+  const int nseg = S;                                       // one list segment per chunk
   if (tid == 0) {
     fs.fail_seg = 0; fs.anyc = 0; fs.dropped = 0;
     fs.bin_k = -1; fs.bin_n = -1; fs.bin_p = 1 << 30; fs.bin_low = 1 << 30; fs.bin_d = -1;
     fs.key_p = 0xFFFFFFFFu; fs.n_memb = 0; fs.n_memb2 = 0; fs.n_memb3 = 0; fs.n_top = 0;
     fs.token = 0x7FFFFFFF; fs.key_k = 0; fs.s1_part = 0;
-  }
-  if (tid <= S) {
-    int cb = chunk_begin(tid, V, S, kWave * (DT == SIP_F32 ? 4 : 8));
-    if (SH && S == a.S) {                       // first attempt on sharded logits: chunks lie inside the shards
-      if (S >= a.t_shards) {
-        const int S_sh = S / a.t_shards, sh = tid / S_sh;
-        cb = sh * a.V_shard + chunk_begin(tid - sh * S_sh, a.V_shard, S_sh, kWave * (DT == SIP_F32 ? 4 : 8));
-      } else {                                  // a chunk is t_shards / S whole shards
-        cb = tid * (a.t_shards / S) * a.V_shard;
-      }
-    }
-    fs.cbeg[tid] = cb;
   }
   if (SH && tid == 0) {                   // constant indices: the piece pointers come through scalar loads
 #pragma unroll
@@ -155,9 +140,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   if (tid < S) {
     const ChunkOut co = a.chunks[(size_t)b * a.S + tid];
     fs.Tc[tid] = co.Tc; fs.R[tid] = co.R; fs.bulk[tid] = co.bulk;
-    fs.r0[tid] = make_bulk_ref(co.Tc, rp).r0;
-#pragma unroll
-    for (int w = 0; w < kStreamWaves; ++w) fs.segoff[tid * kStreamWaves + w] = co.cnt[w];
+    fs.segoff[tid] = co.cnt;
   }
   // history tokens of this thread (the first kTokRegs rounds stay in registers)
   int tok[kTokRegs];
@@ -178,8 +161,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   const bool minp_on = !rp.greedy && rp.min_p > 0.0f;
   const float t_minp = minp_on ? (float)log((double)rp.min_p) : 0.0f;
   const unsigned long long j24 = rp.greedy ? 0ull : (unsigned long long)(philox_word0(a.seed, rp.row_id, step_of(a)) >> 8);
-  float c_row, c_lo;
-  scale_pair(rp, c_row, c_lo);
   __syncthreads();
 
   // ---- (1) prefix of the segment sizes (wave 0); presence bitmap of the history (everyone)
@@ -188,7 +169,8 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     const uint32_t c1 = 2 * lane + 1 < nseg ? fs.segoff[2 * lane + 1] : 0u;
     const uint32_t incl = dpp_scan_add_u32(c0 + c1);
     const uint32_t total = last_lane_u32(incl);
-    if (c0 > (uint32_t)cap_w || c1 > (uint32_t)cap_w) fs.fail_seg = 1;       // a queue overflowed
+    if (c0 > (uint32_t)cap_c || c1 > (uint32_t)cap_c) fs.fail_seg = 1;       // a queue overflowed
+    if (c0 + c1 < c0 || incl < c0 + c1) fs.fail_seg = 1;                       // (the overflow mark wraps the sums)
     if (2 * lane < nseg) fs.segoff[2 * lane] = incl - c0 - c1;
     if (2 * lane + 1 < nseg) fs.segoff[2 * lane + 1] = incl - c1;
     if (lane == 0) fs.segoff[nseg] = total;
@@ -224,7 +206,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   // logits of the history tokens -- are issued as early as their addresses are known and
   // consumed as late as possible, with the LDS work in between.
   // (2a) thread t takes list positions per*t .. per*t + per-1: one segment search, then it walks along
-  const uint2* segs = a.cand + (size_t)b * (size_t)(a.S * kStreamWaves) * (size_t)a.cap_w;
+  const uint2* segs = a.cand + (size_t)b * (size_t)a.S * (size_t)a.cap_c;
   const int per = (int)((total_seg + NT - 1) / NT);                           // uniform, <= CR
   uint2 creg[CR];
   {
@@ -245,7 +227,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
         const uint32_t i = i0 + (uint32_t)r;
         if (i < total_seg) {
           while (i >= hi_off) { ++sg; lo_off = hi_off; hi_off = fs.segoff[sg + 1]; }   // skips empty segments too
-          creg[r] = segs[(size_t)sg * cap_w + (i - lo_off)];
+          creg[r] = segs[(size_t)sg * cap_c + (i - lo_off)];
         }
       }
     }
@@ -346,6 +328,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
 #pragma unroll
   for (int r = 0; r < CR; ++r) {
     fw[r] = 0;
+    if (r < per && creg[r].y != kNoIdx) creg[r].y &= ~kTagBit;                  // the tag repeats what the bitmap says
     if (r < per && has_pen) fw[r] = bm[min(creg[r].y, (uint32_t)V - 1) >> 5];   // uniform condition
   }
 #pragma unroll
@@ -359,43 +342,19 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   __syncthreads();
 
   // ---- (4) penalised values of the history entries; maximum of the list (lowest index on ties)
-  long long corr = 0;               // mass the streaming pass counted for elements that carry a penalty
+  // (the streaming pass, and restream_row, keep history tokens out of the bulk mass, so nothing
+  // has to be taken back out of it)
   uint32_t bkey = 0, bidx = kNoIdx;
   {
     // everything these rounds read from LDS is requested first, then used
     uint32_t mult[SR];
-    BulkRef ref[SR];
-    const float per_elem = (float)S / (float)V;
+#pragma unroll
+    for (int r = 0; r < SR; ++r)
+      if ((uint32_t)(r * NT) < ndist) mult[r] = cnt[r * NT + tid];             // uniform
 #pragma unroll
     for (int r = 0; r < SR; ++r) {
-      if ((uint32_t)(r * NT) < ndist) {                                      // uniform
-        const int v = (int)min(idx[CR + r], (uint32_t)V - 1);
-        // chunk of v: an estimate from the proportion, put right by one step either way
-        int c = min((int)((float)v * per_elem), S - 1);
-        const int lo_c = fs.cbeg[c], hi_c = fs.cbeg[c + 1];
-        c += (v >= hi_c) - (v < lo_c);
-        if (SH) {                               // chunk sizes start over at every shard: make sure
-          while (c + 1 < S && v >= fs.cbeg[c + 1]) ++c;
-          while (c > 0 && v < fs.cbeg[c]) --c;
-        }
-        mult[r] = cnt[r * NT + tid];
-        ref[r].Tc = fs.Tc[c]; ref[r].c = c_row; ref[r].r0 = fs.r0[c]; ref[r].R = fs.R[c];
-      }
-    }
-#pragma unroll
-    for (int r = 0; r < SR; ++r) {
-      if ((uint32_t)(r * NT) < ndist && idx[CR + r] != kNoIdx) {
-        const float rv = raw[r];
-        const float zp = penalise(rv, mult[r], rp.theta, rp.phi, rp.psi);
-        key[CR + r] = __float_as_uint(zp);
-        // the streaming pass saw the raw value: if it was below its chunk's threshold it went into
-        // the bulk sum and has to come out again
-        if (!(rv >= ref[r].Tc)) {
-          const unsigned long long u = bulk_units(bulk_term(rv, ref[r]));
-          const int sh = R_max - ref[r].R;
-          corr += (long long)(sh < 64 ? (u >> sh) : 0ull);
-        }
-      }
+      if ((uint32_t)(r * NT) < ndist && idx[CR + r] != kNoIdx)
+        key[CR + r] = __float_as_uint(penalise(raw[r], mult[r], rp.theta, rp.phi, rp.psi));
     }
   }
 #pragma unroll
@@ -408,18 +367,15 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   {
     const uint32_t wk = last_lane_u32(dpp_scan_max_u32(bkey));
     const uint32_t wi = last_lane_u32(dpp_scan_min_u32(bkey == wk ? bidx : kNoIdx));
-    const unsigned long long uc = dpp_scan_add_u64((unsigned long long)corr);
-    if (lane == kWave - 1) { fs.rkey[wave] = wk; fs.ridx[wave] = wi; fs.rcorr[wave] = (long long)uc; }
+    if (lane == kWave - 1) { fs.rkey[wave] = wk; fs.ridx[wave] = wi; }
     if (__any(anyc) && lane == 0) fs.anyc = 1;
   }
   __syncthreads();
-  long long corr_total = 0;
   bkey = 0; bidx = kNoIdx;
 #pragma unroll
   for (int w = 0; w < kFinalWaves; ++w) {
     const uint32_t ok = fs.rkey[w], oi = fs.ridx[w];
     if (ok > bkey || (ok == bkey && oi < bidx)) { bkey = ok; bidx = oi; }
-    corr_total += fs.rcorr[w];
   }
   // an unpenalised candidate at or above T_row proves that nothing outside the list is larger
   if (!fs.anyc || bidx == kNoIdx) return 6;                                   // uniform
@@ -524,7 +480,6 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     const unsigned long long bc = fs.bulk[c];
     bulk = last_lane_u64(dpp_scan_add_u64((lane < S && sh < 64) ? (bc >> sh) : 0ull));
   }
-  bulk = (long long)bulk > corr_total ? bulk - (unsigned long long)corr_total : 0ull;
   // 2^x with x split into integer and fraction: the fraction goes through the hardware exp2 (1 ulp,
   // far inside the accuracy of the fp32 bulk sums), the integer part is an exponent shift
   const double ln2 = 0.6931471805599453094, log2e = 1.4426950408889634074;
@@ -841,19 +796,20 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
 
 // Second attempt for a row whose candidate list turned out too short: this workgroup reads
 // the row again (it is still in the last-level cache) with a lower threshold `Tc` and leaves
-// the result where the first attempt's data was: one segment of S*4*cap_w entries and one
-// chunk summary.  Same arithmetic as stream_kernel.
+// the result where the first attempt's data was: one segment of S * cap_c entries and one
+// chunk summary.  Same arithmetic as stream_kernel; `bm` (if not null) is the row's history
+// bitmap that the first attempt left in LDS: tokens in it stay out of the bulk mass.
 template <int DT>
 __device__ __attribute__((noinline)) void restream_row(const Args& a, const int b, const RowParams rp, const float Tc,
-                                                       FastShared& fs) {
+                                                       FastShared& fs, const uint32_t* bm) {
   constexpr int NT = kFinalThreads;
   constexpr int EPL = (DT == SIP_F32) ? 4 : 8;
   constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
   const int V = a.V;
   const char* row = reinterpret_cast<const char*>(a.logits) + (size_t)b * (size_t)a.row_stride * ESZ;
-  uint2* region = a.cand + (size_t)b * (size_t)(a.S * kStreamWaves) * (size_t)a.cap_w;
-  const uint32_t cap = (uint32_t)(a.S * kStreamWaves * a.cap_w);
+  uint2* region = a.cand + (size_t)b * (size_t)a.S * (size_t)a.cap_c;
+  const uint32_t cap = (uint32_t)(a.S * a.cap_c);
   const BulkRef ref = make_bulk_ref(Tc, rp);
   const int R = ref.R;
   __syncthreads();
@@ -884,6 +840,8 @@ __device__ __attribute__((noinline)) void restream_row(const Args& a, const int 
         }
       }
       float g = 0.0f;
+      // the elements of one load share a bitmap word (e0 is a multiple of EPL <= 8)
+      const uint32_t hw = bm ? bm[min(e0, V - 1) >> 5] >> (e0 & 31) : 0u;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
         if (e0 + i >= V) z[i] = -INFINITY;
@@ -893,7 +851,7 @@ __device__ __attribute__((noinline)) void restream_row(const Args& a, const int 
           if (pos < cap) region[pos] = make_uint2(__float_as_uint(z[i]), (uint32_t)(e0 + i));
         }
         float e = bulk_term(z[i], ref);
-        e = hit ? 0.0f : e;
+        e = (hit || ((hw >> i) & 1u)) ? 0.0f : e;
         g += e;
       }
       acc += g;
@@ -907,9 +865,8 @@ __device__ __attribute__((noinline)) void restream_row(const Args& a, const int 
     o.bulk = 0;
     for (int w = 0; w < kFinalWaves; ++w) o.bulk += fs.r64[w];
     o.Tc = Tc; o.R = R;
-    o.cnt[0] = fs.rq_n;
-#pragma unroll
-    for (int w = 1; w < 8; ++w) o.cnt[w] = 0;
+    o.cnt = fs.rq_n;
+    o.pad[0] = o.pad[1] = o.pad[2] = 0;
     a.chunks[(size_t)b * a.S] = o;
   }
   // what this workgroup wrote to global memory is read back by other waves of it
@@ -929,17 +886,22 @@ __device__ int whole_row_finish(const Args& a, const int b, const RowParams rp, 
 // kernel was measured to slow all of them down (0.6-1 us each).
 template <int DT, bool SH>
 __device__ __forceinline__ int fast_any(const Args& a, const int b, const RowParams& rp, unsigned char* dyn,
-                                        FastShared& fs, const int S, const int cap_w, const long long ndist_ub) {
+                                        FastShared& fs, const int S, const int cap_c, const long long ndist_ub) {
   constexpr int NT = kFinalThreads;
   int r = kNeedLong;
-  if (ndist_ub <= 2 * NT) r = fast_row<DT, 8, 2, SH>(a, b, rp, dyn, fs, S, cap_w);
-  if (r == kNeedLong) r = fast_row<DT, 8, 8, SH>(a, b, rp, dyn, fs, S, cap_w);
-  if (r == kNeedLong || r == kNeedLongList) r = fast_row<DT, kCandLong, 8, SH>(a, b, rp, dyn, fs, S, cap_w);
+  if (ndist_ub <= 2 * NT) r = fast_row<DT, 8, 2, SH>(a, b, rp, dyn, fs, S, cap_c);
+  if (r == kNeedLong) r = fast_row<DT, 8, 8, SH>(a, b, rp, dyn, fs, S, cap_c);
+  if (r == kNeedLong || r == kNeedLongList) r = fast_row<DT, kCandLong, 8, SH>(a, b, rp, dyn, fs, S, cap_c);
   return (r == kNeedLong || r == kNeedLongList) ? 5 : r;
 }
 
+// The rows that finish_kernel could not settle from their list (it leaves their numbers in
+// Args::rescue_rows): each is taken through the heavier logic below -- the same list in larger
+// register variants, a second and longer list, the continuations over the whole row, the exact
+// multi-pass path -- by one workgroup.  Launched with a fixed, small grid after every
+// finish_kernel; with nothing to rescue a workgroup reads the count and returns.
 template <int DT, bool SH>
-__global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
+__global__ __launch_bounds__(kFinalThreads) void rescue_kernel(Args a_by_value) {
   // The arguments are read where they are used, straight from the kernel-argument segment
   // (the struct is the only parameter, so it starts at offset 0), instead of being held in
   // scalar registers from the first instruction on: there are more of them than registers.
@@ -948,7 +910,11 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   extern __shared__ __align__(16) unsigned char dynraw[];
   __shared__ ExactShared ex;
   __shared__ FastShared fs;
-  const int b = blockIdx.x;
+  const int n_rescue = min(max(*a.rescue_n, 0), a.B);
+#pragma nounroll
+  for (int qi = blockIdx.x; qi < n_rescue; qi += gridDim.x) {
+  if (qi != (int)blockIdx.x) __syncthreads();      // the row before this one is done with the tables in LDS
+  const int b = min(max(a.rescue_rows[qi], 0), a.B - 1);
   const RowParams rp = load_row_params(a, b);
   int how = 2;                                   // 2: not eligible for the single-pass path
   int code = 0;
@@ -966,10 +932,10 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
     }
     if (threadIdx.x == 0) fs.ndist_out = -1;
     // At most two attempts, written as a loop so that the kernel holds one copy of the code.
-    int S = a.S, cap_w = a.cap_w;
+    int S = a.S, cap_c = a.cap_c;
 #pragma nounroll
     for (int attempt = 0; attempt < 2; ++attempt) {
-      int r = fast_any<DT, SH>(a, b, rp, dynraw, fs, S, cap_w, ndist_ub);
+      int r = fast_any<DT, SH>(a, b, rp, dynraw, fs, S, cap_c, ndist_ub);
       bool cut_below = false;
       if (attempt == 0 && r == kWholeRowCut) {
         // a nucleus somewhat longer than the list is cheaper to settle from a second list than
@@ -998,13 +964,16 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
       }
       if (!(t_new < t_old)) break;
       if (SH && !gathered) { gather_row<DT>(a, b); gathered = true; }
-      restream_row<DT>(a, b, rp, t_new, fs);
+      {
+        const bool has_pen = (hr.hi > hr.lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
+        restream_row<DT>(a, b, rp, t_new, fs, has_pen ? reinterpret_cast<const uint32_t*>(dynraw) : nullptr);
+      }
       if (cut_below && fs.rq_n > (uint32_t)(kFinalThreads * kCandLong)) {
         // the second list does not fit either: the first attempt's tables are untouched, go on from them
         how = kWholeRowCut;
         break;
       }
-      S = 1; cap_w = a.S * kStreamWaves * a.cap_w;
+      S = 1; cap_c = a.S * a.cap_c;
     }
   }
   if (how == kWholeRowCut || how == kWholeRow) {
@@ -1022,6 +991,7 @@ __global__ __launch_bounds__(kFinalThreads) void final_kernel(Args a_by_value) {
   if (a.slot) {                                  // device-resident history: the row's id joins it
     __syncthreads();
     if (threadIdx.x == 0) state_append_row(a, b, target != 0 ? fs.ndist_out : -1);
+  }
   }
 }
 

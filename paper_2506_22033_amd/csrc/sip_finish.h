@@ -1,0 +1,695 @@
+// Finishing kernel of the single-pass path: one workgroup per row turns what the streaming
+// kernel left behind -- a list of a few thousand (value, index) entries that holds every
+// element at or above a value threshold and every element that carries a penalty, plus the
+// integer mass of everything else -- into the row's token, its logprob and the best-n list.
+// It never reads the logits.
+//
+// Steps (Sec. 2.1 step 3 (1)-(3); Sec. 5.1 ApplyPenalty / temperature / softmax / filters /
+// draw), every sum an integer sum (masses in units of 2^-40 of the maximum's mass) so that no
+// result depends on the order in which threads add:
+//   (1) multiplicities of the history tokens in an LDS hash table (frequency penalty only);
+//   (2) penalised value of every tagged entry, maximum of the list (lowest index on ties);
+//   (3) s = z'/tau (IEEE), key, mass and value bin of every entry; count and mass per bin
+//       (1024 linear bins between the completeness threshold and the maximum);
+//   (4) one descending scan over the bins gives, per bin, the number and the mass of all
+//       entries above it: that locates the bin of the k-th largest, of the n-th best and of
+//       the nucleus cut, and is the position at which the bin's entries are then laid down in
+//       LDS (a counting sort by bin), so that the members of any bin, and everything above
+//       it, are a contiguous range;
+//   (5) one wave settles top-k, then top-p, inside their bins (all pairs through readlane,
+//       or by descending over the distinct keys of a bin with many ties) while another wave
+//       ranks the best-n;
+//   (6) draw: kept sets of up to 64 entries by that same wave from its registers; larger
+//       ones through a histogram of kept mass over 1024 vocabulary-index bins.
+//
+// Whatever the list cannot prove (a cut that may lie below the completeness threshold, an
+// overflow, a bin with too many members, ...) makes the row's number go to the rescue queue
+// with a reason code; rescue_kernel (sip_final.h) then takes the row over.
+#pragma once
+#include "sip_device.h"
+#include "sip_stream.h"
+
+namespace sip {
+constexpr int kFinThreads = 512;
+constexpr int kFinWaves = kFinThreads / kWave;
+constexpr int kFinCR = 8;                              // list entries a thread holds in registers
+constexpr int kFinBatch = kFinThreads * kFinCR;        // entries per batch
+constexpr int kFinMaxBatches = 3;                      // lists up to 12288 entries
+constexpr int kFinBins = 1024;
+constexpr int kFinBPT = kFinBins / kFinThreads;        // bins per thread in the scans
+constexpr int kFinList = 4352;                         // entries of the bin-sorted list in LDS
+constexpr int kFinHash = 4096;                         // slots of the multiplicity table
+constexpr int kFinHashMax = 3072;                      // distinct history tokens it takes
+constexpr int kFinMembers = 512;                       // members of one index bin the draw resolves
+constexpr int kFinTopMax = 256;                        // entries at or above the bin of the n-th best
+constexpr int kFinKeySteps = 64;                       // distinct keys of one bin that are stepped through
+constexpr uint32_t kFinNone = 0xFFFFFFFFu;
+constexpr int kFinDrawBig = -1;                        // internal: the draw goes through the index histogram
+static_assert(kFinBPT == 2, "scan code below is written for two bins per thread");
+
+struct __align__(16) FinShared {
+  uint32_t hcnt[kFinBins];                  // entries per value bin
+  uint32_t off[kFinBins];                   // entries in all higher bins = where the bin starts in the sorted list
+  uint32_t fill[kFinBins];                  // entries of the bin laid down so far
+  unsigned long long hmass[kFinBins];       // mass per value bin; after the scan: mass of all higher bins
+  unsigned long long hidx[kFinBins];        // kept mass per vocabulary-index bin
+  union {
+    struct { uint32_t skey[kFinList]; uint32_t sidx[kFinList]; } list;      // entries sorted by bin, descending
+    struct { uint32_t key[kFinHash]; uint32_t val[kFinHash]; } hash;        // token -> multiplicity (before the list exists)
+  } u;
+  uint32_t m_key[kFinMembers];
+  uint32_t m_idx[kFinMembers];
+  unsigned long long m_E[kFinMembers];
+  unsigned long long r64[kFinWaves];
+  uint32_t r32[kFinWaves], rkey[kFinWaves], ridx[kFinWaves];
+  int bin_k, bin_n, bin_d;
+  int code, code_top;
+  uint32_t hash_fail, n_memb, key_cut, n_hi;
+  uint32_t token, token_key;
+  unsigned long long before_d;
+};
+
+// Sum / maximum over the 64 lanes, result in every lane (through scalar registers).
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) { return last_lane_u32(dpp_scan_max_u32(v)); }
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return last_lane_u32(dpp_scan_min_u32(v)); }
+__device__ __forceinline__ uint32_t wave_add_u32(uint32_t v) { return last_lane_u32(dpp_scan_add_u32(v)); }
+__device__ __forceinline__ unsigned long long wave_add_u64(unsigned long long v) { return last_lane_u64(dpp_scan_add_u64(v)); }
+
+// Row b, start to finish.  Returns 1 (finished: outputs written) or the reason why the list
+// does not settle the row.  Every return value is workgroup-uniform.
+__device__ __forceinline__ int finish_row(const Args& a, const int b, const RowParams& rp, FinShared& fs) {
+  constexpr int NT = kFinThreads;
+  constexpr int CR = kFinCR;
+  const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+  const int V = a.V;
+  const int S = a.S;
+  auto scaled_s = [&](float z) { return rp.greedy ? z : __fdiv_rn(z, rp.tau); };
+
+  // ---- (0) chunk summaries (lane c reads chunk c), history extent, first history tokens; clear LDS
+  const HistRange hr = hist_range(a, b);
+  const bool has_pen = (hr.hi > hr.lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
+  const bool need_hash = has_pen && rp.phi != 0.0f;
+  uint32_t my_cnt = 0;
+  unsigned long long my_bulk = 0;
+  float Tc;
+  int R;
+  {
+    const ChunkOut co = a.chunks[(size_t)b * S + min(lane, S - 1)];
+    if (lane < S) { my_cnt = co.cnt; my_bulk = co.bulk; }
+    Tc = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(co.Tc)));   // the chunks of a row share
+    R = __builtin_amdgcn_readfirstlane(co.R);                                                      // threshold and exponent
+  }
+  int htok[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const long long i = hr.lo + tid + (long long)j * NT;
+    htok[j] = (need_hash && i < hr.hi) ? a.tokens[i] : -1;
+  }
+  {
+    // hcnt, off, fill, hmass, hidx are contiguous: 28 KB, of which `off` need not be cleared
+    uint4* z4 = reinterpret_cast<uint4*>(fs.hcnt);
+    for (int i = tid; i < kFinBins * 4 / 16; i += NT) z4[i] = make_uint4(0, 0, 0, 0);
+    z4 = reinterpret_cast<uint4*>(fs.fill);
+    for (int i = tid; i < kFinBins * 20 / 16; i += NT) z4[i] = make_uint4(0, 0, 0, 0);
+    if (need_hash) {
+      uint4* k4 = reinterpret_cast<uint4*>(fs.u.hash.key);
+      for (int i = tid; i < kFinHash * 4 / 16; i += NT) k4[i] = make_uint4(kFinNone, kFinNone, kFinNone, kFinNone);
+      uint4* v4 = reinterpret_cast<uint4*>(fs.u.hash.val);
+      for (int i = tid; i < kFinHash * 4 / 16; i += NT) v4[i] = make_uint4(0, 0, 0, 0);
+    }
+    if (tid == 0) {
+      fs.bin_k = -1; fs.bin_n = -1; fs.bin_d = -1; fs.code = 0; fs.code_top = 0; fs.hash_fail = 0; fs.n_memb = 0;
+      fs.token = kFinNone; fs.token_key = 0;
+    }
+  }
+  // row constants that take long arithmetic, worked out while the loads above travel
+  const bool minp_on = !rp.greedy && rp.min_p > 0.0f;
+  const float t_minp = minp_on ? (float)log((double)rp.min_p) : 0.0f;
+  const unsigned long long j24 = rp.greedy ? 0ull : (unsigned long long)(philox_word0(a.seed, rp.row_id, step_of(a)) >> 8);
+  const bool k_act = !rp.greedy && rp.top_k >= 2 && rp.top_k < V;
+  const uint32_t n_top = (uint32_t)max(0, min(a.k_lp, V));
+
+  // list geometry: entry i of the row's list lies in segment c = #{c' >= 1 : i >= first[c']}
+  // at segs[i + sum over those c' of (cap_c - cnt[c'-1])]
+  const uint32_t incl = dpp_scan_add_u32(my_cnt);
+  const uint32_t excl = incl - my_cnt;
+  const bool any_over = __any(my_cnt > (uint32_t)a.cap_c);                   // includes the overflow mark
+  const uint32_t total = last_lane_u32(incl);
+  const unsigned long long bulk = wave_add_u64(my_bulk);
+  if (any_over || !(Tc == Tc)) return 3;                                     // uniform
+  if (total > (uint32_t)(kFinBatch * kFinMaxBatches)) return 5;              // uniform
+  const int nb = (int)((total + kFinBatch - 1) / kFinBatch);                 // uniform
+  uint2* segs = a.cand + (size_t)b * (size_t)S * (size_t)a.cap_c;
+  uint32_t adr[CR];                                                          // where this thread's entries of batch 0 lie
+  {
+#pragma unroll
+    for (int r = 0; r < CR; ++r) adr[r] = (uint32_t)(r * NT + tid);
+    for (int c = 1; c < S; ++c) {
+      const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)excl, c);
+      const uint32_t gap = (uint32_t)a.cap_c - (uint32_t)__builtin_amdgcn_readlane((int)my_cnt, c - 1);
+#pragma unroll
+      for (int r = 0; r < CR; ++r) adr[r] += ((uint32_t)(r * NT + tid) >= first) ? gap : 0u;
+    }
+  }
+  // address of entry i of a later batch (rare: lists longer than one batch)
+  auto address_of = [&](uint32_t i) {
+    uint32_t ad = i;
+    for (int c = 1; c < S; ++c) {
+      const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)excl, c);
+      const uint32_t gap = (uint32_t)a.cap_c - (uint32_t)__builtin_amdgcn_readlane((int)my_cnt, c - 1);
+      ad += (i >= first) ? gap : 0u;
+    }
+    return ad;
+  };
+  uint2 creg[CR];                          // (bits of z, later of z'; index | tag, later index)
+  auto load_batch = [&](int bt) {
+#pragma unroll
+    for (int r = 0; r < CR; ++r) {
+      const uint32_t i = (uint32_t)(bt * kFinBatch + r * NT + tid);
+      creg[r] = make_uint2(0u, kFinNone);
+      if (i < total) creg[r] = segs[bt == 0 ? adr[r] : address_of(i)];
+    }
+  };
+  load_batch(0);
+  __syncthreads();                                                           // LDS is clear
+
+  // ---- (1) multiplicities: open addressing keyed by token, one CAS to claim or find the slot,
+  // one add to count
+  if (need_hash) {
+    uint32_t mine = 0;                     // slots this thread claimed = distinct tokens it saw first
+    auto insert = [&](int t) {
+      if (t < 0 || t >= V) return;
+      uint32_t h = ((uint32_t)t * 0x9E3779B1u) >> 20;
+      for (int probe = 0; probe < kFinHash; ++probe) {
+        const uint32_t old = atomicCAS(&fs.u.hash.key[h], kFinNone, (uint32_t)t);
+        if (old == kFinNone || old == (uint32_t)t) {
+          atomicAdd(&fs.u.hash.val[h], 1u);
+          mine += old == kFinNone;
+          return;
+        }
+        h = (h + 1) & (kFinHash - 1);
+      }
+      fs.hash_fail = 1;                    // table full
+    };
+    insert(htok[0]);
+    insert(htok[1]);
+    for (long long i = hr.lo + tid + 2ll * NT; i < hr.hi; i += NT) insert(a.tokens[i]);
+    const uint32_t wtot = wave_add_u32(mine);
+    if (lane == 0) fs.r32[wave] = wtot;
+    __syncthreads();
+    uint32_t ndist = 0;
+#pragma unroll
+    for (int w = 0; w < kFinWaves; ++w) ndist += fs.r32[w];
+    if (fs.hash_fail || ndist > (uint32_t)kFinHashMax) return 4;            // uniform
+  }
+  auto multiplicity = [&](uint32_t t) -> uint32_t {
+    uint32_t h = (t * 0x9E3779B1u) >> 20;
+    for (int probe = 0; probe < kFinHash; ++probe) {
+      if (fs.u.hash.key[h] == t) return fs.u.hash.val[h];
+      h = (h + 1) & (kFinHash - 1);
+    }
+    return 1u;                             // not reached: every tagged token is in the history
+  };
+
+  // ---- (2) penalised values (Sec. 5.1 ApplyPenalty); maximum of the list, lowest index on ties
+  uint32_t bkey = 0, bidx = kFinNone;
+  for (int bt = 0; bt < nb; ++bt) {
+    if (bt > 0) load_batch(bt);
+#pragma unroll
+    for (int r = 0; r < CR; ++r) {
+      if ((uint32_t)(bt * kFinBatch + r * NT) < total && creg[r].y != kFinNone) {   // first condition uniform
+        const uint32_t v = creg[r].y & ~kTagBit;
+        float z = __uint_as_float(creg[r].x);
+        if (creg[r].y & kTagBit) {
+          z = penalise(z, need_hash ? multiplicity(v) : 1u, rp.theta, rp.phi, rp.psi);
+          // lists of several batches are read again from memory: leave the penalised value there
+          if (nb > 1) segs[bt == 0 ? adr[r] : address_of((uint32_t)(bt * kFinBatch + r * NT + tid))] = make_uint2(__float_as_uint(z), v);
+        }
+        creg[r] = make_uint2(__float_as_uint(z), v < (uint32_t)V ? v : kFinNone);
+        const uint32_t kz = key_of(z);
+        if (creg[r].y != kFinNone && (kz > bkey || (kz == bkey && v < bidx))) { bkey = kz; bidx = v; }
+      }
+    }
+  }
+  {
+    const uint32_t wk = wave_max_u32(bkey);
+    const uint32_t wi = wave_min_u32(bkey == wk ? bidx : kFinNone);
+    if (lane == 0) { fs.rkey[wave] = wk; fs.ridx[wave] = wi; }
+  }
+  __syncthreads();
+  bkey = 0; bidx = kFinNone;
+#pragma unroll
+  for (int w = 0; w < kFinWaves; ++w) {
+    const uint32_t ok = fs.rkey[w], oi = fs.ridx[w];
+    if (ok > bkey || (ok == bkey && oi < bidx)) { bkey = ok; bidx = oi; }
+  }
+  // Every element outside the list is unpenalised and below Tc: a list maximum at or above Tc
+  // is the row's maximum, and its lowest index the row's.
+  const float zmax = value_of(bkey);
+  if (bidx == kFinNone || !(zmax >= Tc)) return 6;                            // uniform
+  const float m = scaled_s(zmax);
+  const float s_c = scaled_s(Tc);          // entries with s > s_c: every such element of the row is in the list
+  const uint32_t key_c = key_of(s_c);
+  const float span = __fsub_rn(m, s_c);
+  if (!(span >= 0.0f) || !(span < 3.0e38f)) return 7;                         // uniform
+  const float binscale = span > 0.0f ? (float)(kFinBins - 2) / span : 0.0f;
+  auto bin_of = [&](float s, uint32_t k) -> int {
+    if (k <= key_c) return 0;
+    const int q = (int)(__fsub_rn(s, s_c) * binscale);
+    return 1 + min(kFinBins - 2, max(q, 0));
+  };
+  auto mass = [&](float s) { return fix_of(expf(__fsub_rn(s, m))); };
+  auto emit = [&](uint32_t token, uint32_t token_key, double lnZ) {          // one thread
+    a.out_ids[b] = (int)token;
+    if (a.k_lp >= 0) {
+      const int cols = 1 + a.k_lp;
+      a.out_lp_ids[(size_t)b * cols] = (int)token;
+      a.out_lp[(size_t)b * cols] = (float)((double)value_of(token_key) - (double)m - lnZ);
+    }
+    if (a.slot) state_append_row(a, b, -1);
+  };
+  if (rp.greedy && a.k_lp < 0) {           // the arg max is all that is asked for
+    if (tid == 0) emit(bidx, key_of(m), 0.0);
+    return 1;
+  }
+
+  // ---- (3) keys, masses, value histogram
+  for (int bt = 0; bt < nb; ++bt) {
+    if (nb > 1) load_batch(bt);
+#pragma unroll
+    for (int r = 0; r < CR; ++r) {
+      if ((uint32_t)(bt * kFinBatch + r * NT) < total && creg[r].y != kFinNone) {
+        const float s = scaled_s(__uint_as_float(creg[r].x));
+        const uint32_t k = key_of(s);
+        const int bin = bin_of(s, k);
+        const unsigned long long E = mass(s);
+        atomicAdd(&fs.hcnt[bin], 1u);
+        if (E) atomicAdd(&fs.hmass[bin], E);
+        creg[r].x = k;                     // from here on: the key of s
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- (4) descending scan over the bins: thread t owns bins kFinBins-1-2t and kFinBins-2-2t
+  unsigned long long S_cand;
+  {
+    const int b0 = kFinBins - 1 - kFinBPT * tid;
+    uint32_t c[kFinBPT];
+    unsigned long long w[kFinBPT];
+#pragma unroll
+    for (int j = 0; j < kFinBPT; ++j) { c[j] = fs.hcnt[b0 - j]; w[j] = fs.hmass[b0 - j]; }
+    const uint32_t csum = c[0] + c[1];
+    const unsigned long long msum = w[0] + w[1];
+    const uint32_t cinc = dpp_scan_add_u32(csum);
+    const unsigned long long minc = dpp_scan_add_u64(msum);
+    if (lane == kWave - 1) { fs.r32[wave] = cinc; fs.r64[wave] = minc; }
+    __syncthreads();
+    uint32_t cex = cinc - csum;
+    unsigned long long mex = minc - msum, mtot = 0;
+#pragma unroll
+    for (int ww = 0; ww < kFinWaves; ++ww) {
+      const uint32_t c32 = fs.r32[ww];
+      const unsigned long long m64 = fs.r64[ww];
+      if (ww < wave) { cex += c32; mex += m64; }
+      mtot += m64;
+    }
+    S_cand = mtot;
+    const uint32_t k = (uint32_t)rp.top_k;
+#pragma unroll
+    for (int j = 0; j < kFinBPT; ++j) {
+      const int bin = b0 - j;
+      fs.off[bin] = cex;
+      fs.hmass[bin] = mex;
+      if (bin >= 1) {                                                          // bin 0 is the incomplete region
+        if (k_act && cex < k && k <= cex + c[j]) fs.bin_k = bin;
+        if (n_top > 0 && cex < n_top && n_top <= cex + c[j]) fs.bin_n = bin;
+      }
+      cex += c[j]; mex += w[j];
+    }
+  }
+  __syncthreads();
+  const int bin_k = fs.bin_k, bin_n = fs.bin_n;
+  if ((k_act && bin_k < 0) || (n_top > 0 && bin_n < 0)) return 8;              // uniform: k-th / n-th not provably in the list
+
+  // total mass: the list's plus the bulk's, brought to units of 2^-40 of the maximum's mass.
+  // 2^x with x split into integer and fraction: the fraction goes through the hardware exp2,
+  // the integer part is an exponent shift.
+  const double ln2 = 0.6931471805599453094, log2e = 1.4426950408889634074;
+  const double x = fmin(fmax((double)R + 10.0 - (double)m * log2e, -2000.0), 2000.0);
+  const double xi = floor(x);
+  const double bulk_rel = ldexp((double)bulk * (double)__builtin_amdgcn_exp2f((float)(x - xi)), (int)xi);
+  const unsigned long long S0 = S_cand + (bulk_rel < 9.0e18 ? (unsigned long long)bulk_rel : 0ull);
+  int e2;
+  const float f2 = (float)frexp((double)S0, &e2);
+  const double lnZ = ((double)__builtin_amdgcn_logf(f2) + (double)(e2 - kFixShift)) * ln2;
+
+  // lowest bin any later step looks into: everything from there up is laid down, sorted by bin
+  int bin_minp = 1;                        // entries below this bin fail min-p (the reverse need not hold)
+  if (minp_on) {
+    const float sm = __fadd_rn(m, t_minp);
+    const float sm_lo = sm - fabsf(sm) * 1.0e-6f - 1.0e-30f;
+    bin_minp = max(1, bin_of(sm_lo, key_of(sm_lo)));
+  }
+  // every element missing from the list fails min-p  <=>  the completeness threshold itself fails it
+  const bool minp_bounds = minp_on && !(__fsub_rn(s_c, m) >= t_minp);
+  int lowbin = kFinBins;
+  if (!rp.greedy) lowbin = k_act ? bin_k : bin_minp;
+  if (n_top > 0) lowbin = min(lowbin, bin_n);
+  uint32_t n_list = 0;
+  if (lowbin < kFinBins) {
+    n_list = fs.off[lowbin] + fs.hcnt[lowbin];
+    if (n_list > (uint32_t)kFinList) return 9;                                 // uniform
+    for (int bt = 0; bt < nb; ++bt) {
+      if (nb > 1) {                         // keys again (the registers hold the last batch only)
+        load_batch(bt);
+#pragma unroll
+        for (int r = 0; r < CR; ++r)
+          if (creg[r].y != kFinNone) creg[r].x = key_of(scaled_s(__uint_as_float(creg[r].x)));
+      }
+#pragma unroll
+      for (int r = 0; r < CR; ++r) {
+        if ((uint32_t)(bt * kFinBatch + r * NT) < total && creg[r].y != kFinNone) {
+          const uint32_t k = creg[r].x;
+          const int bin = bin_of(value_of(k), k);
+          if (bin >= lowbin) {
+            const uint32_t pos = fs.off[bin] + atomicAdd(&fs.fill[bin], 1u);
+            if (pos < (uint32_t)kFinList) { fs.u.list.skey[pos] = k; fs.u.list.sidx[pos] = creg[r].y; }
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- (5) wave 1: best-n.  The range [0, nt) of the sorted list holds every element of the
+  // row at or above the bin of the n-th best, so an entry's rank in it is its rank in the row.
+  if (wave == 1 && n_top > 0) {
+    const uint32_t nt = fs.off[bin_n] + fs.hcnt[bin_n];
+    const int cols = 1 + a.k_lp;
+    if (nt <= (uint32_t)kWave) {
+      const uint32_t kt = (uint32_t)lane < nt ? fs.u.list.skey[lane] : 0u;
+      const uint32_t v = (uint32_t)lane < nt ? fs.u.list.sidx[lane] : kFinNone;
+      uint32_t rank = 0;
+      for (uint32_t q = 0; q < nt; ++q) {
+        const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
+        const uint32_t iq = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q);
+        rank += (uint32_t)((kq > kt) | ((kq == kt) & (iq < v)));
+      }
+      if ((uint32_t)lane < nt && rank < n_top) {
+        a.out_lp_ids[(size_t)b * cols + 1 + rank] = (int)v;
+        a.out_lp[(size_t)b * cols + 1 + rank] = (float)((double)value_of(kt) - (double)m - lnZ);
+      }
+    } else if (nt <= (uint32_t)kFinTopMax) {
+      for (uint32_t e = lane; e < nt; e += kWave) {
+        const uint32_t kt = fs.u.list.skey[e], v = fs.u.list.sidx[e];
+        uint32_t rank = 0;
+        for (uint32_t q = 0; q < nt; ++q) {
+          const uint32_t kq = fs.u.list.skey[q];
+          rank += (kq > kt || (kq == kt && fs.u.list.sidx[q] < v)) ? 1u : 0u;
+        }
+        if (rank < n_top) {
+          a.out_lp_ids[(size_t)b * cols + 1 + rank] = (int)v;
+          a.out_lp[(size_t)b * cols + 1 + rank] = (float)((double)value_of(kt) - (double)m - lnZ);
+        }
+      }
+    } else if (lane == 0) {
+      fs.code_top = 9;                      // too many ties around the n-th best for this kernel
+    }
+  }
+
+  // ---- (5) wave 0: top-k, top-p, and the draw if the kept set is small
+  auto kept_key = [&](uint32_t k, uint32_t key_cut) {
+    return k >= key_cut && k > key_c && (!minp_on || __fsub_rn(value_of(k), m) >= t_minp);
+  };
+  if (wave == 0 && rp.greedy) {
+    if (lane == 0) { fs.token = bidx; fs.token_key = key_of(m); fs.code = 1; }
+  } else if (wave == 0) {
+    int code = 0;
+    uint32_t key_k = 0;
+    unsigned long long S1 = S0;
+    // Members of a bin: the range [p0, p0 + nm) of the sorted list.  Up to 64 of them sit one per
+    // lane and are compared through readlane; more (many equal values: bf16 logits) are stepped
+    // through by distinct key, largest first, each step one pass of the wave over the members.
+    // next_key(): the largest member key below `below`, how many members have it and their mass.
+    auto next_key = [&](uint32_t p0, uint32_t nm, uint32_t below, uint32_t& cnt_eq, unsigned long long& mass_eq) -> uint32_t {
+      uint32_t best = 0, n = 0;
+      bool any = false;
+      for (uint32_t e = lane; e < nm; e += kWave) {
+        const uint32_t k = fs.u.list.skey[p0 + e];
+        if (k < below && (!any || k > best)) { best = k; n = 0; any = true; }
+        n += (any && k == best) ? 1u : 0u;
+      }
+      const uint32_t top = wave_max_u32(any ? best : 0u);
+      const bool mine = any && best == top;
+      cnt_eq = wave_add_u32(mine ? n : 0u);
+      mass_eq = (unsigned long long)cnt_eq * mass(value_of(top));             // equal keys, equal masses
+      return __any(any) ? top : kFinNone;
+    };
+    if (k_act) {
+      const uint32_t p0 = fs.off[bin_k], nm = fs.hcnt[bin_k];
+      const uint32_t k_rem = (uint32_t)rp.top_k - p0;                          // 1 <= k_rem <= nm
+      unsigned long long part = 0;
+      if (nm <= (uint32_t)kWave) {
+        const uint32_t kt = (uint32_t)lane < nm ? fs.u.list.skey[p0 + lane] : 0u;
+        const unsigned long long Et = (uint32_t)lane < nm ? mass(value_of(kt)) : 0ull;
+        uint32_t gt = 0, ge = 0;
+        unsigned long long sum_ge = 0;
+        for (uint32_t q = 0; q < nm; ++q) {
+          const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
+          const unsigned long long Eq = readlane_u64(Et, (int)q);
+          gt += kq > kt; ge += kq >= kt;
+          sum_ge += kq >= kt ? Eq : 0ull;
+        }
+        const unsigned long long ball = __ballot((uint32_t)lane < nm && gt < k_rem && k_rem <= ge);
+        if (ball) {
+          const int src = __ffsll((long long)ball) - 1;
+          key_k = (uint32_t)__builtin_amdgcn_readlane((int)kt, src);
+          part = readlane_u64(sum_ge, src);
+        } else {
+          code = 8;
+        }
+      } else {
+        uint32_t below = kFinNone, seen = 0;
+        int step = 0;
+        for (; step < kFinKeySteps; ++step) {
+          uint32_t ce;
+          unsigned long long me;
+          const uint32_t k = next_key(p0, nm, below, ce, me);
+          if (k == kFinNone) { code = 8; break; }
+          seen += ce; part += me; below = k;
+          if (seen >= k_rem) { key_k = k; break; }
+        }
+        if (step == kFinKeySteps) code = 9;
+      }
+      S1 = fs.hmass[bin_k] + part;
+    }
+    uint32_t key_cut = key_k;
+    if (code == 0 && rp.top_p < 1.0f) {
+      // ---- top-p: the lowest bin whose entries may still be kept (mass of everything above it
+      // short of the limit), then the cut inside it
+      const double lim = ceil((double)rp.top_p * (double)S1);
+      const unsigned long long limit = lim > 0.0 ? (unsigned long long)lim : 0ull;
+      // (without top-k, bins below the one that min-p reaches are not in the sorted list, and
+      // need not be: their entries fail min-p wherever the nucleus ends)
+      const int lowb = k_act ? bin_k : bin_minp;
+      int bin_p = 1 << 30, bin_low = 1 << 30;
+      {
+        constexpr int PER = kFinBins / kWave;                                  // 16 bins per lane
+        const int base = lane * PER;
+#pragma unroll
+        for (int j = PER - 1; j >= 0; --j) {                                   // descending: the last hit is the lowest
+          const int bin = base + j;
+          const uint32_t c = fs.hcnt[bin];
+          const unsigned long long above = fs.hmass[bin];
+          if (bin >= 1 && c) bin_low = bin;
+          if (bin >= lowb && c && above < limit) bin_p = bin;
+        }
+        bin_p = (int)wave_min_u32((uint32_t)bin_p);
+        bin_low = (int)wave_min_u32((uint32_t)bin_low);
+      }
+      if (bin_p >= kFinBins) {
+        code = 10;                                                             // p <= 0
+      } else {
+        const uint32_t p0 = fs.off[bin_p], nm = fs.hcnt[bin_p];
+        const unsigned long long base_mass = fs.hmass[bin_p];
+        uint32_t key_p = kFinNone;
+        bool dropped = false;
+        if (nm <= (uint32_t)kWave) {
+          const bool member = (uint32_t)lane < nm;
+          const uint32_t kt = member ? fs.u.list.skey[p0 + lane] : 0u;
+          const unsigned long long Et = member ? mass(value_of(kt)) : 0ull;
+          unsigned long long G = base_mass;
+          for (uint32_t q = 0; q < nm; ++q) {
+            const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
+            const unsigned long long Eq = readlane_u64(Et, (int)q);
+            G += kq > kt ? Eq : 0ull;
+          }
+          const bool in_k1 = member && kt >= key_k;
+          key_p = wave_min_u32((in_k1 && G < limit) ? kt : kFinNone);
+          dropped = __any(in_k1 && !(G < limit));
+        } else {
+          unsigned long long G = base_mass;
+          uint32_t below = kFinNone;
+          int step = 0;
+          for (; step < kFinKeySteps; ++step) {
+            uint32_t ce;
+            unsigned long long me;
+            const uint32_t k = next_key(p0, nm, below, ce, me);
+            if (k == kFinNone || k < key_k) break;                             // no more members of K1
+            if (!(G < limit)) { dropped = true; break; }
+            key_p = k; G += me; below = k;
+          }
+          if (step == kFinKeySteps) code = 9;
+        }
+        // the cut is proven to lie inside the list if some complete entry fell on its far side
+        const bool inside = k_act || bin_p > bin_low || dropped;
+        if (code == 0 && key_p == kFinNone) code = 10;
+        if (code == 0 && !inside && !minp_bounds) code = 11;                   // the nucleus may reach below the list
+        key_cut = max(key_k, key_p);
+      }
+    } else if (code == 0 && !k_act && !minp_bounds) {
+      code = minp_on ? 12 : 13;                                                // min-p reaches below the list / no filter at all
+    }
+    if (code == 0) {
+      // ---- (6) draw.  The kept set is a range [0, n_hi) of the sorted list minus the entries of
+      // its last bins that fail the exact tests.
+      int bin_c = key_cut ? bin_of(value_of(key_cut), key_cut) : 1;
+      bin_c = max(max(bin_c, 1), minp_on ? bin_minp : 1);
+      const uint32_t n_hi = fs.off[bin_c] + fs.hcnt[bin_c];
+      if (n_hi <= (uint32_t)kWave) {
+        const bool have = (uint32_t)lane < n_hi;
+        const uint32_t kt = have ? fs.u.list.skey[lane] : 0u;
+        const uint32_t v = have ? fs.u.list.sidx[lane] : kFinNone;
+        const unsigned long long Et = (have && kept_key(kt, key_cut)) ? mass(value_of(kt)) : 0ull;
+        const unsigned long long S3 = wave_add_u64(Et);
+        const unsigned long long target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);   // floor(j * S3 / 2^24)
+        unsigned long long C = 0;
+        for (uint32_t q = 0; q < n_hi; ++q) {
+          const uint32_t iq = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q);
+          const unsigned long long Eq = readlane_u64(Et, (int)q);
+          C += iq <= v ? Eq : 0ull;
+        }
+        // kept entries have mass > 0 and distinct indices: exactly one of them is the first crossing
+        const unsigned long long ball = __ballot(Et > 0 && C > target && C - Et <= target);
+        if (ball) {
+          const int src = __ffsll((long long)ball) - 1;
+          if (lane == 0) {
+            fs.token = (uint32_t)__builtin_amdgcn_readlane((int)v, src);
+            fs.token_key = (uint32_t)__builtin_amdgcn_readlane((int)kt, src);
+          }
+          code = 1;
+        } else {
+          code = 14;                                                           // no kept mass
+        }
+      } else {
+        if (lane == 0) { fs.key_cut = key_cut; fs.n_hi = n_hi; }
+        code = kFinDrawBig;
+      }
+    }
+    if (lane == 0) fs.code = code;
+  }
+  __syncthreads();
+  int code = fs.code_top ? fs.code_top : fs.code;                              // a failure of the best-n ranking stands
+  if (code == kFinDrawBig) {
+    // ---- (6') kept mass per vocabulary-index bin, prefix, then the crossing inside one bin
+    const uint32_t key_cut = fs.key_cut, n_hi = fs.n_hi;
+    int ishift = 0;
+    while (((V - 1) >> ishift) >= kFinBins) ++ishift;
+    for (uint32_t p = tid; p < n_hi; p += NT) {
+      const uint32_t k = fs.u.list.skey[p];
+      if (kept_key(k, key_cut)) {
+        const unsigned long long E = mass(value_of(k));
+        if (E) atomicAdd(&fs.hidx[fs.u.list.sidx[p] >> ishift], E);
+      }
+    }
+    __syncthreads();
+    unsigned long long target;
+    {
+      const int b0 = kFinBPT * tid;                      // ascending index order
+      const unsigned long long w0 = fs.hidx[b0], w1 = fs.hidx[b0 + 1];
+      const unsigned long long msum = w0 + w1;
+      const unsigned long long minc = dpp_scan_add_u64(msum);
+      if (lane == kWave - 1) fs.r64[wave] = minc;
+      __syncthreads();
+      unsigned long long ex = minc - msum, S3 = 0;
+#pragma unroll
+      for (int ww = 0; ww < kFinWaves; ++ww) {
+        const unsigned long long m64 = fs.r64[ww];
+        if (ww < wave) ex += m64;
+        S3 += m64;
+      }
+      target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);               // floor(j * S3 / 2^24)
+      if (ex <= target && target < ex + w0) { fs.bin_d = b0; fs.before_d = ex; }
+      ex += w0;
+      if (ex <= target && target < ex + w1) { fs.bin_d = b0 + 1; fs.before_d = ex; }
+    }
+    __syncthreads();
+    const int bin_d = fs.bin_d;
+    if (bin_d < 0) return 14;                                                  // uniform (no kept mass)
+    for (uint32_t p = tid; p < n_hi; p += NT) {
+      const uint32_t k = fs.u.list.skey[p], v = fs.u.list.sidx[p];
+      if ((int)(v >> ishift) == bin_d && kept_key(k, key_cut)) {
+        const unsigned long long E = mass(value_of(k));
+        if (E) {
+          const uint32_t q = atomicAdd(&fs.n_memb, 1u);
+          if (q < (uint32_t)kFinMembers) { fs.m_key[q] = k; fs.m_idx[q] = v; fs.m_E[q] = E; }
+        }
+      }
+    }
+    __syncthreads();
+    const uint32_t nm = fs.n_memb;
+    if (nm > (uint32_t)kFinMembers) return 9;                                  // uniform
+    if (wave == 0) {
+      const unsigned long long before = fs.before_d;
+      if (nm <= (uint32_t)kWave) {
+        const bool have = (uint32_t)lane < nm;
+        const uint32_t v = have ? fs.m_idx[lane] : kFinNone, kt = have ? fs.m_key[lane] : 0u;
+        const unsigned long long Et = have ? fs.m_E[lane] : 0ull;
+        unsigned long long C = before;
+        for (uint32_t q = 0; q < nm; ++q) {
+          const uint32_t iq = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q);
+          const unsigned long long Eq = readlane_u64(Et, (int)q);
+          C += iq <= v ? Eq : 0ull;
+        }
+        if (have && C > target && C - Et <= target) { fs.token = v; fs.token_key = kt; }
+      } else {
+        for (uint32_t e = lane; e < nm; e += kWave) {
+          const uint32_t v = fs.m_idx[e];
+          unsigned long long C = before;
+          for (uint32_t q = 0; q < nm; ++q)
+            if (fs.m_idx[q] <= v) C += fs.m_E[q];
+          if (C > target && C - fs.m_E[e] <= target) { fs.token = v; fs.token_key = fs.m_key[e]; }
+        }
+      }
+    }
+    __syncthreads();
+    code = fs.token == kFinNone ? 14 : 1;
+  }
+  if (code != 1) return code;                                                  // uniform
+  if (tid == 0) emit(fs.token, fs.token_key, lnZ);
+  return 1;
+}
+
+__global__ __launch_bounds__(kFinThreads) void finish_kernel(Args a_by_value) {
+  // The arguments are read where they are used, straight from the kernel-argument segment
+  // (the struct is the only parameter, so it starts at offset 0), instead of being held in
+  // scalar registers from the first instruction on: there are more of them than registers.
+  (void)a_by_value;
+  const Args& a = *(const Args*)__builtin_amdgcn_kernarg_segment_ptr();
+  __shared__ FinShared fs;
+  const int b = blockIdx.x;
+  const RowParams rp = load_row_params(a, b);
+  int code = 2;                            // 2: not eligible for the single-pass path (k beyond any list)
+  if (candidate_target(rp, a) != 0) code = finish_row(a, b, rp, fs);
+  if (threadIdx.x == 0) {
+    a.row_path[b] = code;
+    a.row_why[b] = code;
+    if (code != 1) {
+      const int q = atomicAdd(a.rescue_n, 1);
+      if (q >= 0 && q < a.B) a.rescue_rows[q] = b;
+    }
+  }
+}
+
+}  // namespace sip

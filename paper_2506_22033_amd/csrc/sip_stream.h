@@ -15,8 +15,11 @@
 //     (Sec. 5.1 row-wise softmax, here fused with temperature scaling).  Each thread adds its
 //     terms in fp32 in a fixed order; the per-thread sums are combined as integers in units
 //     of 2^-30.
-// History penalties (Sec. 5.1 ApplyPenalty) touch at most |history| elements of a row and
-// are applied afterwards as a sparse correction by the finishing kernel.
+// History penalties (Sec. 5.1 ApplyPenalty) touch at most |history| elements of a row.  The
+// workgroup marks the row's history tokens that fall into its chunk in an LDS bitmap (one bit
+// per element of the chunk); an element whose bit is set goes into the list whatever its
+// value, tagged, and stays out of the bulk mass, so that the finishing kernel finds the raw
+// logit of every token it has to penalise in the list and never reads the logits itself.
 #pragma once
 #include "sip_device.h"
 
@@ -24,12 +27,15 @@ namespace sip {
 
 constexpr int kStreamThreads = 512;
 constexpr int kStreamWaves = kStreamThreads / kWave;
-static_assert(kStreamWaves == 8, "ChunkOut::cnt holds one count per wave");
+static_assert(kStreamWaves == 8, "a chunk's segment is made of eight wave queues");
 constexpr int kStreamLoads = 2;             // 16-byte loads per thread per tile
 constexpr int kStreamBufs = 2;              // tiles held in registers: one being processed, the others in flight
 constexpr int kSampleBins = 8192;           // 13-bit keys: sign, exponent, 4 mantissa bits
 constexpr int kSampleSize = 8192;           // elements of a row the threshold is estimated from
-constexpr int kQueueCap = 512;              // entries of one wave's LDS candidate queue
+constexpr int kQueueCap = 480;              // entries of one wave's LDS candidate queue
+constexpr int kChunkCap = kStreamWaves * kQueueCap;   // entries of one chunk's segment in the workspace
+constexpr int kChunkBitsMax = 73728;        // most elements a chunk may have (history bitmap: 9 KB of LDS)
+constexpr int kStreamHistRegs = 8;          // history tokens a thread requests at once
 constexpr float kBulkScale = 1073741824.0f; // 2^30
 
 // Per-row decisions shared by the streaming and the finishing kernel.
@@ -134,16 +140,18 @@ __device__ __forceinline__ unsigned long long bulk_units(float acc) {
 
 
 template <int DT, bool SH>
-__global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void stream_kernel(Args a) {
   constexpr int EPL = (DT == SIP_F32) ? 4 : 8;      // elements per 16-byte load
   constexpr int ESZ = (DT == SIP_F32) ? 4 : 2;
   constexpr int SUB = kStreamThreads * EPL;         // elements per workgroup-wide load
   constexpr int TILE = SUB * kStreamLoads;
   constexpr int SLOADS = kSampleSize / SUB;         // sample loads per thread (4 fp32, 2 bf16)
   constexpr int NSB = SLOADS * kStreamWaves;        // 1 KB sample blocks spread over the row
-  // 32 KB of LDS: first the sample histogram (two 16-bit counters per word, 16 KB), then the
-  // per-wave candidate queues
+  // 30 KB of LDS: first the sample histogram (two 16-bit counters per word, 16 KB), then the
+  // per-wave candidate queues; 9 KB for the history bitmap of the chunk (39.6 KB in all: four
+  // workgroups per compute unit)
   __shared__ __align__(16) unsigned char smem[(kSampleBins * 2 > kStreamWaves * kQueueCap * 8) ? kSampleBins * 2 : kStreamWaves * kQueueCap * 8];
+  __shared__ uint32_t bmw[kChunkBitsMax / 32];
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
   __shared__ uint32_t red32[kStreamWaves];
   __shared__ unsigned long long red64[kStreamWaves];
@@ -158,6 +166,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
   // Device-resident history: this call is counted here, before the finishing kernel (which runs
   // after this one and knows that it has been counted) reads the counter.
   if (a.tick_bias && blockIdx.x == 0 && tid == 0) *a.st_tick += 1ull;
+  if (blockIdx.x == 0 && tid == 0) *a.rescue_n = 0;          // the finishing kernel counts from zero
   int wg = blockIdx.x;
   if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   const int b = wg / a.S, ch = wg - b * a.S;
@@ -245,9 +254,40 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
       smp[j] = *reinterpret_cast<const uint4*>(srow + (size_t)e0 * ESZ);
     }
   }
+  // ---- history bitmap of the chunk: bit (v - g0) for every history token v in [g0, g1), the
+  // vocabulary ids this workgroup streams.  Requested here, entered after the first barrier.
+  const HistRange hr = hist_range(a, b);
+  const bool has_pen = (hr.hi > hr.lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);   // uniform
+  const int g0 = (int)ibase + c0;
+  const int g1 = (!SH || split) ? (int)ibase + c1 : (int)ibase + np * Vl;
+  int htok[kStreamHistRegs];
+#pragma unroll
+  for (int j = 0; j < kStreamHistRegs; ++j) {
+    const long long i = hr.lo + tid + (long long)j * kStreamThreads;
+    htok[j] = (has_pen && i < hr.hi) ? a.tokens[i] : -1;
+  }
   for (int i = tid; i < kSampleBins / 2; i += kStreamThreads) hist[i] = 0;
+  for (int i = tid; i < kChunkBitsMax / 32; i += kStreamThreads) bmw[i] = 0;
   if (tid < 32) sub_hist[tid] = 0;
   __syncthreads();
+  if (has_pen) {
+    auto mark = [&](int t) {
+      const uint32_t r = (uint32_t)(t - g0);
+      if (t >= g0 && t < g1) atomicOr(&bmw[r >> 5], 1u << (r & 31));
+    };
+#pragma unroll
+    for (int j = 0; j < kStreamHistRegs; ++j) mark(htok[j]);
+    for (long long i0 = hr.lo + (long long)kStreamHistRegs * kStreamThreads; i0 < hr.hi;
+         i0 += (long long)kStreamHistRegs * kStreamThreads) {
+#pragma unroll
+      for (int j = 0; j < kStreamHistRegs; ++j) {
+        const long long i = i0 + tid + (long long)j * kStreamThreads;
+        htok[j] = i < hr.hi ? a.tokens[i] : -1;
+      }
+#pragma unroll
+      for (int j = 0; j < kStreamHistRegs; ++j) mark(htok[j]);
+    }
+  }
   // Only the upper tail of the sample matters.  When j is small, a thread enters just the
   // three largest of its values: far fewer LDS atomics, and hardly any on the same word.
   // (Should one thread hold more than three of the j largest, the threshold comes out a
@@ -357,30 +397,31 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
 
   // ---- stream
   uint2* queue = reinterpret_cast<uint2*>(smem) + wave * kQueueCap;          // this wave's LDS queue
-  uint2* seg = a.cand + ((size_t)wg * kStreamWaves + wave) * (size_t)a.cap_w;
-  const uint32_t cap = (uint32_t)a.cap_w;
-  uint32_t qn = 0;                          // wave-uniform: candidates seen (entries beyond the queue are dropped)
+  const unsigned char* bm8 = reinterpret_cast<const unsigned char*>(bmw);
+  uint32_t qn = 0;                          // wave-uniform: list entries seen (entries beyond the queue are dropped)
   float acc = 0.0f;                         // this thread's bulk mass, fixed order of additions
 
   uint32_t ib = ibase;                      // SH: first vocabulary id of the piece being processed
-  auto process = [&](const uint4& q, int e0, bool guard) {
+  // `hb`: the history bits of the EPL elements (bit i: element e0 + i carries a penalty)
+  auto process = [&](const uint4& q, int e0, bool guard, uint32_t hb) {
     float z[EPL];
     unpack(q, z);
     if (guard) {
 #pragma unroll
       for (int i = 0; i < EPL; ++i)
-        if (e0 + i >= c1) z[i] = -INFINITY;
+        if (e0 + i >= c1) { z[i] = -INFINITY; hb &= ~(1u << i); }
     }
     float g = 0.0f;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
-      const bool hit = z[i] >= Tc;
+      const uint32_t tag = (hb >> i) & 1u;
+      const bool hit = (z[i] >= Tc) | (tag != 0u);
       const unsigned long long mask = __ballot(hit);
       if (mask) {
         const uint32_t pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
                                       __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
         if (hit && pos < (uint32_t)kQueueCap)
-          queue[pos] = make_uint2(__float_as_uint(z[i]), (uint32_t)(e0 + i) + (SH ? ib : 0u));
+          queue[pos] = make_uint2(__float_as_uint(z[i]), ((uint32_t)(e0 + i) + (SH ? ib : 0u)) | (tag << 31));
         qn += (uint32_t)__popcll(mask);
       }
       float e = bulk_term(z[i], ref);
@@ -389,13 +430,24 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
     }
     acc += g;
   };
+  // Element e0 of the piece being processed is bit (ib - ibase) + e0 - c0 of the bitmap, a
+  // multiple of EPL: the bits of one 16-byte load are half a byte (fp32) or one byte (bf16).
+  // Lanes past the end of the chunk read the last byte; `process` masks what they get.
+  auto hist_bits = [&](int e0) -> uint32_t {
+    const uint32_t bit0 = (uint32_t)(e0 - c0) + (SH ? ib - ibase : 0u);
+    const uint32_t byte = bm8[min(bit0 >> 3, (uint32_t)(kChunkBitsMax / 8 - 1))];
+    return DT == SIP_F32 ? (byte >> (bit0 & 4u)) & 0xFu : byte;
+  };
   auto process_tile = [&](const uint4 (&buf)[kStreamLoads], int t0) {
     const bool partial = t0 + TILE > c1;
+    uint32_t hb[kStreamLoads];
+#pragma unroll
+    for (int j = 0; j < kStreamLoads; ++j) hb[j] = hist_bits(t0 + j * SUB + tid * EPL);
 #pragma unroll
     for (int j = 0; j < kStreamLoads; ++j) {
       const int e0 = t0 + j * SUB + tid * EPL;
-      if (!partial) process(buf[j], e0, false);
-      else if (t0 + j * SUB < c1) process(buf[j], e0, true);     // workgroup-uniform condition
+      if (!partial) process(buf[j], e0, false, hb[j]);
+      else if (t0 + j * SUB < c1) process(buf[j], e0, true, hb[j]);     // workgroup-uniform condition
     }
   };
 
@@ -444,23 +496,33 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(Args a) {
       }
     }
   }
-  // the queue goes out to the wave's segment in one burst (no global stores inside the loop:
-  // they would force every wait on a tile load to drain the whole memory queue)
-  for (uint32_t i = lane; i < min(qn, min(cap, (uint32_t)kQueueCap)); i += kWave) {
-    seg[i] = queue[i];
-  }
-
-  // ---- chunk summary
+  // ---- chunk summary; the eight queues go out, one behind the other, to the chunk's segment
+  // (no global stores inside the loop: they would force every wait on a tile load to drain the
+  // whole memory queue)
   const unsigned long long wsum = dpp_scan_add_u64(bulk_units(acc));      // integer from here on
   if (lane == kWave - 1) { red64[wave] = wsum; wave_cnt[wave] = qn; }
   __syncthreads();
+  uint32_t off = 0, tot = 0;
+  bool overflow = false;
+#pragma unroll
+  for (int w = 0; w < kStreamWaves; ++w) {
+    const uint32_t c = wave_cnt[w];
+    overflow |= c > (uint32_t)kQueueCap;
+    const uint32_t cc = min(c, (uint32_t)kQueueCap);
+    if (w < wave) off += cc;
+    tot += cc;
+  }
+  uint2* seg = a.cand + (size_t)wg * (size_t)kChunkCap + off;
+  for (uint32_t i = lane; i < min(qn, (uint32_t)kQueueCap); i += kWave) seg[i] = queue[i];
   if (tid == 0) {
     ChunkOut o;
     o.bulk = 0;
 #pragma unroll
-    for (int w = 0; w < kStreamWaves; ++w) { o.bulk += red64[w]; o.cnt[w] = wave_cnt[w]; }
+    for (int w = 0; w < kStreamWaves; ++w) o.bulk += red64[w];
     o.Tc = Tc;
     o.R = R;
+    o.cnt = overflow ? kCntOverflow : tot;
+    o.pad[0] = o.pad[1] = o.pad[2] = 0;
     a.chunks[wg] = o;
   }
 }

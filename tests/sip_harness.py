@@ -22,6 +22,7 @@ import paper_2506_22033_amd as sip
 from oracle import sip_oracle as O
 
 last_row_path = None        # per-row code path of the most recent run_gpu() call (see include/sip.h)
+last_row_why = None         # per-row code of the finishing kernel (1, or why the row went to the rescue kernel)
 LP_ABS = 1e-5
 LP_REL = 2.0 ** -22
 DEV = "cuda:0"
@@ -78,8 +79,9 @@ def run_gpu(d: DeviceWorkload, seed: int, step: int, k_logprobs: Optional[int] =
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=DEV)
     ids, lp_ids, lp = sip.sip_sample(d.logits, params, d.indptr, d.tokens, seed, step, k, V=d.V, workspace=ws)
     torch.cuda.synchronize()
-    global last_row_path
+    global last_row_path, last_row_why
     last_row_path = ws[:4 * B].view(torch.int32).cpu().numpy().copy()
+    last_row_why = ws[4 * B:8 * B].view(torch.int32).cpu().numpy().copy()
     return (ids.cpu().numpy(), None if lp_ids is None else lp_ids.cpu().numpy(),
             None if lp is None else lp.cpu().numpy())
 

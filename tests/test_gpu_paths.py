@@ -82,18 +82,20 @@ def test_nucleus_that_reaches_far_below_the_candidate_list(bf16):
 
 def test_rows_that_must_take_the_exact_path():
     rng = np.random.default_rng(2)
-    V, B = 50000, 5
+    V, B = 50000, 6
     z = (rng.standard_normal((B, V)) * 2.0).astype(np.float32)
-    params = dict(temperature=[1.0, 0.9, 1.0, 0.7, 1.0], top_k=[0, 20000, 0, 0, 50],
-                  top_p=[1.0, 1.0, 0.999, 1.0, 1.0], min_p=[0.0, 0.0, 0.0, 0.0, 0.0])
-    hist = [[], [], [], rng.integers(0, V, 9000).tolist(), []]     # row 3: > 4096 distinct history tokens
-    params.update(repetition_penalty=[1.0, 1.0, 1.0, 1.3, 1.0])
-    params["min_p"][3] = 0.1
+    params = dict(temperature=[1.0, 0.9, 1.0, 0.7, 1.0, 0.7], top_k=[0, 20000, 0, 0, 50, 0],
+                  top_p=[1.0, 1.0, 0.999, 1.0, 1.0, 1.0], min_p=[0.0, 0.0, 0.0, 0.1, 0.0, 0.1])
+    long_hist = rng.integers(0, V, 9000).tolist()                  # > 4096 distinct history tokens
+    hist = [[], [], [], long_hist, [], long_hist]
+    params.update(repetition_penalty=[1.0, 1.0, 1.0, 1.3, 1.0, 1.3],
+                  frequency_penalty=[0.0, 0.0, 0.0, 0.2, 0.0, 0.0])
     st, paths = _check(H.custom("exact", z, params, hist, k_logprobs=3), steps=(0, 1))
     assert (paths[:, 0] == 16).all()                       # plain temperature sampling: single pass + whole-row draw
     assert (paths[:, 1] == 2).all()                        # k far beyond the candidate list
-    assert (paths[:, 3] == 4).all()                        # too many distinct history tokens
+    assert (paths[:, 3] == 4).all()                        # more distinct history tokens than any table of multiplicities holds
     assert (paths[:, 4] == 1).all()
+    assert (paths[:, 5] == 1).all()                        # the same history without a frequency penalty needs no multiplicities
 
 
 @pytest.mark.parametrize("B", [1, 3, 5, 9])
