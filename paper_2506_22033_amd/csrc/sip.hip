@@ -84,7 +84,7 @@ Plan make_plan(int32_t B, int32_t V, int dtype, int t = 0) {
 }
 
 struct Layout {
-  size_t row_path, rescue, side_z, side_c, chunks, cand, gather, total;
+  size_t row_path, rescue, side_z, side_c, rowinfo, chunks, cand, gather, total;
 };
 
 thread_local hipEvent_t g_prof[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};   // one-shot, see sip_profile_kernel_events()
@@ -145,6 +145,8 @@ Layout make_layout(int32_t B, const Plan& p, int64_t nnz, size_t gather_row_byte
   l.rescue = off; off += align_up((size_t)(B + 1) * sizeof(int));            // count, then row numbers
   l.side_z = off; off += align_up((size_t)nnz * sizeof(float));
   l.side_c = off; off += align_up((size_t)nnz * sizeof(unsigned int));
+  l.rowinfo = off;
+  if (p.fast) off += align_up((size_t)B * sizeof(sip::RowInfo));
   l.chunks = off;
   if (p.fast) off += align_up((size_t)B * p.S * sizeof(sip::ChunkOut));
   l.cand = off;
@@ -237,6 +239,9 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
   a.row_path = reinterpret_cast<int*>(ws + lay.row_path);
   a.side_z = reinterpret_cast<float*>(ws + lay.side_z);
   a.side_c = reinterpret_cast<unsigned int*>(ws + lay.side_c);
+  a.rowinfo = reinterpret_cast<sip::RowInfo*>(ws + lay.rowinfo);
+  a.fin_tps = plan.fast ? sip::kFinThreads / plan.S : sip::kFinThreads;
+  a.fin_inv = (65536 + a.fin_tps - 1) / a.fin_tps;
   a.chunks = reinterpret_cast<sip::ChunkOut*>(ws + lay.chunks);
   a.cand = reinterpret_cast<uint2*>(ws + lay.cand);
   a.S = plan.S; a.cap_c = plan.cap_c; a.nc_cap = plan.nc_cap;

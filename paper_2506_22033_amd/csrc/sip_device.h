@@ -27,6 +27,18 @@ struct ChunkOut {
   unsigned int pad[3];
 };
 
+// What the streaming kernel (the workgroup of a row's first chunk) leaves for the finishing
+// kernel about row b: its sampling parameters, the extent of its history in Args::tokens and
+// the length the list was asked to have (0: the row cannot be finished from a list).
+struct RowInfo {
+  float tau, top_p, min_p, theta, phi, psi;
+  int top_k, target;
+  unsigned long long row_id;
+  long long lo, hi;
+  int pad[2];
+};
+static_assert(sizeof(RowInfo) == 64, "one 64-byte record per row");
+
 // Everything one call needs, passed by value to the kernels.
 struct Args {
   const void* logits;
@@ -45,6 +57,8 @@ struct Args {
   float* side_z;          // [nnz]  penalised value of the r-th distinct history token of a row
   unsigned int* side_c;   // [nnz]  its multiplicity
   // workspace and launch shape of the single-pass path
+  RowInfo* rowinfo;         // [B]
+  int fin_tps, fin_inv;     // finishing kernel: threads per list segment (512 / S), and ceil(2^16 / that)
   ChunkOut* chunks;         // [B * S]
   uint2* cand;              // [B * S * cap_c]  (value bits, index | tag): one segment per chunk
   int S;                    // chunks per row

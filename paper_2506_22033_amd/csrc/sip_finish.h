@@ -33,8 +33,6 @@ namespace sip {
 constexpr int kFinThreads = 512;
 constexpr int kFinWaves = kFinThreads / kWave;
 constexpr int kFinCR = 8;                              // list entries a thread holds in registers
-constexpr int kFinBatch = kFinThreads * kFinCR;        // entries per batch
-constexpr int kFinMaxBatches = 3;                      // lists up to 12288 entries
 constexpr int kFinBins = 1024;
 constexpr int kFinBPT = kFinBins / kFinThreads;        // bins per thread in the scans
 constexpr int kFinList = 4352;                         // entries of the bin-sorted list in LDS
@@ -75,20 +73,47 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return last_lane_
 __device__ __forceinline__ uint32_t wave_add_u32(uint32_t v) { return last_lane_u32(dpp_scan_add_u32(v)); }
 __device__ __forceinline__ unsigned long long wave_add_u64(unsigned long long v) { return last_lane_u64(dpp_scan_add_u64(v)); }
 
+// Barrier for code that only exchanges data through LDS: unlike __syncthreads() it does not wait
+// for global loads that are still in flight.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Row b, start to finish.  Returns 1 (finished: outputs written) or the reason why the list
 // does not settle the row.  Every return value is workgroup-uniform.
-__device__ __forceinline__ int finish_row(const Args& a, const int b, const RowParams& rp, FinShared& fs) {
+__device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared& fs) {
   constexpr int NT = kFinThreads;
   constexpr int CR = kFinCR;
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
   const int V = a.V;
   const int S = a.S;
-  auto scaled_s = [&](float z) { return rp.greedy ? z : __fdiv_rn(z, rp.tau); };
 
-  // ---- (0) chunk summaries (lane c reads chunk c), history extent, first history tokens; clear LDS
-  const HistRange hr = hist_range(a, b);
-  const bool has_pen = (hr.hi > hr.lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
-  const bool need_hash = has_pen && rp.phi != 0.0f;
+  // ---- (0) Everything this kernel reads from memory has an address that does not depend on
+  // anything else it reads, except the history tokens: the row's parameters and history extent
+  // (one record, left by the streaming kernel), the chunk summaries (lane c reads chunk c) and
+  // the list itself are requested at once.  The list is read before the segment sizes are
+  // known: thread t belongs to segment t / tps and takes, in round r, slot r * tps + t % tps of
+  // it; slots beyond the segment's size are dropped afterwards.
+  const int tps = a.fin_tps;                                   // kFinThreads / S
+  int c_seg = (tid * a.fin_inv) >> 16;                         // tid / tps, put right below
+  c_seg -= c_seg * tps > tid;
+  const int j_seg = tid - c_seg * tps;
+  const bool seg_thread = c_seg < S;
+  uint2* seg = a.cand + ((size_t)b * (size_t)S + (size_t)min(c_seg, S - 1)) * (size_t)a.cap_c;
+  uint2 creg[CR];                          // (bits of z, later of z' and then the key of s; index | tag, later index)
+  auto slot_of = [&](int bt, int r) { return (bt * CR + r) * tps + j_seg; };
+  auto load_batch = [&](int bt) {          // unchecked against the sizes
+#pragma unroll
+    for (int r = 0; r < CR; ++r) {
+      const int sl = slot_of(bt, r);
+      creg[r] = make_uint2(0u, kFinNone);
+      if (seg_thread && sl < a.cap_c) creg[r] = seg[sl];
+    }
+  };
+  load_batch(0);
+  const RowInfo ri = a.rowinfo[b];
   uint32_t my_cnt = 0;
   unsigned long long my_bulk = 0;
   float Tc;
@@ -99,11 +124,20 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
     Tc = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(co.Tc)));   // the chunks of a row share
     R = __builtin_amdgcn_readfirstlane(co.R);                                                      // threshold and exponent
   }
+  if (ri.target == 0) return 2;                                              // uniform: k beyond any list
+  RowParams rp;
+  rp.tau = ri.tau; rp.top_p = ri.top_p; rp.min_p = ri.min_p; rp.theta = ri.theta; rp.phi = ri.phi; rp.psi = ri.psi;
+  rp.top_k = ri.top_k; rp.row_id = ri.row_id;
+  rp.greedy = (rp.tau == 0.0f) || (rp.top_k == 1);
+  auto scaled_s = [&](float z) { return rp.greedy ? z : __fdiv_rn(z, rp.tau); };
+  const long long h_lo = ri.lo, h_hi = ri.hi;
+  const bool has_pen = (h_hi > h_lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
+  const bool need_hash = has_pen && rp.phi != 0.0f;
   int htok[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const long long i = hr.lo + tid + (long long)j * NT;
-    htok[j] = (need_hash && i < hr.hi) ? a.tokens[i] : -1;
+    const long long i = h_lo + tid + (long long)j * NT;
+    htok[j] = (need_hash && i < h_hi) ? a.tokens[i] : -1;
   }
   {
     // hcnt, off, fill, hmass, hidx are contiguous: 28 KB, of which `off` need not be cleared
@@ -129,101 +163,105 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
   const bool k_act = !rp.greedy && rp.top_k >= 2 && rp.top_k < V;
   const uint32_t n_top = (uint32_t)max(0, min(a.k_lp, V));
 
-  // list geometry: entry i of the row's list lies in segment c = #{c' >= 1 : i >= first[c']}
-  // at segs[i + sum over those c' of (cap_c - cnt[c'-1])]
-  const uint32_t incl = dpp_scan_add_u32(my_cnt);
-  const uint32_t excl = incl - my_cnt;
   const bool any_over = __any(my_cnt > (uint32_t)a.cap_c);                   // includes the overflow mark
-  const uint32_t total = last_lane_u32(incl);
+  const uint32_t total = wave_add_u32(my_cnt);
+  const uint32_t longest = wave_max_u32(my_cnt);
   const unsigned long long bulk = wave_add_u64(my_bulk);
   if (any_over || !(Tc == Tc)) return 3;                                     // uniform
-  if (total > (uint32_t)(kFinBatch * kFinMaxBatches)) return 5;              // uniform
-  const int nb = (int)((total + kFinBatch - 1) / kFinBatch);                 // uniform
-  uint2* segs = a.cand + (size_t)b * (size_t)S * (size_t)a.cap_c;
-  uint32_t adr[CR];                                                          // where this thread's entries of batch 0 lie
-  {
+  if (total > (uint32_t)a.nc_cap) return 5;                                  // uniform
+  const int nb = (int)((longest + (uint32_t)(CR * tps) - 1) / (uint32_t)(CR * tps));   // uniform: batches of CR rounds
+  const int cnt_seg = seg_thread ? __shfl((int)my_cnt, c_seg, kWave) : 0;    // size of this thread's segment
+  auto drop_beyond = [&](int bt) {
 #pragma unroll
-    for (int r = 0; r < CR; ++r) adr[r] = (uint32_t)(r * NT + tid);
-    for (int c = 1; c < S; ++c) {
-      const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)excl, c);
-      const uint32_t gap = (uint32_t)a.cap_c - (uint32_t)__builtin_amdgcn_readlane((int)my_cnt, c - 1);
-#pragma unroll
-      for (int r = 0; r < CR; ++r) adr[r] += ((uint32_t)(r * NT + tid) >= first) ? gap : 0u;
-    }
-  }
-  // address of entry i of a later batch (rare: lists longer than one batch)
-  auto address_of = [&](uint32_t i) {
-    uint32_t ad = i;
-    for (int c = 1; c < S; ++c) {
-      const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)excl, c);
-      const uint32_t gap = (uint32_t)a.cap_c - (uint32_t)__builtin_amdgcn_readlane((int)my_cnt, c - 1);
-      ad += (i >= first) ? gap : 0u;
-    }
-    return ad;
+    for (int r = 0; r < CR; ++r)
+      if (!(slot_of(bt, r) < cnt_seg)) creg[r] = make_uint2(0u, kFinNone);
   };
-  uint2 creg[CR];                          // (bits of z, later of z'; index | tag, later index)
-  auto load_batch = [&](int bt) {
-#pragma unroll
-    for (int r = 0; r < CR; ++r) {
-      const uint32_t i = (uint32_t)(bt * kFinBatch + r * NT + tid);
-      creg[r] = make_uint2(0u, kFinNone);
-      if (i < total) creg[r] = segs[bt == 0 ? adr[r] : address_of(i)];
-    }
-  };
-  load_batch(0);
-  __syncthreads();                                                           // LDS is clear
+  lds_barrier();                                                             // LDS is clear
 
-  // ---- (1) multiplicities: open addressing keyed by token, one CAS to claim or find the slot,
-  // one add to count
+  // ---- (1) multiplicities: a hash table of kFinHash / 4 buckets of four slots, keyed by token.
+  // A bucket's four keys are one 16-byte LDS read; a token lives in the first bucket, from its
+  // home bucket on, that had a free slot when it came.  Slots of a bucket fill in order (a thread
+  // claims the first slot it finds free, by compare-and-swap), so a key, once there, stays.
+  uint4* const hkey4 = reinterpret_cast<uint4*>(fs.u.hash.key);
+  auto home = [](uint32_t t) { return (t * 0x9E3779B1u) >> 22; };
+  static_assert(kFinHash == 4096, "home() yields 10 bits: 1024 buckets of 4 slots");
   if (need_hash) {
     uint32_t mine = 0;                     // slots this thread claimed = distinct tokens it saw first
-    auto insert = [&](int t) {
-      if (t < 0 || t >= V) return;
-      uint32_t h = ((uint32_t)t * 0x9E3779B1u) >> 20;
-      for (int probe = 0; probe < kFinHash; ++probe) {
-        const uint32_t old = atomicCAS(&fs.u.hash.key[h], kFinNone, (uint32_t)t);
-        if (old == kFinNone || old == (uint32_t)t) {
-          atomicAdd(&fs.u.hash.val[h], 1u);
-          mine += old == kFinNone;
-          return;
+    auto insert = [&](int ti) {
+      if (ti < 0 || ti >= V) return;
+      const uint32_t t = (uint32_t)ti;
+      uint32_t bk = home(t);
+      for (int probe = 0; probe < kFinHash / 4; ++probe) {
+        const uint4 k4 = hkey4[bk];
+        const uint32_t ks[4] = {k4.x, k4.y, k4.z, k4.w};
+        int j = -1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (j < 0 && ks[e] == t) j = e;
+          if (j < 0 && ks[e] == kFinNone) {                 // free when read: try to take it
+            const uint32_t old = atomicCAS(&fs.u.hash.key[4 * bk + e], kFinNone, t);
+            if (old == kFinNone) { ++mine; j = e; } else if (old == t) j = e;
+          }
         }
-        h = (h + 1) & (kFinHash - 1);
+        if (j >= 0) { atomicAdd(&fs.u.hash.val[4 * bk + j], 1u); return; }
+        bk = (bk + 1) & (kFinHash / 4 - 1);
       }
       fs.hash_fail = 1;                    // table full
     };
     insert(htok[0]);
     insert(htok[1]);
-    for (long long i = hr.lo + tid + 2ll * NT; i < hr.hi; i += NT) insert(a.tokens[i]);
+    for (long long i = h_lo + tid + 2ll * NT; i < h_hi; i += NT) insert(a.tokens[i]);
     const uint32_t wtot = wave_add_u32(mine);
     if (lane == 0) fs.r32[wave] = wtot;
-    __syncthreads();
+    lds_barrier();
     uint32_t ndist = 0;
 #pragma unroll
     for (int w = 0; w < kFinWaves; ++w) ndist += fs.r32[w];
     if (fs.hash_fail || ndist > (uint32_t)kFinHashMax) return 4;            // uniform
   }
-  auto multiplicity = [&](uint32_t t) -> uint32_t {
-    uint32_t h = (t * 0x9E3779B1u) >> 20;
-    for (int probe = 0; probe < kFinHash; ++probe) {
-      if (fs.u.hash.key[h] == t) return fs.u.hash.val[h];
-      h = (h + 1) & (kFinHash - 1);
+  // slot of token t, searched from bucket bk on (the rare continuation of the lookup below)
+  auto slot_slow = [&](uint32_t t, uint32_t bk) -> uint32_t {
+    for (int probe = 0; probe < kFinHash / 4; ++probe) {
+      const uint4 k4 = hkey4[bk];
+      if (k4.x == t) return 4 * bk;
+      if (k4.y == t) return 4 * bk + 1;
+      if (k4.z == t) return 4 * bk + 2;
+      if (k4.w == t) return 4 * bk + 3;
+      bk = (bk + 1) & (kFinHash / 4 - 1);
     }
-    return 1u;                             // not reached: every tagged token is in the history
+    return 0u;                             // not reached: every tagged token is in the history
   };
 
   // ---- (2) penalised values (Sec. 5.1 ApplyPenalty); maximum of the list, lowest index on ties
   uint32_t bkey = 0, bidx = kFinNone;
   for (int bt = 0; bt < nb; ++bt) {
     if (bt > 0) load_batch(bt);
+    drop_beyond(bt);
+    // the home buckets of all entries are read from the table together, then the counts
+    uint32_t hv[CR];
+    if (need_hash) {
+      uint4 hk[CR];
+#pragma unroll
+      for (int r = 0; r < CR; ++r) hk[r] = hkey4[home(creg[r].y & ~kTagBit)];
+      uint32_t hs[CR];
+#pragma unroll
+      for (int r = 0; r < CR; ++r) {
+        const uint32_t v = creg[r].y & ~kTagBit, bk = home(v);
+        hs[r] = hk[r].x == v ? 4 * bk : hk[r].y == v ? 4 * bk + 1 : hk[r].z == v ? 4 * bk + 2 : hk[r].w == v ? 4 * bk + 3 : kFinNone;
+        if (hs[r] == kFinNone) hs[r] = ((creg[r].y & kTagBit) && creg[r].y != kFinNone) ? slot_slow(v, (bk + 1) & (kFinHash / 4 - 1)) : 0u;
+      }
+#pragma unroll
+      for (int r = 0; r < CR; ++r) hv[r] = fs.u.hash.val[hs[r]];
+    }
 #pragma unroll
     for (int r = 0; r < CR; ++r) {
-      if ((uint32_t)(bt * kFinBatch + r * NT) < total && creg[r].y != kFinNone) {   // first condition uniform
+      if (creg[r].y != kFinNone) {
         const uint32_t v = creg[r].y & ~kTagBit;
         float z = __uint_as_float(creg[r].x);
         if (creg[r].y & kTagBit) {
-          z = penalise(z, need_hash ? multiplicity(v) : 1u, rp.theta, rp.phi, rp.psi);
+          z = penalise(z, need_hash ? hv[r] : 1u, rp.theta, rp.phi, rp.psi);
           // lists of several batches are read again from memory: leave the penalised value there
-          if (nb > 1) segs[bt == 0 ? adr[r] : address_of((uint32_t)(bt * kFinBatch + r * NT + tid))] = make_uint2(__float_as_uint(z), v);
+          if (nb > 1) seg[slot_of(bt, r)] = make_uint2(__float_as_uint(z), v);
         }
         creg[r] = make_uint2(__float_as_uint(z), v < (uint32_t)V ? v : kFinNone);
         const uint32_t kz = key_of(z);
@@ -236,7 +274,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
     const uint32_t wi = wave_min_u32(bkey == wk ? bidx : kFinNone);
     if (lane == 0) { fs.rkey[wave] = wk; fs.ridx[wave] = wi; }
   }
-  __syncthreads();
+  lds_barrier();
   bkey = 0; bidx = kFinNone;
 #pragma unroll
   for (int w = 0; w < kFinWaves; ++w) {
@@ -275,10 +313,10 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
 
   // ---- (3) keys, masses, value histogram
   for (int bt = 0; bt < nb; ++bt) {
-    if (nb > 1) load_batch(bt);
+    if (nb > 1) { load_batch(bt); drop_beyond(bt); }
 #pragma unroll
     for (int r = 0; r < CR; ++r) {
-      if ((uint32_t)(bt * kFinBatch + r * NT) < total && creg[r].y != kFinNone) {
+      if (creg[r].y != kFinNone) {
         const float s = scaled_s(__uint_as_float(creg[r].x));
         const uint32_t k = key_of(s);
         const int bin = bin_of(s, k);
@@ -289,7 +327,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
       }
     }
   }
-  __syncthreads();
+  lds_barrier();
 
   // ---- (4) descending scan over the bins: thread t owns bins kFinBins-1-2t and kFinBins-2-2t
   unsigned long long S_cand;
@@ -304,7 +342,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
     const uint32_t cinc = dpp_scan_add_u32(csum);
     const unsigned long long minc = dpp_scan_add_u64(msum);
     if (lane == kWave - 1) { fs.r32[wave] = cinc; fs.r64[wave] = minc; }
-    __syncthreads();
+    lds_barrier();
     uint32_t cex = cinc - csum;
     unsigned long long mex = minc - msum, mtot = 0;
 #pragma unroll
@@ -328,21 +366,24 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
       cex += c[j]; mex += w[j];
     }
   }
-  __syncthreads();
+  lds_barrier();
   const int bin_k = fs.bin_k, bin_n = fs.bin_n;
   if ((k_act && bin_k < 0) || (n_top > 0 && bin_n < 0)) return 8;              // uniform: k-th / n-th not provably in the list
 
   // total mass: the list's plus the bulk's, brought to units of 2^-40 of the maximum's mass.
   // 2^x with x split into integer and fraction: the fraction goes through the hardware exp2,
-  // the integer part is an exponent shift.
-  const double ln2 = 0.6931471805599453094, log2e = 1.4426950408889634074;
-  const double x = fmin(fmax((double)R + 10.0 - (double)m * log2e, -2000.0), 2000.0);
-  const double xi = floor(x);
-  const double bulk_rel = ldexp((double)bulk * (double)__builtin_amdgcn_exp2f((float)(x - xi)), (int)xi);
-  const unsigned long long S0 = S_cand + (bulk_rel < 9.0e18 ? (unsigned long long)bulk_rel : 0ull);
-  int e2;
-  const float f2 = (float)frexp((double)S0, &e2);
-  const double lnZ = ((double)__builtin_amdgcn_logf(f2) + (double)(e2 - kFixShift)) * ln2;
+  // the integer part is an exponent shift.  (Only the waves that use it work it out.)
+  auto total_mass = [&](double& lnZ) -> unsigned long long {
+    const double ln2 = 0.6931471805599453094, log2e = 1.4426950408889634074;
+    const double x = fmin(fmax((double)R + 10.0 - (double)m * log2e, -2000.0), 2000.0);
+    const double xi = floor(x);
+    const double bulk_rel = ldexp((double)bulk * (double)__builtin_amdgcn_exp2f((float)(x - xi)), (int)xi);
+    const unsigned long long S0 = S_cand + (bulk_rel < 9.0e18 ? (unsigned long long)bulk_rel : 0ull);
+    int e2;
+    const float f2 = (float)frexp((double)S0, &e2);
+    lnZ = ((double)__builtin_amdgcn_logf(f2) + (double)(e2 - kFixShift)) * ln2;
+    return S0;
+  };
 
   // lowest bin any later step looks into: everything from there up is laid down, sorted by bin
   int bin_minp = 1;                        // entries below this bin fail min-p (the reverse need not hold)
@@ -363,13 +404,14 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
     for (int bt = 0; bt < nb; ++bt) {
       if (nb > 1) {                         // keys again (the registers hold the last batch only)
         load_batch(bt);
+        drop_beyond(bt);
 #pragma unroll
         for (int r = 0; r < CR; ++r)
           if (creg[r].y != kFinNone) creg[r].x = key_of(scaled_s(__uint_as_float(creg[r].x)));
       }
 #pragma unroll
       for (int r = 0; r < CR; ++r) {
-        if ((uint32_t)(bt * kFinBatch + r * NT) < total && creg[r].y != kFinNone) {
+        if (creg[r].y != kFinNone) {
           const uint32_t k = creg[r].x;
           const int bin = bin_of(value_of(k), k);
           if (bin >= lowbin) {
@@ -380,21 +422,26 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
       }
     }
   }
-  __syncthreads();
+  lds_barrier();
 
   // ---- (5) wave 1: best-n.  The range [0, nt) of the sorted list holds every element of the
   // row at or above the bin of the n-th best, so an entry's rank in it is its rank in the row.
   if (wave == 1 && n_top > 0) {
+    double lnZ;
+    total_mass(lnZ);
     const uint32_t nt = fs.off[bin_n] + fs.hcnt[bin_n];
     const int cols = 1 + a.k_lp;
     if (nt <= (uint32_t)kWave) {
       const uint32_t kt = (uint32_t)lane < nt ? fs.u.list.skey[lane] : 0u;
       const uint32_t v = (uint32_t)lane < nt ? fs.u.list.sidx[lane] : kFinNone;
       uint32_t rank = 0;
-      for (uint32_t q = 0; q < nt; ++q) {
-        const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
-        const uint32_t iq = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q);
-        rank += (uint32_t)((kq > kt) | ((kq == kt) & (iq < v)));
+      for (uint32_t q0 = 0; q0 < nt; q0 += 8) {       // lanes past the members hold neutral values
+#pragma unroll
+        for (uint32_t q = q0; q < q0 + 8; ++q) {
+          const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
+          const uint32_t iq = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q);
+          rank += (uint32_t)((kq > kt) | ((kq == kt) & (iq < v)));
+        }
       }
       if ((uint32_t)lane < nt && rank < n_top) {
         a.out_lp_ids[(size_t)b * cols + 1 + rank] = (int)v;
@@ -427,6 +474,8 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
   } else if (wave == 0) {
     int code = 0;
     uint32_t key_k = 0;
+    double lnZ0;
+    const unsigned long long S0 = total_mass(lnZ0);
     unsigned long long S1 = S0;
     // Members of a bin: the range [p0, p0 + nm) of the sorted list.  Up to 64 of them sit one per
     // lane and are compared through readlane; more (many equal values: bf16 logits) are stepped
@@ -455,11 +504,14 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
         const unsigned long long Et = (uint32_t)lane < nm ? mass(value_of(kt)) : 0ull;
         uint32_t gt = 0, ge = 0;
         unsigned long long sum_ge = 0;
-        for (uint32_t q = 0; q < nm; ++q) {
-          const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
-          const unsigned long long Eq = readlane_u64(Et, (int)q);
-          gt += kq > kt; ge += kq >= kt;
-          sum_ge += kq >= kt ? Eq : 0ull;
+        for (uint32_t q0 = 0; q0 < nm; q0 += 8) {       // lanes past the members hold neutral values
+#pragma unroll
+          for (uint32_t q = q0; q < q0 + 8; ++q) {
+            const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
+            const unsigned long long Eq = readlane_u64(Et, (int)q);
+            gt += kq > kt; ge += kq >= kt;
+            sum_ge += kq >= kt ? Eq : 0ull;
+          }
         }
         const unsigned long long ball = __ballot((uint32_t)lane < nm && gt < k_rem && k_rem <= ge);
         if (ball) {
@@ -495,11 +547,10 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
       const int lowb = k_act ? bin_k : bin_minp;
       int bin_p = 1 << 30, bin_low = 1 << 30;
       {
-        constexpr int PER = kFinBins / kWave;                                  // 16 bins per lane
-        const int base = lane * PER;
-#pragma unroll
+        constexpr int PER = kFinBins / kWave;                                  // 16 bins per lane, 64 apart: consecutive
+#pragma unroll                                                                 // lanes read consecutive words
         for (int j = PER - 1; j >= 0; --j) {                                   // descending: the last hit is the lowest
-          const int bin = base + j;
+          const int bin = j * kWave + lane;
           const uint32_t c = fs.hcnt[bin];
           const unsigned long long above = fs.hmass[bin];
           if (bin >= 1 && c) bin_low = bin;
@@ -520,10 +571,13 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
           const uint32_t kt = member ? fs.u.list.skey[p0 + lane] : 0u;
           const unsigned long long Et = member ? mass(value_of(kt)) : 0ull;
           unsigned long long G = base_mass;
-          for (uint32_t q = 0; q < nm; ++q) {
-            const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
-            const unsigned long long Eq = readlane_u64(Et, (int)q);
-            G += kq > kt ? Eq : 0ull;
+          for (uint32_t q0 = 0; q0 < nm; q0 += 8) {       // lanes past the members hold neutral values
+#pragma unroll
+            for (uint32_t q = q0; q < q0 + 8; ++q) {
+              const uint32_t kq = (uint32_t)__builtin_amdgcn_readlane((int)kt, (int)q);
+              const unsigned long long Eq = readlane_u64(Et, (int)q);
+              G += kq > kt ? Eq : 0ull;
+            }
           }
           const bool in_k1 = member && kt >= key_k;
           key_p = wave_min_u32((in_k1 && G < limit) ? kt : kFinNone);
@@ -564,16 +618,25 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
         const unsigned long long Et = (have && kept_key(kt, key_cut)) ? mass(value_of(kt)) : 0ull;
         const unsigned long long S3 = wave_add_u64(Et);
         const unsigned long long target = (__umul64hi(j24, S3) << 40) | ((j24 * S3) >> 24);   // floor(j * S3 / 2^24)
-        unsigned long long C = 0;
-        for (uint32_t q = 0; q < n_hi; ++q) {
-          const uint32_t iq = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q);
-          const unsigned long long Eq = readlane_u64(Et, (int)q);
-          C += iq <= v ? Eq : 0ull;
+        // The entries are brought into vocabulary order across the lanes: an entry's rank is the
+        // number of smaller indices (the indices are distinct), lane `rank` receives its mass and
+        // the lane it came from, and a prefix sum over the lanes is the running mass.
+        uint32_t rank = 0;
+        for (uint32_t q0 = 0; q0 < n_hi; q0 += 8) {                            // lanes past the entries hold an index above all
+#pragma unroll
+          for (uint32_t q = q0; q < q0 + 8; ++q) rank += (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q) < v;
         }
-        // kept entries have mass > 0 and distinct indices: exactly one of them is the first crossing
-        const unsigned long long ball = __ballot(Et > 0 && C > target && C - Et <= target);
+        if (!have) rank = (uint32_t)lane;                                      // lanes without an entry keep their place
+        const int dst = (int)(rank << 2);
+        const unsigned long long Es =
+            ((unsigned long long)(uint32_t)__builtin_amdgcn_ds_permute(dst, (int)(uint32_t)(Et >> 32)) << 32) |
+            (uint32_t)__builtin_amdgcn_ds_permute(dst, (int)(uint32_t)Et);
+        const int from = __builtin_amdgcn_ds_permute(dst, lane);
+        const unsigned long long C = dpp_scan_add_u64(Es);
+        // kept entries have mass > 0: exactly one of them is the first crossing
+        const unsigned long long ball = __ballot(Es > 0 && C > target && C - Es <= target);
         if (ball) {
-          const int src = __ffsll((long long)ball) - 1;
+          const int src = __builtin_amdgcn_readlane(from, __ffsll((long long)ball) - 1);
           if (lane == 0) {
             fs.token = (uint32_t)__builtin_amdgcn_readlane((int)v, src);
             fs.token_key = (uint32_t)__builtin_amdgcn_readlane((int)kt, src);
@@ -589,7 +652,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
     }
     if (lane == 0) fs.code = code;
   }
-  __syncthreads();
+  lds_barrier();
   int code = fs.code_top ? fs.code_top : fs.code;                              // a failure of the best-n ranking stands
   if (code == kFinDrawBig) {
     // ---- (6') kept mass per vocabulary-index bin, prefix, then the crossing inside one bin
@@ -603,7 +666,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
         if (E) atomicAdd(&fs.hidx[fs.u.list.sidx[p] >> ishift], E);
       }
     }
-    __syncthreads();
+    lds_barrier();
     unsigned long long target;
     {
       const int b0 = kFinBPT * tid;                      // ascending index order
@@ -611,7 +674,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
       const unsigned long long msum = w0 + w1;
       const unsigned long long minc = dpp_scan_add_u64(msum);
       if (lane == kWave - 1) fs.r64[wave] = minc;
-      __syncthreads();
+      lds_barrier();
       unsigned long long ex = minc - msum, S3 = 0;
 #pragma unroll
       for (int ww = 0; ww < kFinWaves; ++ww) {
@@ -624,7 +687,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
       ex += w0;
       if (ex <= target && target < ex + w1) { fs.bin_d = b0 + 1; fs.before_d = ex; }
     }
-    __syncthreads();
+    lds_barrier();
     const int bin_d = fs.bin_d;
     if (bin_d < 0) return 14;                                                  // uniform (no kept mass)
     for (uint32_t p = tid; p < n_hi; p += NT) {
@@ -637,7 +700,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
         }
       }
     }
-    __syncthreads();
+    lds_barrier();
     const uint32_t nm = fs.n_memb;
     if (nm > (uint32_t)kFinMembers) return 9;                                  // uniform
     if (wave == 0) {
@@ -647,10 +710,13 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
         const uint32_t v = have ? fs.m_idx[lane] : kFinNone, kt = have ? fs.m_key[lane] : 0u;
         const unsigned long long Et = have ? fs.m_E[lane] : 0ull;
         unsigned long long C = before;
-        for (uint32_t q = 0; q < nm; ++q) {
-          const uint32_t iq = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q);
-          const unsigned long long Eq = readlane_u64(Et, (int)q);
-          C += iq <= v ? Eq : 0ull;
+        for (uint32_t q0 = 0; q0 < nm; q0 += 8) {       // lanes past the members hold neutral values
+#pragma unroll
+          for (uint32_t q = q0; q < q0 + 8; ++q) {
+            const uint32_t iq = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)q);
+            const unsigned long long Eq = readlane_u64(Et, (int)q);
+            C += iq <= v ? Eq : 0ull;
+          }
         }
         if (have && C > target && C - Et <= target) { fs.token = v; fs.token_key = kt; }
       } else {
@@ -663,11 +729,15 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, const RowP
         }
       }
     }
-    __syncthreads();
+    lds_barrier();
     code = fs.token == kFinNone ? 14 : 1;
   }
   if (code != 1) return code;                                                  // uniform
-  if (tid == 0) emit(fs.token, fs.token_key, lnZ);
+  if (tid == 0) {
+    double lnZ;
+    total_mass(lnZ);
+    emit(fs.token, fs.token_key, lnZ);
+  }
   return 1;
 }
 
@@ -679,9 +749,7 @@ __global__ __launch_bounds__(kFinThreads) void finish_kernel(Args a_by_value) {
   const Args& a = *(const Args*)__builtin_amdgcn_kernarg_segment_ptr();
   __shared__ FinShared fs;
   const int b = blockIdx.x;
-  const RowParams rp = load_row_params(a, b);
-  int code = 2;                            // 2: not eligible for the single-pass path (k beyond any list)
-  if (candidate_target(rp, a) != 0) code = finish_row(a, b, rp, fs);
+  const int code = finish_row(a, b, fs);
   if (threadIdx.x == 0) {
     a.row_path[b] = code;
     a.row_why[b] = code;

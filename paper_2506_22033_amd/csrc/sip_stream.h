@@ -172,7 +172,10 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
   const int b = wg / a.S, ch = wg - b * a.S;
   const RowParams rp = load_row_params(a, b);
   const int target = candidate_target(rp, a);
-  if (target == 0) return;
+  if (target == 0) {
+    if (wg - b * a.S == 0 && tid == 0) a.rowinfo[b].target = 0;             // the finishing kernel looks at nothing else
+    return;
+  }
   const int V = a.V;
   // SH (vocabulary-sharded logits): the row's chunks are dealt out to the shards, S / t_shards
   // each, and a chunk lies inside its shard; c0, c1 and every element index below are then
@@ -260,6 +263,13 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
   const bool has_pen = (hr.hi > hr.lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);   // uniform
   const int g0 = (int)ibase + c0;
   const int g1 = (!SH || split) ? (int)ibase + c1 : (int)ibase + np * Vl;
+  if (ch == 0 && tid == 0) {               // the row's record for the finishing kernel
+    RowInfo ri;
+    ri.tau = rp.tau; ri.top_p = rp.top_p; ri.min_p = rp.min_p; ri.theta = rp.theta; ri.phi = rp.phi; ri.psi = rp.psi;
+    ri.top_k = rp.top_k; ri.target = target; ri.row_id = rp.row_id; ri.lo = hr.lo; ri.hi = hr.hi;
+    ri.pad[0] = ri.pad[1] = 0;
+    a.rowinfo[b] = ri;
+  }
   int htok[kStreamHistRegs];
 #pragma unroll
   for (int j = 0; j < kStreamHistRegs; ++j) {
