@@ -32,7 +32,7 @@
 namespace sip {
 constexpr int kFinThreads = 512;
 constexpr int kFinWaves = kFinThreads / kWave;
-constexpr int kFinCR = 8;                              // list entries a thread holds in registers
+constexpr int kFinCR = 10;                             // list entries a thread holds in registers
 constexpr int kFinBins = 1024;
 constexpr int kFinBPT = kFinBins / kFinThreads;        // bins per thread in the scans
 constexpr int kFinList = 4352;                         // entries of the bin-sorted list in LDS
@@ -133,9 +133,10 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   const long long h_lo = ri.lo, h_hi = ri.hi;
   const bool has_pen = (h_hi > h_lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
   const bool need_hash = has_pen && rp.phi != 0.0f;
-  int htok[2];
+  constexpr int HR = 8;                    // history tokens a thread requests at once
+  int htok[HR];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
+  for (int j = 0; j < HR; ++j) {
     const long long i = h_lo + tid + (long long)j * NT;
     htok[j] = (need_hash && i < h_hi) ? a.tokens[i] : -1;
   }
@@ -171,6 +172,9 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   if (total > (uint32_t)a.nc_cap) return 5;                                  // uniform
   const int nb = (int)((longest + (uint32_t)(CR * tps) - 1) / (uint32_t)(CR * tps));   // uniform: batches of CR rounds
   const int cnt_seg = seg_thread ? __shfl((int)my_cnt, c_seg, kWave) : 0;    // size of this thread's segment
+  // whether round r of batch bt holds anything at all (uniform): every round is unrolled code that
+  // costs time even when no lane has an entry, unless the whole wave branches around it
+  auto live = [&](int bt, int r) { return (uint32_t)((bt * CR + r) * tps) < longest; };
   auto drop_beyond = [&](int bt) {
 #pragma unroll
     for (int r = 0; r < CR; ++r)
@@ -208,9 +212,18 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
       }
       fs.hash_fail = 1;                    // table full
     };
-    insert(htok[0]);
-    insert(htok[1]);
-    for (long long i = h_lo + tid + 2ll * NT; i < h_hi; i += NT) insert(a.tokens[i]);
+#pragma unroll
+    for (int j = 0; j < HR; ++j)
+      if ((long long)j * NT < h_hi - h_lo) insert(htok[j]);                  // uniform condition
+    for (long long i0 = h_lo + (long long)HR * NT; i0 < h_hi; i0 += (long long)HR * NT) {
+#pragma unroll
+      for (int j = 0; j < HR; ++j) {
+        const long long i = i0 + tid + (long long)j * NT;
+        htok[j] = i < h_hi ? a.tokens[i] : -1;
+      }
+#pragma unroll
+      for (int j = 0; j < HR; ++j) insert(htok[j]);
+    }
     const uint32_t wtot = wave_add_u32(mine);
     if (lane == 0) fs.r32[wave] = wtot;
     lds_barrier();
@@ -242,20 +255,24 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
     if (need_hash) {
       uint4 hk[CR];
 #pragma unroll
-      for (int r = 0; r < CR; ++r) hk[r] = hkey4[home(creg[r].y & ~kTagBit)];
+      for (int r = 0; r < CR; ++r)
+        if (live(bt, r)) hk[r] = hkey4[home(creg[r].y & ~kTagBit)];
       uint32_t hs[CR];
 #pragma unroll
       for (int r = 0; r < CR; ++r) {
+        hs[r] = 0u;
+        if (!live(bt, r)) continue;
         const uint32_t v = creg[r].y & ~kTagBit, bk = home(v);
         hs[r] = hk[r].x == v ? 4 * bk : hk[r].y == v ? 4 * bk + 1 : hk[r].z == v ? 4 * bk + 2 : hk[r].w == v ? 4 * bk + 3 : kFinNone;
         if (hs[r] == kFinNone) hs[r] = ((creg[r].y & kTagBit) && creg[r].y != kFinNone) ? slot_slow(v, (bk + 1) & (kFinHash / 4 - 1)) : 0u;
       }
 #pragma unroll
-      for (int r = 0; r < CR; ++r) hv[r] = fs.u.hash.val[hs[r]];
+      for (int r = 0; r < CR; ++r)
+        if (live(bt, r)) hv[r] = fs.u.hash.val[hs[r]];
     }
 #pragma unroll
     for (int r = 0; r < CR; ++r) {
-      if (creg[r].y != kFinNone) {
+      if (live(bt, r) && creg[r].y != kFinNone) {
         const uint32_t v = creg[r].y & ~kTagBit;
         float z = __uint_as_float(creg[r].x);
         if (creg[r].y & kTagBit) {
@@ -316,7 +333,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
     if (nb > 1) { load_batch(bt); drop_beyond(bt); }
 #pragma unroll
     for (int r = 0; r < CR; ++r) {
-      if (creg[r].y != kFinNone) {
+      if (live(bt, r) && creg[r].y != kFinNone) {
         const float s = scaled_s(__uint_as_float(creg[r].x));
         const uint32_t k = key_of(s);
         const int bin = bin_of(s, k);
@@ -411,7 +428,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
       }
 #pragma unroll
       for (int r = 0; r < CR; ++r) {
-        if (creg[r].y != kFinNone) {
+        if (live(bt, r) && creg[r].y != kFinNone) {
           const uint32_t k = creg[r].x;
           const int bin = bin_of(value_of(k), k);
           if (bin >= lowbin) {
@@ -741,7 +758,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   return 1;
 }
 
-__global__ __launch_bounds__(kFinThreads) void finish_kernel(Args a_by_value) {
+__global__ __launch_bounds__(kFinThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void finish_kernel(Args a_by_value) {
   // The arguments are read where they are used, straight from the kernel-argument segment
   // (the struct is the only parameter, so it starts at offset 0), instead of being held in
   // scalar registers from the first instruction on: there are more of them than registers.
