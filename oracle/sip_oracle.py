@@ -140,11 +140,19 @@ class RowResult:
     S1: float = 0.0
     S3: float = 0.0
     s: Optional[np.ndarray] = field(default=None, repr=False)
+    # Near-boundary accounting.  ``topp_matters``: moving the top-p cut by the one value group
+    # that lies within the margin changes the final kept set (it does not when min-p removes
+    # that group anyway).  ``alt_tokens``: what the draw returns under each such neighbouring
+    # decision -- the cut one group earlier or later, the CDF entry before or after the one
+    # chosen -- i.e. the only other ids a correct implementation in lower precision may return
+    # for a near-boundary row.  Filled in when a margin is below 1e-5.
+    topp_matters: bool = True
+    alt_tokens: tuple = ()
 
     def flagged(self, eps: float = 1e-6) -> bool:
         """Near-boundary row: the fp64 decision is closer than eps (relative mass) to
         flipping, so an fp32 implementation may legitimately pick the neighbour."""
-        return (self.draw_margin < eps) or (self.topp_margin < eps)
+        return (self.draw_margin < eps) or (self.topp_margin < eps and self.topp_matters)
 
 
 def sample_row(row: np.ndarray, *, temperature: float = 1.0, top_k: int = 0, top_p: float = 1.0,
@@ -219,7 +227,8 @@ def sample_row(row: np.ndarray, *, temperature: float = 1.0, top_k: int = 0, top
         # first position of each element's value group (vals is non-increasing)
         first = np.searchsorted(-vals, -vals, side="left")
         mass_gt = excl[first]
-        target = float(np.float64(p)) * S1
+        target_p = float(np.float64(p)) * S1
+        target = target_p
         keep2 = mass_gt < target
         n2 = int(np.count_nonzero(keep2))                # again a prefix
         # how close the cut came to landing one group earlier or later
@@ -237,23 +246,63 @@ def sample_row(row: np.ndarray, *, temperature: float = 1.0, top_k: int = 0, top
         t = f32(math.log(float(np.float64(mp))))
         keep_sorted &= (s_sorted - m).astype(np.float32) >= t
 
+    minp_sorted = np.ones(V, dtype=bool)
+    if mp > f32(0.0):
+        minp_sorted = (s_sorted - m).astype(np.float32) >= t
+
     kept = np.zeros(V, dtype=bool)
     kept[order[keep_sorted]] = True
 
     # (9) draw (Sec. 2.1 (3)): explicit CDF over the kept set in ascending vocabulary index
     u = row_uniform(seed, row_id, step) if u_override is None else float(u_override)
-    kept_idx = idx[kept]
-    cdf = np.cumsum(e[kept_idx])
+
+    def draw(kept_mask):
+        k_idx = idx[kept_mask]
+        c = np.cumsum(e[k_idx])
+        tgt = u * float(c[-1])
+        h = np.flatnonzero(c > tgt)
+        ps = int(h[0]) if h.size else k_idx.size - 1
+        return k_idx, c, ps
+
+    kept_idx, cdf, pos = draw(kept)
     S3 = float(cdf[-1])
-    target = u * S3
-    hit = np.flatnonzero(cdf > target)
-    pos = int(hit[0]) if hit.size else kept_idx.size - 1
     tok = int(kept_idx[pos])
     draw_margin = float(np.min(np.abs(cdf / S3 - u)))
 
+    # neighbouring decisions of a near-boundary row (see RowResult.alt_tokens)
+    near = 1e-5
+    alts = set()
+    topp_matters = True
+    if draw_margin < near:
+        for q in (pos - 1, pos + 1):
+            if 0 <= q < kept_idx.size:
+                alts.add(int(kept_idx[q]))
+    if topp_margin < near:
+        topp_matters = False
+        variants = []
+        if abs(mass_gt[n2 - 1] - target_p) / S1 < near and first[n2 - 1] > 0:
+            variants.append(int(first[n2 - 1]))                       # the last kept group dropped
+        if n2 < n1 and abs(mass_gt[n2] - target_p) / S1 < near:
+            variants.append(int(np.searchsorted(-vals, -vals[n2], side="right")))   # the next group kept too
+        for n2v in variants:
+            ks = np.zeros(V, dtype=bool)
+            ks[:n2v] = True
+            ks &= minp_sorted
+            kv = np.zeros(V, dtype=bool)
+            kv[order[ks]] = True
+            if kv.any() and not np.array_equal(kv, kept):
+                topp_matters = True
+                k_idx, c, ps = draw(kv)
+                alts.add(int(k_idx[ps]))
+                for q in (ps - 1, ps + 1):                            # and its own neighbours
+                    if 0 <= q < k_idx.size and float(np.min(np.abs(c / float(c[-1]) - u))) < near:
+                        alts.add(int(k_idx[q]))
+    alts.discard(tok)
+
     return RowResult(tok, float(logprob[tok]), top_ids, top_lp, False,
                      kept if keep_arrays else None, u, draw_margin, topp_margin,
-                     float(m), logZ, S1, S3, s if keep_arrays else None)
+                     float(m), logZ, S1, S3, s if keep_arrays else None,
+                     topp_matters, tuple(sorted(alts)))
 
 
 # ----------------------------------------------------------------------------------

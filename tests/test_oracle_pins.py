@@ -262,3 +262,30 @@ def test_margins_flag_the_rows_that_can_flip():
     r = O.sample_row(zz, top_p=2.0 / 3.0, u_override=0.1)
     assert r.topp_margin < 1e-6 and r.flagged()
     assert not O.sample_row(zz, top_p=0.5, u_override=0.1).flagged()
+
+
+# ---------------------------------------------------------------- near-boundary accounting
+def test_alternatives_of_a_draw_next_to_a_cdf_edge_are_the_neighbouring_tokens():
+    # four equal logits: CDF edges at 1/4, 1/2, 3/4; a uniform just below 1/2 picks token 1 and is
+    # within 1e-6 of the edge, so a lower-precision CDF may land on token 2 (or, the other way, 0)
+    row = np.zeros(4, dtype=np.float32)
+    r = O.sample_row(row, temperature=1.0, u_override=0.5 - 1e-9)
+    assert r.token == 1 and r.flagged() and r.draw_margin < 1e-8
+    assert set(r.alt_tokens) == {0, 2}
+    far = O.sample_row(row, temperature=1.0, u_override=0.4)
+    assert far.token == 1 and not far.flagged() and far.alt_tokens == ()
+
+
+def test_alternatives_of_a_nucleus_cut_on_a_group_edge():
+    # probabilities 1/2, 1/4, 1/8, 1/8 and p = 3/4: the mass above the tied pair {2, 3} equals the
+    # target up to rounding, so the pair is kept or dropped on the last bit; u = 0.9 then draws
+    # token 3 (pair kept) or token 1 (pair dropped) -- one is the result, the other the alternative
+    row = np.log(np.array([0.5, 0.25, 0.125, 0.125])).astype(np.float32)
+    r = O.sample_row(row, temperature=1.0, top_p=0.75, u_override=0.9)
+    assert r.topp_margin < 1e-9 and r.topp_matters and r.flagged()
+    assert {r.token} | set(r.alt_tokens) == {1, 3}
+    # with min-p 0.3 the pair (1/8 < 0.3 * 1/2) is removed wherever the nucleus ends: the same
+    # razor-edge cut no longer decides anything, and the row is not near-boundary
+    q = O.sample_row(row, temperature=1.0, top_p=0.75, min_p=0.3, u_override=0.9)
+    assert q.topp_margin < 1e-9 and not q.topp_matters and not q.flagged()
+    assert q.token == 1 and q.alt_tokens == ()
