@@ -167,9 +167,21 @@ sip_status sip_sample_sharded(const void* const* shard_logits, int32_t t, int32_
  *   byte 0    uint64  tick      sampling calls made on the state since sip_state_init()
  *   byte 8    uint32  overflow  ids that found their slot full, plus prompts cut to L_max
  *   byte 256  int32   len[slots]
- *   byte 256 + round_up(4 * slots, 256)       int32 for the library's own use [slots]
+ *   byte 256 + round_up(4 * slots, 256)       int32 distinct[slots]: distinct tokens in the slot's
+ *                                             table below, -1 = the table has been given up
  *   byte 256 + 2 * round_up(4 * slots, 256)   int32 tokens[slots][L_max]
- * Calls that touch one state must be ordered (same stream, or events between streams).
+ *   after that, rounded up to 256             per slot a table token -> number of occurrences in
+ *                                             the slot's history: uint32 key[4096] (0xFFFFFFFF =
+ *                                             free), uint32 count[4096]; open addressing in 1024
+ *                                             buckets of 4 slots, home bucket (token * 0x9E3779B1)
+ *                                             >> 22.  Updated at the one new token per call
+ *                                             (Sec. 5.1 "incremental penalty construction"); a
+ *                                             history with more than 3072 distinct tokens gives
+ *                                             its table up and is counted per call like a CSR.
+ * Calls that touch the same SLOTS of a state must be ordered (same stream, or events between
+ * streams); calls on disjoint sets of slots may be in flight at once on different streams with
+ * different workspaces (the batches a pipeline keeps in flight): each takes its own value of the
+ * call counter, in the order in which their first kernels happen to start.
  */
 
 /* Bytes of a state with this shape; 0 if slots or L_max is not in 1..SIP_MAX_SLOTS / 1..SIP_MAX_L. */

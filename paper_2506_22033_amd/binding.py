@@ -339,6 +339,9 @@ def sip_sample_state(logits: torch.Tensor, params: Optional[Dict[str, Optional[t
     return out_ids, out_lp_ids, out_lp
 
 
+STATE_TABLE_SLOTS = 4096     # slots of a state's per-sequence table of multiplicities
+
+
 def state_views(state: torch.Tensor, slots: int, L_max: int):
     """(tick, overflow, len [slots], tokens [slots, L_max]) as views of a state buffer, per the
     layout that include/sip.h documents."""
@@ -349,6 +352,16 @@ def state_views(state: torch.Tensor, slots: int, L_max: int):
     base = 256 + 2 * len_bytes
     tokens = state[base:base + 4 * slots * L_max].view(torch.int32).view(slots, L_max)
     return tick, overflow, length, tokens
+
+
+def state_table_views(state: torch.Tensor, slots: int, L_max: int):
+    """(distinct [slots], keys [slots, 4096], multiplicities [slots, 4096]) of a state buffer:
+    each slot's table token -> occurrences (key -1 = free slot; distinct -1 = table given up)."""
+    len_bytes = (4 * slots + 255) // 256 * 256
+    distinct = state[256 + len_bytes:256 + len_bytes + 4 * slots].view(torch.int32)
+    base = 256 + 2 * len_bytes + (4 * slots * L_max + 255) // 256 * 256
+    tab = state[base:base + slots * 2 * STATE_TABLE_SLOTS * 4].view(torch.int32).view(slots, 2, STATE_TABLE_SLOTS)
+    return distinct, tab[:, 0], tab[:, 1]
 
 
 # ---- vocabulary-sharded logits

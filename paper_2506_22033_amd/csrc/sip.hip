@@ -142,7 +142,7 @@ Layout make_layout(int32_t B, const Plan& p, int64_t nnz, size_t gather_row_byte
   size_t off = 0;
   l.row_path = off; off += align_up((size_t)2 * B * sizeof(int));            // first, so that callers can find it: path
                                                                              // codes, then the finishing kernel's own codes
-  l.rescue = off; off += align_up((size_t)(B + 1) * sizeof(int));            // count, then row numbers
+  l.rescue = off; off += align_up((size_t)(B + 1) * sizeof(int) + 16);       // count, row numbers, the state's call counter
   l.side_z = off; off += align_up((size_t)nnz * sizeof(float));
   l.side_c = off; off += align_up((size_t)nnz * sizeof(unsigned int));
   l.rowinfo = off;
@@ -229,10 +229,10 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
   a.tokens = h.tokens;
   a.nnz = h.slot ? (long long)h.slots * h.L_max : ((h.indptr && h.tokens) ? h.nnz : 0);
   a.slot = h.slot; a.L_max = h.L_max; a.slots = h.slots;
-  a.st_len = h.state.len; a.st_ndist = h.state.ndist; a.st_tokens = h.state.tokens;
+  a.st_len = h.state.len; a.st_ndist = h.state.ndist; a.st_tokens = h.state.tokens; a.st_table = h.state.table;
   a.st_tick = h.slot ? &h.state.head->tick : nullptr;
   a.st_overflow = h.slot ? &h.state.head->overflow : nullptr;
-  a.tick_bias = 0;
+  a.call_tick = nullptr;
   a.seed = seed; a.step = step;
   a.out_ids = out_ids; a.out_lp_ids = out_lp_ids; a.out_lp = out_lp; a.k_lp = k_logprobs;
   char* ws = static_cast<char*>(workspace);
@@ -248,6 +248,7 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
   a.row_why = a.row_path + B;
   a.rescue_n = reinterpret_cast<int*>(ws + lay.rescue);
   a.rescue_rows = a.rescue_n + 1;
+  a.rescue_tick = reinterpret_cast<unsigned long long*>(ws + lay.rescue + ((size_t)(B + 1) * sizeof(int) + 7) / 8 * 8);
 
   sip::StateHeader* head = h.slot ? h.state.head : nullptr;
   return sh.t ? launch<true>(a, B, (int)dtype, plan, h.slot != nullptr, head, stream)
@@ -272,7 +273,7 @@ sip_status launch(const sip::Args& a_in, int32_t B, int dtype, const Plan& plan,
     }
     return SIP_OK;
   }
-  a.tick_bias = state ? 1 : 0;             // the streaming kernel counts the call, the finishing kernel knows
+  a.call_tick = state ? a.rescue_tick : nullptr;   // the streaming kernel takes the state's counter and leaves it here
   auto k_stream = dtype == SIP_F32 ? sip::stream_kernel<SIP_F32, SH> : sip::stream_kernel<SIP_BF16, SH>;
   auto k_rescue = dtype == SIP_F32 ? sip::rescue_kernel<SIP_F32, SH> : sip::rescue_kernel<SIP_BF16, SH>;
   const size_t dyn = std::max(plan.final_lds, 2 * words * sizeof(uint32_t));
@@ -380,9 +381,8 @@ sip_status sip_state_init(void* state, size_t state_bytes, int32_t slots, int32_
   if (!state_shape_ok(slots, L_max)) return SIP_ERR_INVALID_ARG;
   if (!state_ok(state, state_bytes, slots, L_max)) return SIP_ERR_WORKSPACE;
   const sip::StateView v = sip::state_view(state, slots, L_max);
-  const int blocks = (slots + sip::kStateThreads - 1) / sip::kStateThreads;
-  hipLaunchKernelGGL(sip::state_init_kernel, dim3(blocks), dim3(sip::kStateThreads), 0,
-                     static_cast<hipStream_t>(hip_stream), v.head, v.len, v.ndist, slots);
+  hipLaunchKernelGGL(sip::state_init_kernel, dim3(slots), dim3(sip::kStateThreads), 0,
+                     static_cast<hipStream_t>(hip_stream), v.head, v.len, v.ndist, v.table, slots);
   return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
 }
 
@@ -396,7 +396,7 @@ sip_status sip_state_assign(void* state, size_t state_bytes, int32_t slots, int3
   if (n == 0) return SIP_OK;
   const sip::StateView v = sip::state_view(state, slots, L_max);
   hipLaunchKernelGGL(sip::state_assign_kernel, dim3(n), dim3(sip::kStateThreads), 0,
-                     static_cast<hipStream_t>(hip_stream), v.head, v.len, v.ndist, v.tokens, slots, L_max, slot_ids,
+                     static_cast<hipStream_t>(hip_stream), v.head, v.len, v.ndist, v.tokens, v.table, slots, L_max, slot_ids,
                      reinterpret_cast<const long long*>(indptr), tokens, (long long)nnz);
   return hipGetLastError() == hipSuccess ? SIP_OK : SIP_ERR_HIP;
 }

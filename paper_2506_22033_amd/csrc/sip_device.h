@@ -35,7 +35,8 @@ struct RowInfo {
   int top_k, target;
   unsigned long long row_id;
   long long lo, hi;
-  int pad[2];
+  int slot;                 // device-resident state: the row's slot, -1 = none (or a CSR call)
+  int ndist;                // ... and the distinct tokens in the slot's table of multiplicities, -1 = table not valid
 };
 static_assert(sizeof(RowInfo) == 64, "one 64-byte record per row");
 
@@ -68,16 +69,18 @@ struct Args {
   int* row_why;             // [B] diagnostic: 1, or why the finishing kernel handed the row to the rescue kernel
   int* rescue_n;            // rows the finishing kernel could not settle from the list ...
   int* rescue_rows;         // [B] ... and which; the rescue kernel takes them from here
+  unsigned long long* rescue_tick;   // room in the workspace for `call_tick`
   // Device-resident history (sip_sample_state): `slot` != nullptr replaces the CSR above.  Row b's
   // history is tokens[slot[b] * L_max .. + st_len[slot[b]]); `tokens` then points at the state's
   // token table and nnz = slots * L_max.
   const int* slot;                     // [B]; outside [0, slots): the row has no history
   int* st_len;                         // [slots]
-  int* st_ndist;                       // [slots] upper bound on the slot's distinct tokens, -1 = unknown
+  int* st_ndist;                       // [slots] distinct tokens in the slot's table of multiplicities, -1 = table not valid
+  uint32_t* st_table;                  // [slots, 2 * kTableSlots]: per slot, keys then multiplicities
+  unsigned long long* call_tick;       // workspace: the state's call counter as this call found it
   int* st_tokens;                      // [slots, L_max]: same memory as `tokens`, for the append
   unsigned long long* st_tick;         // sampling calls made on the state so far; added to `step`
   unsigned int* st_overflow;           // ids that found their slot full
-  int tick_bias;                       // 1: the streaming kernel has already counted this call in *st_tick
   // Vocabulary-sharded logits (sip_sample_sharded): row b is the concatenation of t_shards pieces of
   // V_shard elements, piece i at shard[i] + b * shard_stride elements.  `logits` / `row_stride` then
   // describe the workspace rows that a workgroup gathers its row into before any whole-row access.
@@ -136,27 +139,93 @@ __device__ __attribute__((noinline)) void gather_row(const Args& a, int b) {
   }
   __syncthreads();
 }
-// Philox step of this call.
+// Philox step of this call: on a state, `step` plus the number of calls made on the state before
+// this one.  The streaming kernel takes that number (one atomic add, so that calls in flight at
+// once on one state each get their own) and leaves it in the call's workspace; a call that has no
+// streaming kernel reads the counter itself and counts afterwards.
 __device__ __forceinline__ unsigned long long step_of(const Args& a) {
-  return a.step + (a.st_tick ? *a.st_tick - (unsigned long long)a.tick_bias : 0ull);
+  if (!a.st_tick) return a.step;
+  return a.step + (a.call_tick ? *a.call_tick : *a.st_tick);
 }
-// Row b's sampled id joins the history of its slot.  For one thread of the row's workgroup, once
-// out_ids[b] is written and visible to it.  Nobody else reads or writes this slot during the call
-// (the slots of a call are distinct).  `ndist`: the distinct tokens the slot held before the
-// append if this call counted them, else -1; either way the stored bound stays a bound, because
-// one more token is at most one more distinct token.
-__device__ __forceinline__ void state_append_row(const Args& a, int b, int ndist) {
+
+// ---------------------------------------------------------------- table of multiplicities
+// token -> number of occurrences in a history, as an open-addressing hash table of
+// kTableSlots / 4 buckets of four slots: `key[kTableSlots]` (kTableEmpty = free) and
+// `val[kTableSlots]`.  A token lives in the first bucket, from its home bucket on, that had a
+// free slot when it came; the slots of a bucket fill in order, and a key, once there, stays.
+// The finishing kernel builds one per row in LDS, or copies the one a device-resident state
+// keeps per slot and updates at the one new token per call (Sec. 5.1, incremental penalty
+// construction).
+constexpr int kTableSlots = 4096;
+constexpr int kTableMaxDistinct = 3072;            // beyond this load the table is given up
+constexpr uint32_t kTableEmpty = 0xFFFFFFFFu;
+static_assert(kTableSlots == 4096, "table_home() yields 10 bits: 1024 buckets of 4 slots");
+__device__ __forceinline__ uint32_t table_home(uint32_t t) { return (t * 0x9E3779B1u) >> 22; }
+
+// Insert by many threads at once (LDS).  Returns 1 if this call claimed a new slot, 0 if the
+// token was there already, -1 if the table is full.
+__device__ __forceinline__ int table_insert_shared(uint32_t* key, uint32_t* val, uint32_t t) {
+  const uint4* key4 = reinterpret_cast<const uint4*>(key);
+  uint32_t bk = table_home(t);
+  for (int probe = 0; probe < kTableSlots / 4; ++probe) {
+    const uint4 k4 = key4[bk];
+    const uint32_t ks[4] = {k4.x, k4.y, k4.z, k4.w};
+    int j = -1, fresh = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (j < 0 && ks[e] == t) j = e;
+      if (j < 0 && ks[e] == kTableEmpty) {                 // free when read: try to take it
+        const uint32_t old = atomicCAS(&key[4 * bk + e], kTableEmpty, t);
+        if (old == kTableEmpty) { fresh = 1; j = e; } else if (old == t) j = e;
+      }
+    }
+    if (j >= 0) { atomicAdd(&val[4 * bk + j], 1u); return fresh; }
+    bk = (bk + 1) & (kTableSlots / 4 - 1);
+  }
+  return -1;
+}
+// Insert by the one thread that owns the table (global memory): one 16-byte read per bucket
+// looked at.  Same return values.
+__device__ __forceinline__ int table_insert_single(uint32_t* key, uint32_t* val, uint32_t t) {
+  const uint4* key4 = reinterpret_cast<const uint4*>(key);
+  uint32_t bk = table_home(t);
+  for (int probe = 0; probe < kTableSlots / 4; ++probe) {
+    const uint4 k4 = key4[bk];
+    const uint32_t hit = (uint32_t)(k4.x == t) | ((uint32_t)(k4.y == t) << 1) | ((uint32_t)(k4.z == t) << 2) |
+                         ((uint32_t)(k4.w == t) << 3);
+    const uint32_t free = (uint32_t)(k4.x == kTableEmpty) | ((uint32_t)(k4.y == kTableEmpty) << 1) |
+                          ((uint32_t)(k4.z == kTableEmpty) << 2) | ((uint32_t)(k4.w == kTableEmpty) << 3);
+    if (hit) { val[4 * bk + (uint32_t)(__ffs((int)hit) - 1)] += 1u; return 0; }
+    if (free) {
+      const uint32_t e = 4 * bk + (uint32_t)(__ffs((int)free) - 1);
+      key[e] = t; val[e] = 1u;
+      return 1;
+    }
+    bk = (bk + 1) & (kTableSlots / 4 - 1);
+  }
+  return -1;
+}
+
+// Row b's sampled id joins the history of its slot, and the slot's table of multiplicities.  For
+// one thread of the row's workgroup, once out_ids[b] is written and visible to it.  Nobody else
+// reads or writes this slot during the call (the slots of a call are distinct).
+__device__ __forceinline__ void state_append_row(const Args& a, int b) {
   const int s = a.slot[b];
   if (s < 0 || s >= a.slots) return;
   const int n = a.st_len[s];
-  const int old = a.st_ndist[s];
-  const int known = ndist >= 0 ? ndist : old;
   if (n >= 0 && n < a.L_max) {
-    a.st_tokens[(size_t)s * (size_t)a.L_max + n] = a.out_ids[b];
+    const int tok = a.out_ids[b];
+    a.st_tokens[(size_t)s * (size_t)a.L_max + n] = tok;
     a.st_len[s] = n + 1;
-    a.st_ndist[s] = known >= 0 ? known + 1 : -1;
+    int nd = a.st_ndist[s];
+    if (nd >= 0 && tok >= 0) {
+      uint32_t* key = a.st_table + (size_t)s * (size_t)(2 * kTableSlots);
+      const int r = table_insert_single(key, key + kTableSlots, (uint32_t)tok);
+      nd = r < 0 ? -1 : nd + r;
+      if (nd > kTableMaxDistinct) nd = -1;
+      a.st_ndist[s] = nd;
+    }
   } else {
-    a.st_ndist[s] = known;
     atomicAdd(a.st_overflow, 1u);
   }
 }

@@ -547,7 +547,7 @@ __global__ __launch_bounds__(kExactThreads) void exact_kernel(Args a) {
   if (threadIdx.x == 0) { a.row_path[blockIdx.x] = 14; a.row_why[blockIdx.x] = 14; }   // 14: shape outside the single-pass kernels
   if (a.slot) {                                          // device-resident history: the row's id joins it
     __syncthreads();
-    if (threadIdx.x == 0) state_append_row(a, blockIdx.x, -1);
+    if (threadIdx.x == 0) state_append_row(a, blockIdx.x);
   }
 }
 

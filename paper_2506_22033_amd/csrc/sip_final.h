@@ -990,7 +990,7 @@ __global__ __launch_bounds__(kFinalThreads) void rescue_kernel(Args a_by_value) 
   if (threadIdx.x == 0) a.row_path[b] = code ? code : how;
   if (a.slot) {                                  // device-resident history: the row's id joins it
     __syncthreads();
-    if (threadIdx.x == 0) state_append_row(a, b, target != 0 ? fs.ndist_out : -1);
+    if (threadIdx.x == 0) state_append_row(a, b);
   }
   }
 }

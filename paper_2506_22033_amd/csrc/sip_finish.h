@@ -133,12 +133,23 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   const long long h_lo = ri.lo, h_hi = ri.hi;
   const bool has_pen = (h_hi > h_lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
   const bool need_hash = has_pen && rp.phi != 0.0f;
+  // a device-resident state keeps the row's table of multiplicities: copy it instead of counting
+  // (32 KB to copy against 4 bytes and two LDS atomics per history token: it pays from about two
+  // thousand tokens on)
+  const bool use_table = need_hash && ri.slot >= 0 && ri.ndist >= 0 && ri.hi - ri.lo > 2048;
+  static_assert(kFinHash == kTableSlots && kFinHashMax == kTableMaxDistinct, "one table geometry");
+  uint4 tq[2 * kFinHash * 4 / 16 / NT];
+  if (use_table) {
+    const uint4* t4 = reinterpret_cast<const uint4*>(a.st_table + (size_t)ri.slot * (size_t)(2 * kTableSlots));
+#pragma unroll
+    for (int j = 0; j < 2 * kFinHash * 4 / 16 / NT; ++j) tq[j] = t4[j * NT + tid];
+  }
   constexpr int HR = 8;                    // history tokens a thread requests at once
   int htok[HR];
 #pragma unroll
   for (int j = 0; j < HR; ++j) {
     const long long i = h_lo + tid + (long long)j * NT;
-    htok[j] = (need_hash && i < h_hi) ? a.tokens[i] : -1;
+    htok[j] = (need_hash && !use_table && i < h_hi) ? a.tokens[i] : -1;
   }
   {
     // hcnt, off, fill, hmass, hidx are contiguous: 28 KB, of which `off` need not be cleared
@@ -146,7 +157,11 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
     for (int i = tid; i < kFinBins * 4 / 16; i += NT) z4[i] = make_uint4(0, 0, 0, 0);
     z4 = reinterpret_cast<uint4*>(fs.fill);
     for (int i = tid; i < kFinBins * 20 / 16; i += NT) z4[i] = make_uint4(0, 0, 0, 0);
-    if (need_hash) {
+    if (use_table) {                       // keys and multiplicities lie one behind the other, here as there
+      uint4* k4 = reinterpret_cast<uint4*>(fs.u.hash.key);
+#pragma unroll
+      for (int j = 0; j < 2 * kFinHash * 4 / 16 / NT; ++j) k4[j * NT + tid] = tq[j];
+    } else if (need_hash) {
       uint4* k4 = reinterpret_cast<uint4*>(fs.u.hash.key);
       for (int i = tid; i < kFinHash * 4 / 16; i += NT) k4[i] = make_uint4(kFinNone, kFinNone, kFinNone, kFinNone);
       uint4* v4 = reinterpret_cast<uint4*>(fs.u.hash.val);
@@ -189,7 +204,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   uint4* const hkey4 = reinterpret_cast<uint4*>(fs.u.hash.key);
   auto home = [](uint32_t t) { return (t * 0x9E3779B1u) >> 22; };
   static_assert(kFinHash == 4096, "home() yields 10 bits: 1024 buckets of 4 slots");
-  if (need_hash) {
+  if (need_hash && !use_table) {
     uint32_t mine = 0;                     // slots this thread claimed = distinct tokens it saw first
     auto insert = [&](int ti) {
       if (ti < 0 || ti >= V) return;
@@ -321,7 +336,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
       a.out_lp_ids[(size_t)b * cols] = (int)token;
       a.out_lp[(size_t)b * cols] = (float)((double)value_of(token_key) - (double)m - lnZ);
     }
-    if (a.slot) state_append_row(a, b, -1);
+    if (a.slot) state_append_row(a, b);
   };
   if (rp.greedy && a.k_lp < 0) {           // the arg max is all that is asked for
     if (tid == 0) emit(bidx, key_of(m), 0.0);

@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
   // on logical chunk (i % 8) * (n / 8) + i / 8 when n, the grid size, is a multiple of 8.
   // Device-resident history: this call is counted here, before the finishing kernel (which runs
   // after this one and knows that it has been counted) reads the counter.
-  if (a.tick_bias && blockIdx.x == 0 && tid == 0) *a.st_tick += 1ull;
+  if (a.call_tick && blockIdx.x == 0 && tid == 0) *a.call_tick = atomicAdd(a.st_tick, 1ull);
   if (blockIdx.x == 0 && tid == 0) *a.rescue_n = 0;          // the finishing kernel counts from zero
   int wg = blockIdx.x;
   if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
@@ -267,7 +267,11 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     RowInfo ri;
     ri.tau = rp.tau; ri.top_p = rp.top_p; ri.min_p = rp.min_p; ri.theta = rp.theta; ri.phi = rp.phi; ri.psi = rp.psi;
     ri.top_k = rp.top_k; ri.target = target; ri.row_id = rp.row_id; ri.lo = hr.lo; ri.hi = hr.hi;
-    ri.pad[0] = ri.pad[1] = 0;
+    ri.slot = -1; ri.ndist = -1;
+    if (a.slot) {
+      const int sl = a.slot[b];
+      if (sl >= 0 && sl < a.slots) { ri.slot = sl; ri.ndist = a.st_ndist[sl]; }
+    }
     a.rowinfo[b] = ri;
   }
   int htok[kStreamHistRegs];

@@ -94,8 +94,9 @@ def test_bad_arguments_are_rejected_on_the_host(over, want):
 
 
 def test_state_size_query():
-    assert sip.sip_state_bytes(256, 4096) == 256 + 2 * 1024 + 256 * 4096 * 4
-    assert sip.sip_state_bytes(3, 5) == 256 + 2 * 256 + 60
+    table = 2 * 4096 * 4                                  # per slot: 4096 keys and 4096 multiplicities
+    assert sip.sip_state_bytes(256, 4096) == 256 + 2 * 1024 + 256 * 4096 * 4 + 256 * table
+    assert sip.sip_state_bytes(3, 5) == 256 + 2 * 256 + 256 + 3 * table
     for slots, L in [(0, 5), (-1, 5), (4, 0), (sip.SIP_MAX_SLOTS + 1, 4), (4, sip.SIP_MAX_L + 1)]:
         assert sip.sip_state_bytes(slots, L) == 0
 
@@ -121,7 +122,7 @@ def _call_state(**over):
     (dict(B=0), binding.SIP_ERR_INVALID_ARG),
     (dict(state=None), binding.SIP_ERR_WORKSPACE),
     (dict(state=0x80010), binding.SIP_ERR_WORKSPACE),                # not 256-byte aligned
-    (dict(state_bytes=256 + 2 * 256 + 8 * 64 * 4 - 1), binding.SIP_ERR_WORKSPACE),
+    (dict(state_bytes=256 + 2 * 256 + 8 * 64 * 4 + 8 * 2 * 4096 * 4 - 1), binding.SIP_ERR_WORKSPACE),
     (dict(logits=None), binding.SIP_ERR_INVALID_ARG),                # the checks of sip_sample apply too
     (dict(stride=1001), binding.SIP_ERR_INVALID_ARG),
     (dict(ws_bytes=4 * 64 * 8 - 1), binding.SIP_ERR_WORKSPACE),      # side tables of B * L_max entries

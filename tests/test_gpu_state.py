@@ -106,13 +106,22 @@ def _decode(name, V, B, slots, L_max, slot_of_row, prompts, T, seed, bf16=False,
     assert np.array_equal(length, ost.length)
     for s in range(slots):
         assert np.array_equal(tokens[s, :length[s]], ost.history(s)), f"{name}: slot {s}"
-    # the library's own per-slot figure (an upper bound on the slot's distinct tokens, or -1) must
-    # never be too small: it decides which code path is tried first
-    lb = (4 * slots + 255) // 256 * 256
-    hint = dst.buf[256 + lb:256 + lb + 4 * slots].view(torch.int32).cpu().numpy()
+    # each slot's table of multiplicities, kept up to date at the one new token per call, against
+    # the oracle's frequency vector f (Sec. 5.1: f is updated at the newly generated tokens only)
+    distinct, keys, counts = sip.state_table_views(dst.buf, slots, L_max)
+    distinct, keys, counts = distinct.cpu().numpy(), keys.cpu().numpy(), counts.cpu().numpy()
     for s in range(slots):
         h = ost.history(s)
-        assert hint[s] == -1 or hint[s] >= len(np.unique(h[(h >= 0) & (h < V)])), f"{name}: slot {s} hint {hint[s]}"
+        h = h[h >= 0]
+        want = dict(zip(*[x.tolist() for x in np.unique(h, return_counts=True)]))
+        if distinct[s] == -1:
+            assert len(want) > 3072, f"{name}: slot {s} gave its table up at {len(want)} distinct tokens"
+            continue
+        used = keys[s] != -1
+        got = dict(zip(keys[s][used].tolist(), counts[s][used].tolist()))
+        assert distinct[s] == len(want) and got == want, f"{name}: slot {s} table"
+        in_v = {t: c for t, c in want.items() if t < V}
+        assert all(ost.f[s, t] == c for t, c in in_v.items()) and int(ost.f[s].sum()) == sum(in_v.values())
     print(f"[state] {name}: {stats.rows} rows, paths {paths}, flagged={stats.flagged} "
           f"mismatch={stats.flagged_mismatch} overflow={ovf} max|dlogprob|={stats.max_lp_err:.2e}")
     return stats
@@ -128,6 +137,17 @@ def test_decode_iterations_on_device_state_match_the_oracle(V, bf16):
     st = _decode(f"state V={V} {'bf16' if bf16 else 'f32'}", V, B, slots, L_max, slot_of_row, prompts, T=6,
                  seed=V, bf16=bf16)
     assert st.rows == 6 * B
+
+
+def test_long_histories_use_the_tables_the_state_keeps():
+    """Histories of a few thousand tokens: the finishing kernel copies the slot's table of
+    multiplicities instead of counting the history.  Slot 2 has more distinct tokens than a table
+    takes: its table is given up and the row is counted, and finished, the long way."""
+    rng = np.random.default_rng(21)
+    V, B, slots, L_max = 40009, 4, 4, 4200
+    zipf = lambda n: (rng.zipf(1.2, n) % V).tolist()
+    prompts = {0: zipf(2500), 1: zipf(3900), 2: rng.permutation(V)[:3500].tolist(), 3: zipf(2100)}
+    _decode("state long", V, B, slots, L_max, [0, 1, 2, 3], prompts, T=4, seed=10)
 
 
 def test_full_slots_stay_as_they_are_and_long_prompts_are_cut():
@@ -236,3 +256,67 @@ def test_recorded_decode_step_replays_with_fresh_numbers_each_time():
     tick, ovf, length, tokens = dst.read()
     assert tick == 4 and ovf == 0 and (length == 4).all()
     assert np.array_equal(tokens[:, :4], np.stack(seen, axis=1))
+
+
+def test_two_batches_in_flight_on_disjoint_slots_of_one_state():
+    """The microbatches of a pipeline share one state and run on their own streams with their own
+    workspaces: neither sees the other's slots, every call gets a call-counter value of its own,
+    and each batch's ids equal the oracle's for the counter value it drew."""
+    import workloads
+    rng = np.random.default_rng(31)
+    V, Bh, slots, L_max, T = 30011, 6, 12, 64, 3
+    dst = DeviceState(slots, L_max)
+    prompts = {s: rng.integers(0, V, int(rng.integers(0, 30))).tolist() for s in range(slots)}
+    dst.assign(list(range(slots)), [prompts[s] for s in range(slots)])
+    ost = O.DecodeState(slots, L_max, V)
+    for s in range(slots):
+        ost.assign(s, prompts[s])
+    halves = [list(range(0, 6)), list(range(6, 12))]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for t in range(T):
+        work = []
+        for hidx, (rows_slots, st) in enumerate(zip(halves, streams)):
+            z = rng.normal(0.0, 2.5, (Bh, V)).astype(np.float32)
+            p = _params(rng, Bh, V)
+            p["temperature"][:] = np.maximum(p["temperature"], 0.3)        # stochastic rows: the counter matters
+            p["top_k"][:] = np.where(p["top_k"] == 1, 5, p["top_k"])
+            dparams = {k: torch.from_numpy(v).to(DEV) for k, v in p.items()}
+            rid = np.arange(100 * hidx, 100 * hidx + Bh, dtype=np.int64)
+            dparams["row_id"] = torch.from_numpy(rid).to(DEV)
+            dl = H.logits_to_device(z)
+            ws = torch.empty(sip.sip_workspace_bytes(Bh, V, sip.SIP_F32, Bh * L_max, 2), dtype=torch.uint8, device=DEV)
+            slot_dev = torch.tensor(rows_slots, dtype=torch.int32, device=DEV)
+            work.append((z, p, rid, dl, dparams, ws, slot_dev, rows_slots))
+        torch.cuda.synchronize()
+        outs = []
+        for (z, p, rid, dl, dparams, ws, slot_dev, rows_slots), st in zip(work, streams):      # both enqueued, no wait between
+            with torch.cuda.stream(st):
+                outs.append(sip.sip_sample_state(dl, dparams, dst.buf, slots, L_max, slot_dev, 5, 40, 2, V=V,
+                                                 workspace=ws, stream=st))
+        torch.cuda.synchronize()
+        # which call drew which counter value is decided on the device: either order must explain both
+        base = ost.tick
+        ok = False
+        for order in ((0, 1), (1, 0)):
+            trial = [None, None]
+            good = True
+            for tick_off, hidx in enumerate(order):
+                z, p, rid, dl, dparams, ws, slot_dev, rows_slots = work[hidx]
+                ref = [O.sample_row(z[b], counts=ost.f[rows_slots[b]], seed=5, step=40 + base + tick_off, row_id=int(rid[b]),
+                                    n_logprobs=2, **{k: v[b] for k, v in p.items()}) for b in range(Bh)]
+                ids = outs[hidx][0].cpu().numpy()
+                good &= all(ids[b] == r.token or (r.flagged() and int(ids[b]) in r.alt_tokens) for b, r in enumerate(ref))
+                trial[hidx] = ids
+            if good:
+                ok = True
+                break
+        assert ok, f"iteration {t}: no order of the two calls explains their ids"
+        for hidx in (0, 1):
+            for b, s in enumerate(halves[hidx]):
+                ost._push(s, int(trial[hidx][b]))
+        ost.tick += 2
+    tick, ovf, length, tokens = dst.read()
+    assert tick == 2 * T and ovf == 0
+    for s in range(slots):
+        assert np.array_equal(tokens[s, :length[s]], ost.history(s)), f"slot {s}"
