@@ -99,9 +99,16 @@ def history_counts(history: np.ndarray, V: int) -> np.ndarray:
     return c
 
 
-def apply_penalties(z: np.ndarray, c: np.ndarray, theta: float, phi: float, psi: float) -> np.ndarray:
+def apply_penalties(z: np.ndarray, c: np.ndarray, theta: float, phi: float, psi: float,
+                    c_prompt: Optional[np.ndarray] = None) -> np.ndarray:
     """ApplyPenalty of Sec. 2.1 (1) / Sec. 5.1, in IEEE fp32, one rounding per operation,
     only where c_v > 0, in the order repetition -> frequency -> presence.
+
+    ``c_prompt`` (optional): occurrences in the sequence's prompt, handed in separately from the
+    generated tokens.  Sec. 2.1 defines y_<s as the *generated* tokens while a sequence is prompt
+    plus output; the reading taken for a separate prompt is the usual one of serving engines: the
+    repetition penalty looks at prompt and output together, frequency and presence at the output
+    only.  Without ``c_prompt`` one history serves all three.
 
     The paper writes all three as ``Z - alpha * f``.  Frequency and presence are taken
     that way (f = count, resp. f = 1 for seen tokens).  Repetition is taken in the
@@ -109,11 +116,17 @@ def apply_penalties(z: np.ndarray, c: np.ndarray, theta: float, phi: float, psi:
     theta, multiply the others), the form under which theta = 1 is "off"."""
     f32 = np.float32
     out = z.astype(np.float32, copy=True)
+    th, ph, ps = f32(theta), f32(phi), f32(psi)
+    if c_prompt is not None and th != f32(1.0):
+        # repetition over prompt and output; the tokens of the output alone go on below
+        rep = np.flatnonzero((c > 0) | (np.asarray(c_prompt) > 0))
+        y = out[rep]
+        out[rep] = np.where(y > f32(0.0), y / th, y * th).astype(np.float32)
+        th = f32(1.0)
     seen = np.flatnonzero(c > 0)
     if seen.size == 0:
         return out
     x = out[seen]
-    th, ph, ps = f32(theta), f32(phi), f32(psi)
     if th != f32(1.0):
         x = np.where(x > f32(0.0), x / th, x * th).astype(np.float32)
     if ph != f32(0.0):
@@ -160,7 +173,7 @@ def sample_row(row: np.ndarray, *, temperature: float = 1.0, top_k: int = 0, top
                presence_penalty: float = 0.0, history: Optional[np.ndarray] = None,
                seed: int = 0, step: int = 0, row_id: int = 0, n_logprobs: int = 0,
                u_override: Optional[float] = None, keep_arrays: bool = False,
-               counts: Optional[np.ndarray] = None) -> RowResult:
+               counts: Optional[np.ndarray] = None, prompt: Optional[np.ndarray] = None) -> RowResult:
     f32 = np.float32
     V = int(row.shape[0])
     idx = np.arange(V)
@@ -170,7 +183,8 @@ def sample_row(row: np.ndarray, *, temperature: float = 1.0, top_k: int = 0, top
     # iterations, the incremental construction of Sec. 5.1 (see DecodeState below).
     z = widen(row)
     c = history_counts(history, V) if counts is None else np.asarray(counts, dtype=np.int64)
-    z = apply_penalties(z, c, repetition_penalty, frequency_penalty, presence_penalty)
+    z = apply_penalties(z, c, repetition_penalty, frequency_penalty, presence_penalty,
+                        None if prompt is None else history_counts(prompt, V))
 
     tau = f32(temperature)
     k = int(top_k)
@@ -315,7 +329,8 @@ _DEFAULTS = dict(temperature=1.0, top_k=0, top_p=1.0, min_p=0.0,
 def sample_batch(logits: np.ndarray, params: dict, hist_indptr: Optional[np.ndarray],
                  hist_tokens: Optional[np.ndarray], seed: int, step: int, n_logprobs: int,
                  row_ids: Optional[np.ndarray] = None, rows: Optional[Sequence[int]] = None,
-                 keep_arrays: bool = False):
+                 keep_arrays: bool = False, prompt_indptr: Optional[np.ndarray] = None,
+                 prompt_tokens: Optional[np.ndarray] = None):
     """Run ``sample_row`` on the chosen rows (default all) and return the RowResults.
 
     ``params`` maps the names of ``_DEFAULTS`` to per-row arrays or None (feature off)."""
@@ -330,9 +345,12 @@ def sample_batch(logits: np.ndarray, params: dict, hist_indptr: Optional[np.ndar
         hist = None
         if hist_indptr is not None and hist_tokens is not None:
             hist = hist_tokens[int(hist_indptr[b]):int(hist_indptr[b + 1])]
+        prompt = None
+        if prompt_indptr is not None and prompt_tokens is not None:
+            prompt = prompt_tokens[int(prompt_indptr[b]):int(prompt_indptr[b + 1])]
         rid = b if row_ids is None else int(row_ids[b])
         out.append(sample_row(logits[b], history=hist, seed=seed, step=step, row_id=rid,
-                              n_logprobs=n_logprobs, keep_arrays=keep_arrays, **kw))
+                              n_logprobs=n_logprobs, keep_arrays=keep_arrays, prompt=prompt, **kw))
     return out
 
 

@@ -289,3 +289,29 @@ def test_alternatives_of_a_nucleus_cut_on_a_group_edge():
     q = O.sample_row(row, temperature=1.0, top_p=0.75, min_p=0.3, u_override=0.9)
     assert q.topp_margin < 1e-9 and not q.topp_matters and not q.flagged()
     assert q.token == 1 and q.alt_tokens == ()
+
+
+# ---------------------------------------------------------------- separate prompt tokens
+def test_a_separate_prompt_feeds_the_repetition_penalty_only():
+    # z = +2 / -2, theta = 2, phi = 0.5, psi = 0.3.  Token 0: in the output 3 times -> all three
+    # penalties (+2 -> 1 -> -0.5 -> -0.8).  Token 1: in the prompt only -> repetition only (-2 -> -4).
+    # Token 2: in both (output once) -> 2 -> 1 -> 0.5 -> 0.2.  Token 3: in neither -> untouched.
+    z = np.array([2.0, -2.0, 2.0, -2.0], dtype=np.float32)
+    c_out = np.array([3, 0, 1, 0])
+    c_prompt = np.array([0, 5, 2, 0])
+    got = O.apply_penalties(z, c_out, 2.0, 0.5, 0.3, c_prompt)
+    f = np.float32
+    want = np.array([f(-0.5) - f(0.3), -4.0, f(0.5) - f(0.3), -2.0], dtype=np.float32)     # one fp32 rounding per step
+    assert np.array_equal(got, want) and abs(float(got[0]) + 0.8) < 1e-6 and abs(float(got[2]) - 0.2) < 1e-6
+    # a prompt that is handed in as part of the one history counts for everything instead
+    merged = O.apply_penalties(z, c_out + c_prompt, 2.0, 0.5, 0.3)
+    assert np.array_equal(merged, np.array([np.float32(1.0) - np.float32(1.5) - np.float32(0.3),
+                                            np.float32(-4.0) - np.float32(2.5) - np.float32(0.3),
+                                            np.float32(1.0) - np.float32(1.5) - np.float32(0.3), -2.0], dtype=np.float32))
+    # no prompt given, or an empty one, or theta = 1: the separate prompt changes nothing
+    assert np.array_equal(O.apply_penalties(z, c_out, 2.0, 0.5, 0.3, np.zeros(4, int)), O.apply_penalties(z, c_out, 2.0, 0.5, 0.3))
+    assert np.array_equal(O.apply_penalties(z, c_out, 1.0, 0.5, 0.3, c_prompt), O.apply_penalties(z, c_out, 1.0, 0.5, 0.3))
+    # and through the row front end
+    r = O.sample_row(z, temperature=0.0, repetition_penalty=2.0, frequency_penalty=0.5, presence_penalty=0.3,
+                     history=np.array([0, 0, 0, 2]), prompt=np.array([1, 1, 2]), n_logprobs=4, keep_arrays=True)
+    assert np.array_equal(r.s, want) and r.token == 2
