@@ -290,6 +290,14 @@ typedef struct {
   void* workspace;                   /* at least sip_call_workspace_bytes(call) bytes                  */
   size_t workspace_bytes;
   void* hip_stream;
+  /* Prompt tokens handed in separately from the generated ones (Sec. 2.1 defines y_<s as the generated
+   * tokens, a sequence as prompt plus output): a CSR like the history's, device pointers, NULL / 0 =
+   * none.  The repetition penalty then applies to the tokens of prompt and history together, the
+   * frequency and presence penalties to those of the history alone.  Not with a state (whose slots
+   * hold prompt and output as one history): SIP_ERR_INVALID_ARG. */
+  const int64_t* prompt_indptr;      /* [B+1]                                                          */
+  const int32_t* prompt_tokens;      /* [prompt_nnz]; ids outside [0, V) are ignored                   */
+  int64_t prompt_nnz;
 } sip_call;
 
 /* Workspace the call needs (workspace / workspace_bytes / outputs of `call` are not looked at);

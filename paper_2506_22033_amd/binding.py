@@ -46,7 +46,8 @@ class SipCall(ctypes.Structure):
                 ("out_ids", ctypes.c_void_p), ("out_lp_ids", ctypes.c_void_p), ("out_lp", ctypes.c_void_p),
                 ("k_logprobs", ctypes.c_int32),
                 ("host_ids", ctypes.c_void_p), ("host_flag", ctypes.c_void_p), ("ticket", ctypes.c_uint64),
-                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("hip_stream", ctypes.c_void_p)]
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("hip_stream", ctypes.c_void_p),
+                ("prompt_indptr", ctypes.c_void_p), ("prompt_tokens", ctypes.c_void_p), ("prompt_nnz", ctypes.c_int64)]
 
 
 class SipError(RuntimeError):
@@ -475,6 +476,7 @@ def sip_sample_call(*, logits: Optional[torch.Tensor] = None, shards=None, V: Op
                     out_ids: Optional[torch.Tensor] = None, out_lp_ids: Optional[torch.Tensor] = None,
                     out_lp: Optional[torch.Tensor] = None, host_ids: Optional[torch.Tensor] = None,
                     host_flag: Optional[torch.Tensor] = None, ticket: int = 0,
+                    prompt_indptr: Optional[torch.Tensor] = None, prompt_tokens: Optional[torch.Tensor] = None,
                     workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None
                     ) -> Tuple[torch.Tensor, Optional[torch.Tensor], Optional[torch.Tensor]]:
     """sip_sample_call of include/sip.h: logits as one matrix (``logits``, ``V``) or as pieces
@@ -503,6 +505,10 @@ def sip_sample_call(*, logits: Optional[torch.Tensor] = None, shards=None, V: Op
         if hist_indptr.dtype != torch.int64 or hist_tokens.dtype != torch.int32 or hist_indptr.numel() != B + 1:
             raise TypeError("hist_indptr must be int64 with B + 1 entries and hist_tokens int32")
         c.hist_indptr, c.hist_tokens, c.hist_nnz = _ptr(hist_indptr), _ptr(hist_tokens), hist_tokens.numel()
+    if prompt_indptr is not None and prompt_tokens is not None and prompt_tokens.numel():
+        if prompt_indptr.dtype != torch.int64 or prompt_tokens.dtype != torch.int32 or prompt_indptr.numel() != B + 1:
+            raise TypeError("prompt_indptr must be int64 with B + 1 entries and prompt_tokens int32")
+        c.prompt_indptr, c.prompt_tokens, c.prompt_nnz = _ptr(prompt_indptr), _ptr(prompt_tokens), prompt_tokens.numel()
     c.seed, c.step, c.k_logprobs = seed, step, k_logprobs
     if out_ids is None:
         out_ids = torch.empty(B, dtype=torch.int32, device=dev)

@@ -162,6 +162,9 @@ struct HistSource {
   const int64_t* indptr = nullptr;
   const int32_t* tokens = nullptr;
   int64_t nnz = 0;                                   // entries the side tables of the workspace are sized for
+  const int64_t* p_indptr = nullptr;                 // separate prompt tokens (CSR), or none
+  const int32_t* p_tokens = nullptr;
+  int64_t p_nnz = 0;
   const int32_t* slot = nullptr;
   sip::StateView state{};                            // valid when slot != nullptr
   int L_max = 0, slots = 0;
@@ -183,7 +186,7 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
                        const sip_params* params, const HistSource& h, uint64_t seed, uint64_t step,
                        int32_t* out_ids, int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs, void* workspace,
                        size_t workspace_bytes, hipStream_t stream, const ShardSource& sh = ShardSource{}) {
-  if (!shape_ok(B, V, (int)dtype, h.nnz, k_logprobs)) return SIP_ERR_INVALID_ARG;
+  if (!shape_ok(B, V, (int)dtype, h.nnz, k_logprobs) || h.p_nnz < 0) return SIP_ERR_INVALID_ARG;
   if (!out_ids) return SIP_ERR_INVALID_ARG;
   if ((k_logprobs >= 0) != (out_lp_ids != nullptr) || (k_logprobs >= 0) != (out_lp != nullptr))
     return SIP_ERR_INVALID_ARG;
@@ -200,7 +203,7 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
   }
   if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return SIP_ERR_UNSUPPORTED;
   const Plan plan = make_plan(B, V, (int)dtype, sh.t);
-  const Layout lay = make_layout(B, plan, h.nnz, sh.t ? (size_t)V * esz : 0);
+  const Layout lay = make_layout(B, plan, h.nnz + h.p_nnz, sh.t ? (size_t)V * esz : 0);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 || workspace_bytes < lay.total)
     return SIP_ERR_WORKSPACE;
 
@@ -228,6 +231,9 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
   a.indptr = reinterpret_cast<const long long*>(h.indptr);
   a.tokens = h.tokens;
   a.nnz = h.slot ? (long long)h.slots * h.L_max : ((h.indptr && h.tokens) ? h.nnz : 0);
+  a.p_indptr = reinterpret_cast<const long long*>(h.p_indptr);
+  a.p_tokens = h.p_tokens;
+  a.p_nnz = (h.p_indptr && h.p_tokens) ? h.p_nnz : 0;
   a.slot = h.slot; a.L_max = h.L_max; a.slots = h.slots;
   a.st_len = h.state.len; a.st_ndist = h.state.ndist; a.st_tokens = h.state.tokens; a.st_table = h.state.table;
   a.st_tick = h.slot ? &h.state.head->tick : nullptr;
@@ -441,6 +447,9 @@ sip_status call_sources(const sip_call* c, HistSource& h, ShardSource& sh, int32
     if (c->hist_nnz < 0 || (c->hist_nnz > 0 && (!c->hist_indptr || !c->hist_tokens))) return SIP_ERR_INVALID_ARG;
     h.indptr = c->hist_indptr; h.tokens = c->hist_tokens; h.nnz = c->hist_nnz;
   }
+  if (c->prompt_nnz < 0 || (c->prompt_nnz > 0 && (!c->prompt_indptr || !c->prompt_tokens))) return SIP_ERR_INVALID_ARG;
+  if (c->prompt_nnz > 0 && c->state) return SIP_ERR_INVALID_ARG;      // a state's slots hold prompt and output as one history
+  h.p_indptr = c->prompt_indptr; h.p_tokens = c->prompt_tokens; h.p_nnz = c->prompt_nnz;
   if ((c->host_ids != nullptr) != (c->host_flag != nullptr)) return SIP_ERR_INVALID_ARG;
   if (c->host_flag && ((reinterpret_cast<uintptr_t>(c->host_flag) & 7u) != 0 ||
                        (reinterpret_cast<uintptr_t>(c->host_ids) & 3u) != 0))
@@ -455,7 +464,7 @@ size_t sip_call_workspace_bytes(const sip_call* c) {
   if (!shape_ok(c->B, V, (int)c->dtype, h.nnz, c->k_logprobs)) return 0;
   if (V > SIP_MAX_V || c->k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
   const size_t esz = c->dtype == SIP_F32 ? 4 : 2;
-  return make_layout(c->B, make_plan(c->B, V, (int)c->dtype, sh.t), h.nnz, sh.t ? (size_t)V * esz : 0).total;
+  return make_layout(c->B, make_plan(c->B, V, (int)c->dtype, sh.t), h.nnz + h.p_nnz, sh.t ? (size_t)V * esz : 0).total;
 }
 
 sip_status sip_sample_call(const sip_call* c) {

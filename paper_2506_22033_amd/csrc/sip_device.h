@@ -14,6 +14,7 @@ constexpr float kFixScale = 1099511627776.0f;   // 2^40
 // Bit 31 of a list entry's index: the token occurs in the row's history and the row has a penalty
 // switched on, so the entry's value is the raw logit that the penalty still has to be applied to.
 constexpr uint32_t kTagBit = 0x80000000u;
+constexpr int kPromptFlag = 1 << 30;             // RowInfo::target: tokens of a separate prompt are tagged too
 constexpr uint32_t kCntOverflow = 0xFFFFFFFFu;   // ChunkOut::cnt of a chunk whose queue overflowed
 
 // What the streaming workgroup of one chunk leaves behind.  Its list (the chunk's segment in
@@ -49,6 +50,10 @@ struct Args {
   const long long* indptr;
   const int* tokens;
   long long nnz;
+  // separate prompt tokens (CSR; nullptr = none): the repetition penalty looks at them too
+  const long long* p_indptr;
+  const int* p_tokens;
+  long long p_nnz;
   unsigned long long seed, step;
   int* out_ids;
   int* out_lp_ids;
@@ -115,6 +120,35 @@ __device__ __forceinline__ HistRange hist_range(const Args& a, int b) {
     h.side = h.lo;
   }
   return h;
+}
+// Which tokens of row b carry a penalty and what has to be known about them (Sec. 2.1 step 3 (1);
+// Sec. 5.1 CalcPenalty): the row's history (the generated tokens: all three penalties) and,
+// if the caller hands them in separately, its prompt tokens (repetition penalty only).
+struct PenaltyPlan {
+  HistRange h;
+  long long p_lo, p_hi;   // extent of the prompt in a.p_tokens; empty unless the repetition penalty is on
+  long long side;         // where the row's part of the exact path's side tables starts
+  bool any;               // some token of the row carries a penalty
+  bool prompt_on;
+  bool counts;            // the tokens' multiplicities in the history are needed ...
+  unsigned int dflt;      // ... otherwise every penalised token is taken to occur this often in it
+};
+__device__ __forceinline__ PenaltyPlan penalty_plan(const Args& a, int b, float theta, float phi, float psi) {
+  PenaltyPlan q;
+  q.h = hist_range(a, b);
+  q.p_lo = q.p_hi = 0;
+  if (a.p_indptr && a.p_tokens && a.p_nnz > 0 && theta != 1.0f) {
+    q.p_lo = a.p_indptr[b]; q.p_hi = a.p_indptr[b + 1];
+    q.p_lo = q.p_lo < 0 ? 0 : (q.p_lo > a.p_nnz ? a.p_nnz : q.p_lo);
+    q.p_hi = q.p_hi < q.p_lo ? q.p_lo : (q.p_hi > a.p_nnz ? a.p_nnz : q.p_hi);
+  }
+  const bool hist = q.h.hi > q.h.lo;
+  q.prompt_on = q.p_hi > q.p_lo;
+  q.any = (hist && (theta != 1.0f || phi != 0.0f || psi != 0.0f)) || q.prompt_on;
+  q.counts = hist && (phi != 0.0f || (q.prompt_on && psi != 0.0f));
+  q.dflt = hist ? 1u : 0u;
+  q.side = q.h.side + q.p_lo;
+  return q;
 }
 // Base of shard `sh` (uniform or per lane): a chain of selects, because the table lives in the
 // kernel-argument segment and must be indexed with constants.
@@ -242,11 +276,15 @@ __host__ __device__ inline int chunk_begin(int ch, int V, int S, int unit) {
 }
 
 // ApplyPenalty for one seen token: repetition, then frequency, then presence, one fp32
-// rounding per operation (Sec. 2.1 step 3 (1); Sec. 5.1).
+// rounding per operation (Sec. 2.1 step 3 (1); Sec. 5.1).  `count`: occurrences among the
+// generated tokens; 0 = the token is in the separately given prompt only, which the frequency
+// and presence penalties do not look at.
 __device__ __forceinline__ float penalise(float z, unsigned int count, float theta, float phi, float psi) {
   if (theta != 1.0f) z = (z > 0.0f) ? __fdiv_rn(z, theta) : __fmul_rn(z, theta);
-  if (phi != 0.0f) z = __fsub_rn(z, __fmul_rn(phi, (float)count));
-  if (psi != 0.0f) z = __fsub_rn(z, psi);
+  if (count != 0u) {
+    if (phi != 0.0f) z = __fsub_rn(z, __fmul_rn(phi, (float)count));
+    if (psi != 0.0f) z = __fsub_rn(z, psi);
+  }
   return z;
 }
 

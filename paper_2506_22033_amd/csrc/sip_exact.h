@@ -356,17 +356,21 @@ __device__ __attribute__((noinline)) void exact_row(const Args& a, const int b, 
   r.greedy = (r.tau == 0.0f) || (top_k == 1);
 
   // ---- (1) history -> bitmap, ranks, multiplicities, penalised values  (Sec. 5.1 CalcPenalty)
-  const HistRange hr = hist_range(a, b);
-  const long long lo = hr.lo, hi = hr.hi;
-  r.has_pen = (hi > lo) && (theta != 1.0f || phi != 0.0f || psi != 0.0f);
-  r.side_z = a.side_z + hr.side;
+  const PenaltyPlan pen = penalty_plan(a, b, theta, phi, psi);
+  const long long lo = pen.h.lo, hi = pen.h.hi;
+  r.has_pen = pen.any;
+  r.side_z = a.side_z + pen.side;
   if (r.has_pen) {
-    float* side_z = a.side_z + hr.side;
-    unsigned int* side_c = a.side_c + hr.side;
+    float* side_z = a.side_z + pen.side;
+    unsigned int* side_c = a.side_c + pen.side;
     for (int w = tid; w < W; w += (int)blockDim.x) bm[w] = 0;
     __syncthreads();
     for (long long i = lo + tid; i < hi; i += (int)blockDim.x) {
       const int t = a.tokens[i];
+      if (t >= 0 && t < V) atomicOr(&bm[t >> 5], 1u << (t & 31));
+    }
+    for (long long i = pen.p_lo + tid; i < pen.p_hi; i += (int)blockDim.x) {     // a separate prompt: presence only
+      const int t = a.p_tokens[i];
       if (t >= 0 && t < V) atomicOr(&bm[t >> 5], 1u << (t & 31));
     }
     __syncthreads();
@@ -378,7 +382,7 @@ __device__ __attribute__((noinline)) void exact_row(const Args& a, const int b, 
     uint32_t run = block_excl_scan_u32(local, sh, ndist);
     for (int w = w0; w < w1; ++w) { pre[w] = run; run += __popc(bm[w]); }
     __syncthreads();
-    const bool need_counts = (phi != 0.0f);
+    const bool need_counts = pen.counts;
     if (need_counts) {
       for (uint32_t i = tid; i < ndist; i += (int)blockDim.x) side_c[i] = 0;
       __threadfence();
@@ -405,7 +409,7 @@ __device__ __attribute__((noinline)) void exact_row(const Args& a, const int b, 
         const int v = (w << 5) + __ffs((int)bits) - 1;
         bits &= bits - 1;
         const float z = load_one<DT>(raw, v);
-        unsigned int c = 1;
+        unsigned int c = pen.dflt;
         if (need_counts) c = __hip_atomic_load(&side_c[rank], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         side_z[rank] = penalise(z, c, theta, phi, psi);
         ++rank;

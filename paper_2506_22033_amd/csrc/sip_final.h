@@ -121,9 +121,9 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
   auto scaled_s = [&](float z) { return rp.greedy ? z : __fdiv_rn(z, rp.tau); };
 
   // ---- (0) chunk summaries, history extent; clear the LDS tables meanwhile
-  const HistRange hr = hist_range(a, b);
-  const long long lo = hr.lo, hi = hr.hi;
-  const bool has_pen = (hi > lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
+  const PenaltyPlan pen = penalty_plan(a, b, rp.theta, rp.phi, rp.psi);
+  const long long lo = pen.h.lo, hi = pen.h.hi;
+  const bool has_pen = pen.any;
   const int nseg = S;                                       // one list segment per chunk
   if (tid == 0) {
     fs.fail_seg = 0; fs.anyc = 0; fs.dropped = 0;
@@ -183,6 +183,10 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     }
     for (long long i = lo + tid + (long long)kTokRegs * NT; i < hi; i += NT) {
       const int t = a.tokens[i];
+      if (t >= 0 && t < V) atomicOr(&bm[t >> 5], 1u << (t & 31));
+    }
+    for (long long i = pen.p_lo + tid; i < pen.p_hi; i += NT) {             // a separate prompt: presence only
+      const int t = a.p_tokens[i];
       if (t >= 0 && t < V) atomicOr(&bm[t >> 5], 1u << (t & 31));
     }
   }
@@ -298,7 +302,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
       }
     }
   // ---- (3) multiplicities of the history tokens
-  if (has_pen && rp.phi != 0.0f) {
+  if (has_pen && pen.counts) {
     auto count = [&](int t) {
       if (t >= 0 && t < V) {
         const uint32_t word = bm[t >> 5];
@@ -350,7 +354,7 @@ __device__ __forceinline__ int fast_row(const Args& a, const int b, const RowPar
     uint32_t mult[SR];
 #pragma unroll
     for (int r = 0; r < SR; ++r)
-      if ((uint32_t)(r * NT) < ndist) mult[r] = cnt[r * NT + tid];             // uniform
+      if ((uint32_t)(r * NT) < ndist) mult[r] = pen.counts ? cnt[r * NT + tid] : pen.dflt;   // uniform
 #pragma unroll
     for (int r = 0; r < SR; ++r) {
       if ((uint32_t)(r * NT) < ndist && idx[CR + r] != kNoIdx)
@@ -924,8 +928,9 @@ __global__ __launch_bounds__(kFinalThreads) void rescue_kernel(Args a_by_value) 
     // Upper bound on the row's distinct history tokens, which decides the instantiation that is
     // tried first: the history's length, or what a device-resident state remembers from the
     // slot's previous call.
-    const HistRange hr = hist_range(a, b);
-    long long ndist_ub = hr.hi - hr.lo;
+    const PenaltyPlan pen0 = penalty_plan(a, b, rp.theta, rp.phi, rp.psi);
+    const HistRange hr = pen0.h;
+    long long ndist_ub = (hr.hi - hr.lo) + (pen0.p_hi - pen0.p_lo);
     if (a.slot && hr.hi > hr.lo) {
       const int hint = a.st_ndist[a.slot[b]];
       if (hint >= 0 && hint < ndist_ub) ndist_ub = hint;
@@ -965,7 +970,7 @@ __global__ __launch_bounds__(kFinalThreads) void rescue_kernel(Args a_by_value) 
       if (!(t_new < t_old)) break;
       if (SH && !gathered) { gather_row<DT>(a, b); gathered = true; }
       {
-        const bool has_pen = (hr.hi > hr.lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
+        const bool has_pen = penalty_plan(a, b, rp.theta, rp.phi, rp.psi).any;
         restream_row<DT>(a, b, rp, t_new, fs, has_pen ? reinterpret_cast<const uint32_t*>(dynraw) : nullptr);
       }
       if (cut_below && fs.rq_n > (uint32_t)(kFinalThreads * kCandLong)) {

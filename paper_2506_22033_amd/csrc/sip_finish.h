@@ -124,15 +124,18 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
     Tc = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(co.Tc)));   // the chunks of a row share
     R = __builtin_amdgcn_readfirstlane(co.R);                                                      // threshold and exponent
   }
-  if (ri.target == 0) return 2;                                              // uniform: k beyond any list
+  if ((ri.target & ~kPromptFlag) == 0) return 2;                             // uniform: k beyond any list
+  const bool prompt_on = (ri.target & kPromptFlag) != 0;                     // tokens of a separate prompt are tagged too
   RowParams rp;
   rp.tau = ri.tau; rp.top_p = ri.top_p; rp.min_p = ri.min_p; rp.theta = ri.theta; rp.phi = ri.phi; rp.psi = ri.psi;
   rp.top_k = ri.top_k; rp.row_id = ri.row_id;
   rp.greedy = (rp.tau == 0.0f) || (rp.top_k == 1);
   auto scaled_s = [&](float z) { return rp.greedy ? z : __fdiv_rn(z, rp.tau); };
   const long long h_lo = ri.lo, h_hi = ri.hi;
-  const bool has_pen = (h_hi > h_lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);
-  const bool need_hash = has_pen && rp.phi != 0.0f;
+  // multiplicities in the history are needed for the frequency penalty, and, next to a separate
+  // prompt, to tell the tokens that frequency and presence apply to (see penalty_plan())
+  const bool need_hash = (h_hi > h_lo) && (rp.phi != 0.0f || (prompt_on && rp.psi != 0.0f));
+  const uint32_t mult_dflt = (h_hi > h_lo) ? 1u : 0u;
   // a device-resident state keeps the row's table of multiplicities: copy it instead of counting
   // (32 KB to copy against 4 bytes and two LDS atomics per history token: it pays from about two
   // thousand tokens on)
@@ -247,17 +250,19 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
     for (int w = 0; w < kFinWaves; ++w) ndist += fs.r32[w];
     if (fs.hash_fail || ndist > (uint32_t)kFinHashMax) return 4;            // uniform
   }
-  // slot of token t, searched from bucket bk on (the rare continuation of the lookup below)
-  auto slot_slow = [&](uint32_t t, uint32_t bk) -> uint32_t {
+  // multiplicity of token t, searched from bucket bk on (the rare continuation of the lookup
+  // below: t's home bucket is full of other tokens); 0 = not in the history (a prompt token)
+  auto count_slow = [&](uint32_t t, uint32_t bk) -> uint32_t {
     for (int probe = 0; probe < kFinHash / 4; ++probe) {
       const uint4 k4 = hkey4[bk];
-      if (k4.x == t) return 4 * bk;
-      if (k4.y == t) return 4 * bk + 1;
-      if (k4.z == t) return 4 * bk + 2;
-      if (k4.w == t) return 4 * bk + 3;
+      if (k4.x == t) return fs.u.hash.val[4 * bk];
+      if (k4.y == t) return fs.u.hash.val[4 * bk + 1];
+      if (k4.z == t) return fs.u.hash.val[4 * bk + 2];
+      if (k4.w == t) return fs.u.hash.val[4 * bk + 3];
+      if (k4.w == kFinNone) return 0u;     // slots fill in order: a free last slot ends the search
       bk = (bk + 1) & (kFinHash / 4 - 1);
     }
-    return 0u;                             // not reached: every tagged token is in the history
+    return 0u;
   };
 
   // ---- (2) penalised values (Sec. 5.1 ApplyPenalty); maximum of the list, lowest index on ties
@@ -272,18 +277,15 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
 #pragma unroll
       for (int r = 0; r < CR; ++r)
         if (live(bt, r)) hk[r] = hkey4[home(creg[r].y & ~kTagBit)];
-      uint32_t hs[CR];
 #pragma unroll
       for (int r = 0; r < CR; ++r) {
-        hs[r] = 0u;
+        hv[r] = 0u;
         if (!live(bt, r)) continue;
         const uint32_t v = creg[r].y & ~kTagBit, bk = home(v);
-        hs[r] = hk[r].x == v ? 4 * bk : hk[r].y == v ? 4 * bk + 1 : hk[r].z == v ? 4 * bk + 2 : hk[r].w == v ? 4 * bk + 3 : kFinNone;
-        if (hs[r] == kFinNone) hs[r] = ((creg[r].y & kTagBit) && creg[r].y != kFinNone) ? slot_slow(v, (bk + 1) & (kFinHash / 4 - 1)) : 0u;
+        const uint32_t hs = hk[r].x == v ? 4 * bk : hk[r].y == v ? 4 * bk + 1 : hk[r].z == v ? 4 * bk + 2 : hk[r].w == v ? 4 * bk + 3 : kFinNone;
+        if (hs != kFinNone) hv[r] = fs.u.hash.val[hs];
+        else if (hk[r].w != kFinNone && (creg[r].y & kTagBit) && creg[r].y != kFinNone) hv[r] = count_slow(v, (bk + 1) & (kFinHash / 4 - 1));
       }
-#pragma unroll
-      for (int r = 0; r < CR; ++r)
-        if (live(bt, r)) hv[r] = fs.u.hash.val[hs[r]];
     }
 #pragma unroll
     for (int r = 0; r < CR; ++r) {
@@ -291,7 +293,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
         const uint32_t v = creg[r].y & ~kTagBit;
         float z = __uint_as_float(creg[r].x);
         if (creg[r].y & kTagBit) {
-          z = penalise(z, need_hash ? hv[r] : 1u, rp.theta, rp.phi, rp.psi);
+          z = penalise(z, need_hash ? hv[r] : mult_dflt, rp.theta, rp.phi, rp.psi);
           // lists of several batches are read again from memory: leave the penalised value there
           if (nb > 1) seg[slot_of(bt, r)] = make_uint2(__float_as_uint(z), v);
         }

@@ -259,14 +259,17 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
   }
   // ---- history bitmap of the chunk: bit (v - g0) for every history token v in [g0, g1), the
   // vocabulary ids this workgroup streams.  Requested here, entered after the first barrier.
-  const HistRange hr = hist_range(a, b);
-  const bool has_pen = (hr.hi > hr.lo) && (rp.theta != 1.0f || rp.phi != 0.0f || rp.psi != 0.0f);   // uniform
+  const PenaltyPlan pen = penalty_plan(a, b, rp.theta, rp.phi, rp.psi);
+  const HistRange hr = pen.h;
+  const bool has_pen = pen.any;                                                                       // uniform
+  const bool hist_pen = has_pen && hr.hi > hr.lo;
   const int g0 = (int)ibase + c0;
   const int g1 = (!SH || split) ? (int)ibase + c1 : (int)ibase + np * Vl;
   if (ch == 0 && tid == 0) {               // the row's record for the finishing kernel
     RowInfo ri;
     ri.tau = rp.tau; ri.top_p = rp.top_p; ri.min_p = rp.min_p; ri.theta = rp.theta; ri.phi = rp.phi; ri.psi = rp.psi;
-    ri.top_k = rp.top_k; ri.target = target; ri.row_id = rp.row_id; ri.lo = hr.lo; ri.hi = hr.hi;
+    ri.top_k = rp.top_k; ri.target = target | (pen.prompt_on ? kPromptFlag : 0);
+    ri.row_id = rp.row_id; ri.lo = hr.lo; ri.hi = hr.hi;
     ri.slot = -1; ri.ndist = -1;
     if (a.slot) {
       const int sl = a.slot[b];
@@ -278,7 +281,7 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
   for (int j = 0; j < kStreamHistRegs; ++j) {
     const long long i = hr.lo + tid + (long long)j * kStreamThreads;
-    htok[j] = (has_pen && i < hr.hi) ? a.tokens[i] : -1;
+    htok[j] = (hist_pen && i < hr.hi) ? a.tokens[i] : -1;
   }
   for (int i = tid; i < kSampleBins / 2; i += kStreamThreads) hist[i] = 0;
   for (int i = tid; i < kChunkBitsMax / 32; i += kStreamThreads) bmw[i] = 0;
@@ -301,6 +304,7 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
       for (int j = 0; j < kStreamHistRegs; ++j) mark(htok[j]);
     }
+    for (long long i = pen.p_lo + tid; i < pen.p_hi; i += kStreamThreads) mark(a.p_tokens[i]);   // separate prompt
   }
   // Only the upper tail of the sample matters.  When j is small, a thread enters just the
   // three largest of its values: far fewer LDS atomics, and hardly any on the same word.

@@ -120,3 +120,45 @@ def test_many_rows_many_paths_on_pieces_with_state():
         assert np.array_equal(tokens[s, :length[s]], ost.history(s))
     print(f"[call] many paths: {stats.rows} rows, paths {paths}, flagged={stats.flagged} mismatch={stats.flagged_mismatch}")
     assert len(set(paths) - {1}) >= 2, "the parameters were meant to send rows down several paths"
+
+
+@pytest.mark.parametrize("V,bf16", [(40000, False), (40000, True), (1000, False)])
+def test_separate_prompt_tokens_feed_the_repetition_penalty_only(V, bf16):
+    """sip_sample_call with the prompt handed in as a CSR of its own: repetition over prompt and
+    history, frequency and presence over the history alone; on the single-pass kernels and on the
+    exact path, with rows that have no history, no prompt, or a repetition penalty of 1."""
+    import workloads
+    from oracle import sip_oracle as O
+    rng = np.random.default_rng(V + bf16)
+    B = 12
+    z = (rng.standard_normal((B, V)) * 2.5).astype(np.float32)
+    hist = [rng.integers(0, V, int(n)).tolist() for n in rng.choice([0, 0, 40, 300], B)]
+    prompts = [rng.integers(0, V, int(n)).tolist() for n in rng.choice([0, 25, 500], B)]
+    for b in range(B):                                        # make prompt and history matter: their tokens lead the row
+        for t in (hist[b][-3:] + prompts[b][:3]):
+            z[b, t] += 7.0
+        if hist[b] and prompts[b]:
+            prompts[b][0] = hist[b][0]                        # a token in both
+    params = dict(temperature=rng.choice([0.0, 0.7, 1.0], B), top_k=rng.choice([0, 30], B),
+                  top_p=rng.choice([1.0, 0.9], B), min_p=rng.choice([0.0, 0.05], B),
+                  repetition_penalty=rng.choice([1.0, 1.3, 0.8], B), frequency_penalty=rng.choice([0.0, 0.4], B),
+                  presence_penalty=rng.choice([0.0, 0.5], B))
+    logits = workloads.f32_to_bf16_bits(z) if bf16 else z
+    w = H.custom("prompt", logits, params, hist, k_logprobs=4)
+    d = H.to_device(w)
+    p_indptr = np.concatenate(([0], np.cumsum([len(p) for p in prompts]))).astype(np.int64)
+    p_tokens = np.array([t for p in prompts for t in p], dtype=np.int32)
+    for step in (0, 1):
+        ids, lp_ids, lp = sip.sip_sample_call(logits=d.logits, V=V, params=d.params, hist_indptr=d.indptr,
+                                              hist_tokens=d.tokens, seed=3, step=step, k_logprobs=4,
+                                              prompt_indptr=torch.from_numpy(p_indptr).to(H.DEV),
+                                              prompt_tokens=torch.from_numpy(p_tokens).to(H.DEV))
+        torch.cuda.synchronize()
+        ref = O.sample_batch(w.logits, w.params, w.hist_indptr, w.hist_tokens, 3, step, 4,
+                             prompt_indptr=p_indptr, prompt_tokens=p_tokens)
+        st = H.check_rows(f"prompt V={V} step {step}", range(B), ref, (ids.cpu().numpy(), lp_ids.cpu().numpy(), lp.cpu().numpy()), 4)
+        assert st.rows == B
+    # and the prompt does change the result: without it some row differs
+    ref0 = O.sample_batch(w.logits, w.params, w.hist_indptr, w.hist_tokens, 3, 0, 4)
+    ref1 = O.sample_batch(w.logits, w.params, w.hist_indptr, w.hist_tokens, 3, 0, 4, prompt_indptr=p_indptr, prompt_tokens=p_tokens)
+    assert any(abs(a.logprob - c.logprob) > 1e-3 for a, c in zip(ref0, ref1))
