@@ -15,6 +15,7 @@
 #include "sip_exact.h"
 #include "sip_final.h"
 #include "sip_finish.h"
+#include "sip_fused.h"
 #include "sip_handoff.h"
 #include "sip_state.h"
 #include "sip_stream.h"
@@ -103,6 +104,7 @@ static __device__ __align__(256) unsigned char scratch[kNoallocBytes];
 struct DeviceSetup {
   std::atomic<int> state{0};                // 0: not done, 1: done
   void* scratch_ptr = nullptr;
+  int compute_units = 0;
 };
 DeviceSetup g_dev[kMaxDevices];
 std::mutex g_dev_mutex;
@@ -128,6 +130,10 @@ DeviceSetup* device_setup() {
   void* p = nullptr;
   if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return nullptr; }
   d.scratch_ptr = p;
+  if (hipDeviceGetAttribute(&d.compute_units, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    d.compute_units = 0;
+  }
   d.state.store(1, std::memory_order_release);
   return &d;
 }
@@ -264,7 +270,8 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
 template <bool SH>
 sip_status launch(const sip::Args& a_in, int32_t B, int dtype, const Plan& plan, bool state, sip::StateHeader* head,
                   hipStream_t stream) {
-  if (!device_setup()) return SIP_ERR_HIP;
+  const DeviceSetup* dev = device_setup();
+  if (!dev) return SIP_ERR_HIP;
   sip::Args a = a_in;
   const size_t words = ((size_t)a.V + 31) / 32;
   if (!plan.fast) {
@@ -286,17 +293,33 @@ sip_status launch(const sip::Args& a_in, int32_t B, int dtype, const Plan& plan,
   hipEvent_t ev[6];
   for (int i = 0; i < 6; ++i) { ev[i] = g_prof[i]; g_prof[i] = nullptr; }
   const bool timed = ev[0] || ev[1] || ev[2] || ev[3] || ev[4] || ev[5];
-  // three launches: the pass over the logits; one workgroup per row on what it left; and a small
-  // fixed grid for the rows (normally none) that need more than that
-  const int n_rescue_wg = std::min<int>(B, kRescueGrid);
-  if (timed) {               // the events take the dispatches' own begin / end time stamps
-    hipExtLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, ev[0], ev[1], 0, a);
-    hipExtLaunchKernelGGL(sip::finish_kernel, dim3(B), dim3(sip::kFinThreads), 0, stream, ev[2], ev[3], 0, a);
-    hipExtLaunchKernelGGL(k_rescue, dim3(n_rescue_wg), dim3(sip::kFinalThreads), dyn, stream, ev[4], ev[5], 0, a);
+  // The pass over the logits, then one workgroup per row on what it left.  A batch of no more rows
+  // than the device has compute units: the workgroup also takes its row through the heavier logic
+  // if the list does not settle it (sip_fused.h).  Larger batches: the lean finishing kernel, two
+  // workgroups per compute unit, and a small fixed grid behind it for the rows (normally none) that
+  // need more.
+  const bool fused = B <= dev->compute_units && (size_t)plan.final_lds <= sip::kFusedRawBytes &&
+                     2 * words * sizeof(uint32_t) <= sip::kFusedRawBytes;
+  if (timed) hipExtLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, ev[0], ev[1], 0, a);
+  else hipLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, a);
+  if (fused) {
+    auto k_fused = dtype == SIP_F32 ? sip::finish_rescue_kernel<SIP_F32, SH> : sip::finish_rescue_kernel<SIP_BF16, SH>;
+    if (timed) {             // the events take the dispatches' own begin / end time stamps
+      hipExtLaunchKernelGGL(k_fused, dim3(B), dim3(sip::kFinalThreads), 0, stream, ev[2], ev[3], 0, a);
+      if (ev[4]) (void)hipEventRecord(ev[4], stream);       // no third kernel: an empty interval
+      if (ev[5]) (void)hipEventRecord(ev[5], stream);
+    } else {
+      hipLaunchKernelGGL(k_fused, dim3(B), dim3(sip::kFinalThreads), 0, stream, a);
+    }
   } else {
-    hipLaunchKernelGGL(k_stream, dim3(B * plan.S), dim3(sip::kStreamThreads), 0, stream, a);
-    hipLaunchKernelGGL(sip::finish_kernel, dim3(B), dim3(sip::kFinThreads), 0, stream, a);
-    hipLaunchKernelGGL(k_rescue, dim3(n_rescue_wg), dim3(sip::kFinalThreads), dyn, stream, a);
+    const int n_rescue_wg = std::min<int>(B, kRescueGrid);
+    if (timed) {
+      hipExtLaunchKernelGGL(sip::finish_kernel, dim3(B), dim3(sip::kFinThreads), 0, stream, ev[2], ev[3], 0, a);
+      hipExtLaunchKernelGGL(k_rescue, dim3(n_rescue_wg), dim3(sip::kFinalThreads), dyn, stream, ev[4], ev[5], 0, a);
+    } else {
+      hipLaunchKernelGGL(sip::finish_kernel, dim3(B), dim3(sip::kFinThreads), 0, stream, a);
+      hipLaunchKernelGGL(k_rescue, dim3(n_rescue_wg), dim3(sip::kFinalThreads), dyn, stream, a);
+    }
   }
   if (hipGetLastError() != hipSuccess) return SIP_ERR_HIP;
   return SIP_OK;

@@ -137,17 +137,20 @@ __device__ __forceinline__ PenaltyPlan penalty_plan(const Args& a, int b, float 
   PenaltyPlan q;
   q.h = hist_range(a, b);
   q.p_lo = q.p_hi = 0;
-  if (a.p_indptr && a.p_tokens && a.p_nnz > 0 && theta != 1.0f) {
-    q.p_lo = a.p_indptr[b]; q.p_hi = a.p_indptr[b + 1];
-    q.p_lo = q.p_lo < 0 ? 0 : (q.p_lo > a.p_nnz ? a.p_nnz : q.p_lo);
-    q.p_hi = q.p_hi < q.p_lo ? q.p_lo : (q.p_hi > a.p_nnz ? a.p_nnz : q.p_hi);
+  long long p_before = 0;   // prompt tokens of the rows before this one: they shift the row's part of the side tables
+  if (a.p_indptr && a.p_tokens && a.p_nnz > 0) {
+    long long p0 = a.p_indptr[b], p1 = a.p_indptr[b + 1];
+    p0 = p0 < 0 ? 0 : (p0 > a.p_nnz ? a.p_nnz : p0);
+    p1 = p1 < p0 ? p0 : (p1 > a.p_nnz ? a.p_nnz : p1);
+    p_before = p0;
+    if (theta != 1.0f) { q.p_lo = p0; q.p_hi = p1; }
   }
   const bool hist = q.h.hi > q.h.lo;
   q.prompt_on = q.p_hi > q.p_lo;
   q.any = (hist && (theta != 1.0f || phi != 0.0f || psi != 0.0f)) || q.prompt_on;
   q.counts = hist && (phi != 0.0f || (q.prompt_on && psi != 0.0f));
   q.dflt = hist ? 1u : 0u;
-  q.side = q.h.side + q.p_lo;
+  q.side = q.h.side + p_before;
   return q;
 }
 // Base of shard `sh` (uniform or per lane): a chain of selects, because the table lives in the

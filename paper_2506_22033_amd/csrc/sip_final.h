@@ -899,26 +899,13 @@ __device__ __forceinline__ int fast_any(const Args& a, const int b, const RowPar
   return (r == kNeedLong || r == kNeedLongList) ? 5 : r;
 }
 
-// The rows that finish_kernel could not settle from their list (it leaves their numbers in
-// Args::rescue_rows): each is taken through the heavier logic below -- the same list in larger
-// register variants, a second and longer list, the continuations over the whole row, the exact
-// multi-pass path -- by one workgroup.  Launched with a fixed, small grid after every
-// finish_kernel; with nothing to rescue a workgroup reads the count and returns.
+// One row that the finishing logic could not settle from its list is taken through the heavier
+// logic below -- the same list in larger register variants, a second and longer list, the
+// continuations over the whole row, the exact multi-pass path -- by the calling workgroup.
+// `dynraw`: final_lds_fixed(V) (and at least 2 * ceil(V / 32) words) of LDS.
 template <int DT, bool SH>
-__global__ __launch_bounds__(kFinalThreads) void rescue_kernel(Args a_by_value) {
-  // The arguments are read where they are used, straight from the kernel-argument segment
-  // (the struct is the only parameter, so it starts at offset 0), instead of being held in
-  // scalar registers from the first instruction on: there are more of them than registers.
-  (void)a_by_value;
-  const Args& a = *(const Args*)__builtin_amdgcn_kernarg_segment_ptr();
-  extern __shared__ __align__(16) unsigned char dynraw[];
-  __shared__ ExactShared ex;
-  __shared__ FastShared fs;
-  const int n_rescue = min(max(*a.rescue_n, 0), a.B);
-#pragma nounroll
-  for (int qi = blockIdx.x; qi < n_rescue; qi += gridDim.x) {
-  if (qi != (int)blockIdx.x) __syncthreads();      // the row before this one is done with the tables in LDS
-  const int b = min(max(a.rescue_rows[qi], 0), a.B - 1);
+__device__ __forceinline__ void rescue_row(const Args& a, const int b, unsigned char* dynraw, ExactShared& ex,
+                                           FastShared& fs) {
   const RowParams rp = load_row_params(a, b);
   int how = 2;                                   // 2: not eligible for the single-pass path
   int code = 0;
@@ -997,6 +984,26 @@ __global__ __launch_bounds__(kFinalThreads) void rescue_kernel(Args a_by_value) 
     __syncthreads();
     if (threadIdx.x == 0) state_append_row(a, b);
   }
+}
+
+// The rows that finish_kernel could not settle (it leaves their numbers in Args::rescue_rows),
+// one workgroup per row at a time.  Launched with a fixed, small grid after every finish_kernel;
+// with nothing to rescue a workgroup reads the count and returns.
+template <int DT, bool SH>
+__global__ __launch_bounds__(kFinalThreads) void rescue_kernel(Args a_by_value) {
+  // The arguments are read where they are used, straight from the kernel-argument segment
+  // (the struct is the only parameter, so it starts at offset 0), instead of being held in
+  // scalar registers from the first instruction on: there are more of them than registers.
+  (void)a_by_value;
+  const Args& a = *(const Args*)__builtin_amdgcn_kernarg_segment_ptr();
+  extern __shared__ __align__(16) unsigned char dynraw[];
+  __shared__ ExactShared ex;
+  __shared__ FastShared fs;
+  const int n_rescue = min(max(*a.rescue_n, 0), a.B);
+#pragma nounroll
+  for (int qi = blockIdx.x; qi < n_rescue; qi += gridDim.x) {
+    if (qi != (int)blockIdx.x) __syncthreads();    // the row before this one is done with the tables in LDS
+    rescue_row<DT, SH>(a, min(max(a.rescue_rows[qi], 0), a.B - 1), dynraw, ex, fs);
   }
 }
 

@@ -61,6 +61,21 @@ def test_second_attempt_with_a_lower_threshold():
     assert st.rows == 36                                   # ... and every row matched the oracle
 
 
+def test_batches_of_more_rows_than_compute_units_queue_their_hard_rows():
+    """Up to one row per compute unit a workgroup takes its row through the heavier logic itself;
+    beyond that the rows that need it are queued for a kernel of their own.  The same twelve hard
+    rows as above, 25 times over (300 rows), must match the oracle on that route as well."""
+    rng = np.random.default_rng(1)
+    V, B0, rep = 33000, 12, 25
+    z0 = (rng.standard_normal((B0, V)) * 2.0).astype(np.float32)
+    hist0 = [[] for _ in range(6)] + [np.argsort(-z0[b])[:400].tolist() for b in range(6, 12)]
+    params = dict(temperature=([1.0] * 6 + [0.8] * 6) * rep, top_p=([0.9] * 3 + [1.0] * 9) * rep,
+                  min_p=([0.0] * 6 + [0.05] * 6) * rep, presence_penalty=([0.0] * 6 + [6.0] * 6) * rep)
+    st, paths = _check(H.custom("queued", np.tile(z0, (rep, 1)), params, hist0 * rep, k_logprobs=5), steps=(1,))
+    assert st.rows == B0 * rep
+    assert (paths == 15).any() and (paths == 16).any() and (paths == 1).any(), np.unique(paths, return_counts=True)
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_nucleus_that_reaches_far_below_the_candidate_list(bf16):
     """top-p alone on flat and on hot distributions keeps tens of thousands of tokens: the cut is
