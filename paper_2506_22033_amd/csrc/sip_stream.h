@@ -432,14 +432,17 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     float g = 0.0f;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
-      const uint32_t tag = (hb >> i) & 1u;
-      const bool hit = (z[i] >= Tc) | (tag != 0u);
+      // One comparison decides "at or above the threshold, or a history token": the history bit,
+      // spread over the word, is or-ed into the value's bits, which turns a tagged value into a
+      // NaN, and "not below" holds for every NaN.
+      const uint32_t tagm = (uint32_t)((int)(hb << (31 - i)) >> 31);          // 0 or all ones
+      const bool hit = !(__uint_as_float(__float_as_uint(z[i]) | tagm) < Tc);
       const unsigned long long mask = __ballot(hit);
       if (mask) {
         const uint32_t pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
                                       __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
         if (hit && pos < (uint32_t)kQueueCap)
-          queue[pos] = make_uint2(__float_as_uint(z[i]), ((uint32_t)(e0 + i) + (SH ? ib : 0u)) | (tag << 31));
+          queue[pos] = make_uint2(__float_as_uint(z[i]), ((uint32_t)(e0 + i) + (SH ? ib : 0u)) | (tagm & kTagBit));
         qn += (uint32_t)__popcll(mask);
       }
       float e = bulk_term(z[i], ref);
