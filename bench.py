@@ -448,8 +448,13 @@ def main() -> int:
     alg = algorithmic_bytes(w)
     single_pass_rows = int((path == 1).sum())       # settled by the streaming + finishing kernels alone
     kernels = {}
-    if not bool((path == 14).all()):                # the library launched its three single-pass kernels
-        for name, (i0, i1) in (("stream_kernel", (0, 1)), ("finish_kernel", (2, 3)), ("rescue_kernel", (4, 5))):
+    if not bool((path == 14).all()):                # the library launched its single-pass kernels
+        # a batch of at most one row per compute unit is finished by one kernel (finish_rescue_kernel);
+        # a larger one by finish_kernel and, behind it, rescue_kernel (include/sip.h, "Kernels of a call")
+        one_kernel = w.B <= torch.cuda.get_device_properties(dev).multi_processor_count
+        names = (("stream_kernel", (0, 1)), ("finish_rescue_kernel", (2, 3))) if one_kernel else \
+                (("stream_kernel", (0, 1)), ("finish_kernel", (2, 3)), ("rescue_kernel", (4, 5)))
+        for name, (i0, i1) in names:
             kernels[name] = float(np.median([q[i0].elapsed_time(q[i1]) for q in marks[4:]]))
     dominant = max(kernels, key=kernels.get) if kernels else "exact_kernel"
     dom_ms = kernels.get(dominant, launch_ms)
@@ -486,7 +491,7 @@ def main() -> int:
         # uninstrumented loop.  Per-kernel figures (a separate, instrumented loop) are sub-keys.
         "roofline": {"bound": "hbm", "achieved": whole_call, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": whole_call / HBM_PEAK_GBS, "traffic": read_traffic(w.name),
-                     "kernel": "whole call: stream_kernel + finish_kernel + rescue_kernel",
+                     "kernel": "whole call: " + " + ".join(kernels) if kernels else "whole call: exact_kernel",
                      "call_ms_hip_events": launch_ms,
                      "algorithmic_bytes_per_call": alg,
                      "dominant_kernel": dominant,

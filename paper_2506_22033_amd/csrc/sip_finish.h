@@ -141,12 +141,6 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   // thousand tokens on)
   const bool use_table = need_hash && ri.slot >= 0 && ri.ndist >= 0 && ri.hi - ri.lo > 2048;
   static_assert(kFinHash == kTableSlots && kFinHashMax == kTableMaxDistinct, "one table geometry");
-  uint4 tq[2 * kFinHash * 4 / 16 / NT];
-  if (use_table) {
-    const uint4* t4 = reinterpret_cast<const uint4*>(a.st_table + (size_t)ri.slot * (size_t)(2 * kTableSlots));
-#pragma unroll
-    for (int j = 0; j < 2 * kFinHash * 4 / 16 / NT; ++j) tq[j] = t4[j * NT + tid];
-  }
   constexpr int HR = 8;                    // history tokens a thread requests at once
   int htok[HR];
 #pragma unroll
@@ -161,7 +155,11 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
     z4 = reinterpret_cast<uint4*>(fs.fill);
     for (int i = tid; i < kFinBins * 20 / 16; i += NT) z4[i] = make_uint4(0, 0, 0, 0);
     if (use_table) {                       // keys and multiplicities lie one behind the other, here as there
+      const uint4* t4 = reinterpret_cast<const uint4*>(a.st_table + (size_t)ri.slot * (size_t)(2 * kTableSlots));
       uint4* k4 = reinterpret_cast<uint4*>(fs.u.hash.key);
+      uint4 tq[2 * kFinHash * 4 / 16 / NT];
+#pragma unroll
+      for (int j = 0; j < 2 * kFinHash * 4 / 16 / NT; ++j) tq[j] = t4[j * NT + tid];
 #pragma unroll
       for (int j = 0; j < 2 * kFinHash * 4 / 16 / NT; ++j) k4[j * NT + tid] = tq[j];
     } else if (need_hash) {
