@@ -45,11 +45,25 @@ Plan make_plan(int32_t B, int32_t V, int dtype, int t = 0) {
   if (!p.fast) return p;
   const int tile = sip::kStreamThreads * sip::kStreamLoads * (dtype == SIP_F32 ? 4 : 8);
   const int n_tiles = (Vp + tile - 1) / tile * pieces;
-  // Chunks per row.  Small batches: as many workgroups as fit on the chip at once (4 per compute
-  // unit), so that there is a single, full round.  Large batches: 4, which makes many rounds
-  // and lets the per-wave candidate queues (kQueueCap each) add up to 16K entries per row.
+  // Chunks per row.  Up to 256 rows: as many workgroups as fit on the chip at once (4 per compute
+  // unit), so that there is a single, full round.  Larger batches run in rounds of that many
+  // workgroups, and every workgroup pays a fixed set-up (sample, threshold, history bitmap: about
+  // what streaming 38 elements per lane costs) before it streams its V / (S * 512) elements per
+  // lane: take the S with the cheapest rounds x (set-up + stream).
   constexpr int kResident = 256 * 4;
-  int want = B * 4 <= kResident ? kResident / B : (B * 2 <= kResident ? kResident / B : 4);
+  int want;
+  if (B * 4 <= kResident) {
+    want = kResident / B;
+  } else {
+    // (from 2 on: one chunk's queues alone are short for a long list plus a long history)
+    double best_cost = 0.0;
+    want = 2;
+    for (int S = 2; S <= sip::kMaxChunks; ++S) {
+      const double rounds = std::ceil((double)B * S / kResident);
+      const double cost = rounds * (38.0 + (double)V / (S * (double)sip::kStreamThreads));
+      if (S == 2 || cost < best_cost) { best_cost = cost; want = S; }
+    }
+  }
   want = std::max(1, std::min({want, sip::kMaxChunks, std::max(1, n_tiles / 2)}));
   if (want >= pieces) {
     want = want / pieces * pieces;                     // a chunk is part of one piece: a multiple of their number
@@ -79,7 +93,9 @@ Plan make_plan(int32_t B, int32_t V, int dtype, int t = 0) {
   }
   p.S = want;                                          // <= n_tiles / 2: every chunk holds at least two tiles
   p.cap_c = sip::kChunkCap;
-  p.nc_cap = sip::kFinalThreads * sip::kCandLong;     // the finishing kernel holds the list in registers
+  // the longest list a row may have: what the heavier per-row logic holds in registers, and what
+  // the row's chunks can hand over
+  p.nc_cap = std::min(sip::kFinalThreads * sip::kCandLong, p.S * sip::kChunkCap);
   p.final_lds = sip::final_lds_fixed(V);
   return p;
 }
