@@ -19,7 +19,11 @@
  *    out-of-bounds access: history offsets are clamped to [0, hist_nnz], token ids
  *    outside [0, V) are skipped.
  *  - Concurrent calls are allowed on different streams if they use different workspaces.
- *  - Same inputs, seed, step and row ids give the same output bits on every call.
+ *  - Same inputs, seed, step and row ids in a call of the same shape (B, V, dtype, sharding)
+ *    give the same output bits on every call.  In a call of another shape a row's partial sums
+ *    are grouped differently: its token id and best-n ids are still the same unless a decision
+ *    of the row lies within rounding of a boundary (a uniform within 1e-6 of a CDF edge), and
+ *    its log-probabilities agree within 1e-5 + 2^-22 * |logprob|.
  */
 #ifndef SIP_H_
 #define SIP_H_
@@ -75,15 +79,28 @@ typedef struct {
  * arguments; returns 0 for an invalid shape.  The workspace must be 256-byte aligned; its
  * contents need not be preserved between calls and need not be initialised.
  *
- * Diagnostic: after a call has completed, the first B int32 of the workspace say which
- * code path finished each row: 1 = the single-pass path (logits read once), any other value
- * = finished after reading the row again (normally from cache): 15 = the single-pass logic
- * on a second, longer candidate list (one more read of that row); 16 = by the row's workgroup
- * over the whole row (plain temperature sampling without any filter: two more reads; a
- * nucleus that reaches below the candidate list: four to six); anything else = the exact
- * multi-pass path, the value naming the reason (2 top_k too large for the candidate list,
- * 3-13 the candidate list could not prove the answer, 17-29 nor could the longer one,
- * 14 vocabulary size outside the single-pass kernels).  Results mean the same either way.
+ * Diagnostic: after a call has completed, the first 2 * B int32 of the workspace say, per row,
+ * which code path finished it (path[B]) and what the finishing kernel made of it (why[B]).
+ *   path: 1 = settled from the candidate list the one pass over the logits left behind; any
+ *   other value = finished after reading the row again (normally from cache): 15 = from a second,
+ *   longer candidate list (one more read of that row); 16 = by the row's workgroup over the whole
+ *   row (plain temperature sampling without any filter: two more reads; a nucleus that reaches
+ *   below the candidate list: four to six); anything else = the exact multi-pass path, the value
+ *   naming the reason (2 top_k too large for any candidate list, 3-13 the candidate list could
+ *   not prove the answer, 17-29 nor could the longer one, 14 vocabulary size outside the
+ *   single-pass kernels).
+ *   why: 1 = the finishing kernel settled the row; else why it passed the row on: 2 no list was
+ *   made, 3 a chunk's list overflowed, 4 more distinct history tokens than the table of
+ *   multiplicities holds, 5 list too long, 6 maximum not proven, 7 value span not representable,
+ *   8 k-th / n-th largest not in the list, 9 too many equal values in one bin, 10 top_p <= 0,
+ *   11 nucleus reaches below the list, 12 min-p cut below the list, 13 no filter at all,
+ *   14 no mass / exact-only shape.
+ * Results mean the same whichever path ran.
+ *
+ * Kernels of a call (names as a profiler shows them): stream_kernel (the one pass over the
+ * logits), then finish_rescue_kernel for batches of no more rows than the device has compute
+ * units, else finish_kernel followed by rescue_kernel (which returns at once when no row was
+ * passed on); exact_kernel alone for vocabulary sizes outside the single-pass kernels.
  */
 size_t sip_workspace_bytes(int32_t B, int32_t V, sip_dtype dtype, int64_t hist_nnz, int32_t k_logprobs);
 

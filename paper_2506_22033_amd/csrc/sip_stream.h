@@ -163,8 +163,9 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
   // Workgroups are handed to the 8 XCDs round-robin by their id.  The chunks of one row read
   // the same sample, so they are renumbered to land on the same XCD (and its L2): id i works
   // on logical chunk (i % 8) * (n / 8) + i / 8 when n, the grid size, is a multiple of 8.
-  // Device-resident history: this call is counted here, before the finishing kernel (which runs
-  // after this one and knows that it has been counted) reads the counter.
+  // Device-resident history: this call takes its number from the state's call counter here (one
+  // atomic add, so that calls in flight at once on one state each get their own) and leaves it in
+  // the workspace, where the kernels behind this one read it (step_of()).
   if (a.call_tick && blockIdx.x == 0 && tid == 0) *a.call_tick = atomicAdd(a.st_tick, 1ull);
   if (blockIdx.x == 0 && tid == 0) *a.rescue_n = 0;          // the finishing kernel counts from zero
   int wg = blockIdx.x;
