@@ -903,9 +903,32 @@ __device__ __forceinline__ int fast_any(const Args& a, const int b, const RowPar
 // logic below -- the same list in larger register variants, a second and longer list, the
 // continuations over the whole row, the exact multi-pass path -- by the calling workgroup.
 // `dynraw`: final_lds_fixed(V) (and at least 2 * ceil(V / 32) words) of LDS.
+// Bitmap over the vocabulary of the row's history (and prompt) tokens, as restream_row() wants it.
+__device__ __forceinline__ void history_bitmap(const Args& a, const int b, const PenaltyPlan& pen, uint32_t* bm) {
+  const int W = (a.V + 31) / 32, V = a.V;
+  for (int w = threadIdx.x; w < W; w += kFinalThreads) bm[w] = 0;
+  __syncthreads();
+  for (long long i = pen.h.lo + threadIdx.x; i < pen.h.hi; i += kFinalThreads) {
+    const int t = a.tokens[i];
+    if (t >= 0 && t < V) atomicOr(&bm[t >> 5], 1u << (t & 31));
+  }
+  for (long long i = pen.p_lo + threadIdx.x; i < pen.p_hi; i += kFinalThreads) {
+    const int t = a.p_tokens[i];
+    if (t >= 0 && t < V) atomicOr(&bm[t >> 5], 1u << (t & 31));
+  }
+  __syncthreads();
+}
+
+// `seen`: what a finishing attempt on the row's first list has already found out (finish_row()
+// in the same workgroup), or nothing.
+struct RescueSeen {
+  int why = 0;               // finish_row()'s code; 0 = nothing is known
+  bool retry_ok = false;
+  float m = 0.0f, zmax = 0.0f, T = 0.0f;
+};
 template <int DT, bool SH>
 __device__ __forceinline__ void rescue_row(const Args& a, const int b, unsigned char* dynraw, ExactShared& ex,
-                                           FastShared& fs) {
+                                           FastShared& fs, const RescueSeen seen = RescueSeen()) {
   const RowParams rp = load_row_params(a, b);
   int how = 2;                                   // 2: not eligible for the single-pass path
   int code = 0;
@@ -927,8 +950,18 @@ __device__ __forceinline__ void rescue_row(const Args& a, const int b, unsigned 
     int S = a.S, cap_c = a.cap_c;
 #pragma nounroll
     for (int attempt = 0; attempt < 2; ++attempt) {
-      int r = fast_any<DT, SH>(a, b, rp, dynraw, fs, S, cap_c, ndist_ub);
+      int r;
       bool cut_below = false;
+      const bool skipped = attempt == 0 && (seen.why == 12 || (seen.why == 11 && seen.retry_ok));
+      if (skipped) {
+        // The first list has been looked at already and is known to be too short for a cut whose
+        // place a second list can reach: go straight on to that one.
+        r = seen.why;
+        cut_below = seen.why == 11;
+        if (threadIdx.x == 0) { fs.m_out = seen.m; fs.zmax_out = seen.zmax; fs.trow_out = seen.T; }
+      } else {
+        r = fast_any<DT, SH>(a, b, rp, dynraw, fs, S, cap_c, ndist_ub);
+      }
       if (attempt == 0 && r == kWholeRowCut) {
         // a nucleus somewhat longer than the list is cheaper to settle from a second list than
         // over the whole row
@@ -956,16 +989,23 @@ __device__ __forceinline__ void rescue_row(const Args& a, const int b, unsigned 
       }
       if (!(t_new < t_old)) break;
       if (SH && !gathered) { gather_row<DT>(a, b); gathered = true; }
-      {
-        const bool has_pen = penalty_plan(a, b, rp.theta, rp.phi, rp.psi).any;
-        restream_row<DT>(a, b, rp, t_new, fs, has_pen ? reinterpret_cast<const uint32_t*>(dynraw) : nullptr);
-      }
+      const PenaltyPlan pen1 = penalty_plan(a, b, rp.theta, rp.phi, rp.psi);
+      const uint32_t* bm1 = pen1.any ? reinterpret_cast<const uint32_t*>(dynraw) : nullptr;
+      if (skipped && pen1.any) history_bitmap(a, b, pen1, reinterpret_cast<uint32_t*>(dynraw));   // (else the first attempt left it there)
+      restream_row<DT>(a, b, rp, t_new, fs, bm1);
+      S = 1; cap_c = a.S * a.cap_c;
       if (cut_below && fs.rq_n > (uint32_t)(kFinalThreads * kCandLong)) {
-        // the second list does not fit either: the first attempt's tables are untouched, go on from them
+        // The second list does not fit either: the cut is settled over the whole row, from the
+        // tables of an attempt on the first list -- which are there, untouched, unless that
+        // attempt was skipped: then the first list is made again (the second one lies where it
+        // was) and looked at now.
         how = kWholeRowCut;
+        if (skipped) {
+          restream_row<DT>(a, b, rp, t_old, fs, bm1);
+          how = fast_any<DT, SH>(a, b, rp, dynraw, fs, S, cap_c, ndist_ub);
+        }
         break;
       }
-      S = 1; cap_c = a.S * a.cap_c;
     }
   }
   if (how == kWholeRowCut || how == kWholeRow) {

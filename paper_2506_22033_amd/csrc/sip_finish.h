@@ -62,6 +62,7 @@ struct __align__(16) FinShared {
   uint32_t r32[kFinWaves], rkey[kFinWaves], ridx[kFinWaves];
   int bin_k, bin_n, bin_d;
   int code, code_top;
+  int retry_ok;                             // code 11 only: a second, longer list can be expected to hold the nucleus
   uint32_t hash_fail, n_memb, key_cut, n_hi;
   uint32_t token, token_key;
   unsigned long long before_d;
@@ -81,9 +82,18 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// What a caller that goes on with a row this function could not settle may reuse (uniform).
+struct FinHint {
+  bool valid = false;        // m, zmax and T are the row's
+  bool retry_ok = false;     // code 11: a second, longer list can be expected to hold the nucleus
+  float m = 0.0f;            // maximum of s
+  float zmax = 0.0f;         // maximum of z'
+  float T = 0.0f;            // every element of the row above T is in the list
+};
+
 // Row b, start to finish.  Returns 1 (finished: outputs written) or the reason why the list
 // does not settle the row.  Every return value is workgroup-uniform.
-__device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared& fs) {
+__device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared& fs, FinHint* hint = nullptr) {
   constexpr int NT = kFinThreads;
   constexpr int CR = kFinCR;
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
@@ -318,6 +328,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   const float zmax = value_of(bkey);
   if (bidx == kFinNone || !(zmax >= Tc)) return 6;                            // uniform
   const float m = scaled_s(zmax);
+  if (hint) { hint->valid = true; hint->m = m; hint->zmax = zmax; hint->T = Tc; }
   const float s_c = scaled_s(Tc);          // entries with s > s_c: every such element of the row is in the list
   const uint32_t key_c = key_of(s_c);
   const float span = __fsub_rn(m, s_c);
@@ -631,7 +642,18 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
         // the cut is proven to lie inside the list if some complete entry fell on its far side
         const bool inside = k_act || bin_p > bin_low || dropped;
         if (code == 0 && key_p == kFinNone) code = 10;
-        if (code == 0 && !inside && !minp_bounds) code = 11;                   // the nucleus may reach below the list
+        if (code == 0 && !inside && !minp_bounds) {
+          code = 11;                                                           // the nucleus may reach below the list
+          // Every token below the list weighs at most what the completeness threshold weighs, so
+          // the nucleus needs at least (limit - mass of the complete part of the list) / that many
+          // more entries: a second list is worth trying if that bound fits one and the list
+          // already holds three quarters of the nucleus' mass.  With min-p on the kept set ends
+          // at the min-p threshold at the latest, so a list cut there settles the row if it fits.
+          const unsigned long long have = fs.hmass[0], e_c = mass(s_c);
+          const unsigned long long lack = limit > have ? limit - have : 0ull;
+          const bool ok = minp_on || (e_c > 0 && lack / e_c + total < 10000ull && have >= limit - (limit >> 2));
+          if (lane == 0) fs.retry_ok = ok ? 1 : 0;
+        }
         key_cut = max(key_k, key_p);
       }
     } else if (code == 0 && !k_act && !minp_bounds) {
@@ -686,6 +708,7 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   }
   lds_barrier();
   int code = fs.code_top ? fs.code_top : fs.code;                              // a failure of the best-n ranking stands
+  if (hint && code == 11) hint->retry_ok = fs.retry_ok != 0;
   if (code == kFinDrawBig) {
     // ---- (6') kept mass per vocabulary-index bin, prefix, then the crossing inside one bin
     const uint32_t key_cut = fs.key_cut, n_hi = fs.n_hi;

@@ -22,14 +22,17 @@ __global__ __launch_bounds__(kFinalThreads) void finish_rescue_kernel(Args a_by_
   __shared__ FastShared fsr;
   static_assert(kFinThreads == kFinalThreads, "one workgroup shape for both parts");
   const int b = blockIdx.x;
-  const int code = finish_row(a, b, u.fs);
+  FinHint hint;
+  const int code = finish_row(a, b, u.fs, &hint);
   if (threadIdx.x == 0) {
     a.row_path[b] = code;
     a.row_why[b] = code;
   }
   if (code == 1) return;                     // uniform
   __syncthreads();
-  rescue_row<DT, SH>(a, b, u.raw, ex, fsr);
+  RescueSeen seen;
+  if (hint.valid) { seen.why = code; seen.retry_ok = hint.retry_ok; seen.m = hint.m; seen.zmax = hint.zmax; seen.T = hint.T; }
+  rescue_row<DT, SH>(a, b, u.raw, ex, fsr, seen);
 }
 
 }  // namespace sip
