@@ -48,6 +48,7 @@ typedef enum {
 } sip_status;
 
 #define SIP_MAX_V (1 << 19)        /* largest vocabulary the kernels support            */
+#define SIP_MAX_B (1 << 20)        /* most rows of one call                             */
 #define SIP_MAX_K_LOGPROBS 64      /* largest k_logprobs                                */
 #define SIP_MAX_SHARDS 8           /* most vocabulary shards sip_sample_sharded() takes */
 #define SIP_MAX_SLOTS (1 << 20)    /* most slots a sampler state can have               */

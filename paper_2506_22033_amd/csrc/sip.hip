@@ -164,7 +164,7 @@ Layout make_layout(int32_t B, const Plan& p, int64_t nnz, size_t gather_row_byte
   size_t off = 0;
   l.row_path = off; off += align_up((size_t)2 * B * sizeof(int));            // first, so that callers can find it: path
                                                                              // codes, then the finishing kernel's own codes
-  l.rescue = off; off += align_up((size_t)(B + 1) * sizeof(int) + 16);       // count, row numbers, the state's call counter
+  l.rescue = off; off += align_up(((size_t)B + 1) * sizeof(int) + 16);       // count, row numbers, the state's call counter
   l.side_z = off; off += align_up((size_t)nnz * sizeof(float));
   l.side_c = off; off += align_up((size_t)nnz * sizeof(unsigned int));
   l.rowinfo = off;
@@ -223,7 +223,7 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
     for (int i = 0; i < sh.t; ++i)
       if (!sh.base[i] || (reinterpret_cast<uintptr_t>(sh.base[i]) & 15u) != 0) return SIP_ERR_INVALID_ARG;
   }
-  if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return SIP_ERR_UNSUPPORTED;
+  if (B > SIP_MAX_B || V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return SIP_ERR_UNSUPPORTED;
   const Plan plan = make_plan(B, V, (int)dtype, sh.t);
   const Layout lay = make_layout(B, plan, h.nnz + h.p_nnz, sh.t ? (size_t)V * esz : 0);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 || workspace_bytes < lay.total)
@@ -276,7 +276,7 @@ sip_status sample_impl(const void* logits, int32_t B, int32_t V, int64_t row_str
   a.row_why = a.row_path + B;
   a.rescue_n = reinterpret_cast<int*>(ws + lay.rescue);
   a.rescue_rows = a.rescue_n + 1;
-  a.rescue_tick = reinterpret_cast<unsigned long long*>(ws + lay.rescue + ((size_t)(B + 1) * sizeof(int) + 7) / 8 * 8);
+  a.rescue_tick = reinterpret_cast<unsigned long long*>(ws + lay.rescue + (((size_t)B + 1) * sizeof(int) + 7) / 8 * 8);
 
   sip::StateHeader* head = h.slot ? h.state.head : nullptr;
   return sh.t ? launch<true>(a, B, (int)dtype, plan, h.slot != nullptr, head, stream)
@@ -355,7 +355,7 @@ extern "C" {
 
 size_t sip_workspace_bytes(int32_t B, int32_t V, sip_dtype dtype, int64_t hist_nnz, int32_t k_logprobs) {
   if (!shape_ok(B, V, (int)dtype, hist_nnz, k_logprobs)) return 0;
-  if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
+  if (B > SIP_MAX_B || V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
   return make_layout(B, make_plan(B, V, (int)dtype), hist_nnz).total;
 }
 
@@ -379,9 +379,10 @@ sip_status sip_sample_noalloc(const void* logits, int32_t B, int32_t V, int64_t 
                               const sip_params* params, const int64_t* hist_indptr, const int32_t* hist_tokens,
                               int64_t hist_nnz, uint64_t seed, uint64_t step, int32_t* out_ids,
                               int32_t* out_lp_ids, float* out_lp, int32_t k_logprobs, void* hip_stream) {
+  if (!logits || !out_ids) return SIP_ERR_INVALID_ARG;     // (the rest is checked by sample_impl, before anything is enqueued)
   if (hist_nnz > 0 && (!hist_indptr || !hist_tokens)) return SIP_ERR_INVALID_ARG;
   if (!shape_ok(B, V, (int)dtype, hist_nnz, k_logprobs)) return SIP_ERR_INVALID_ARG;
-  if (V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return SIP_ERR_UNSUPPORTED;
+  if (B > SIP_MAX_B || V > SIP_MAX_V || k_logprobs > SIP_MAX_K_LOGPROBS) return SIP_ERR_UNSUPPORTED;
   const size_t need = make_layout(B, make_plan(B, V, (int)dtype), hist_nnz).total;
   if (need > kNoallocBytes) return SIP_ERR_SCRATCH;
   DeviceSetup* d = device_setup();                 // the current device's copy of the array
@@ -395,7 +396,7 @@ sip_status sip_sample_noalloc(const void* logits, int32_t B, int32_t V, int64_t 
 
 size_t sip_workspace_bytes_sharded(int32_t B, int32_t V_shard, int32_t t, sip_dtype dtype, int64_t hist_nnz,
                                    int32_t k_logprobs) {
-  if (t < 1 || t > SIP_MAX_SHARDS || V_shard <= 0 || (int64_t)V_shard * t > SIP_MAX_V) return 0;
+  if (t < 1 || t > SIP_MAX_SHARDS || V_shard <= 0 || (int64_t)V_shard * t > SIP_MAX_V || B > SIP_MAX_B) return 0;
   const int32_t V = V_shard * t;
   if (!shape_ok(B, V, (int)dtype, hist_nnz, k_logprobs) || k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
   return make_layout(B, make_plan(B, V, (int)dtype, t), hist_nnz, (size_t)V * (dtype == SIP_F32 ? 4 : 2)).total;
@@ -407,7 +408,7 @@ sip_status sip_sample_sharded(const void* const* shard_logits, int32_t t, int32_
                               uint64_t seed, uint64_t step, int32_t* out_ids, int32_t* out_lp_ids, float* out_lp,
                               int32_t k_logprobs, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (t < 1 || t > SIP_MAX_SHARDS || V_shard <= 0 || !shard_logits) return SIP_ERR_INVALID_ARG;
-  if ((int64_t)V_shard * t > SIP_MAX_V) return SIP_ERR_UNSUPPORTED;
+  if ((int64_t)V_shard * t > SIP_MAX_V || B > SIP_MAX_B) return SIP_ERR_UNSUPPORTED;
   if (hist_nnz > 0 && (!hist_indptr || !hist_tokens)) return SIP_ERR_INVALID_ARG;
   HistSource h;
   h.indptr = hist_indptr; h.tokens = hist_tokens; h.nnz = hist_nnz;
@@ -469,7 +470,7 @@ sip_status call_sources(const sip_call* c, HistSource& h, ShardSource& sh, int32
   if (c->t_shards < 0 || c->t_shards > SIP_MAX_SHARDS) return SIP_ERR_INVALID_ARG;
   if (c->t_shards > 0) {
     if (c->V_shard <= 0 || !c->shard_logits) return SIP_ERR_INVALID_ARG;
-    if ((int64_t)c->V_shard * c->t_shards > SIP_MAX_V) return SIP_ERR_UNSUPPORTED;
+    if ((int64_t)c->V_shard * c->t_shards > SIP_MAX_V || c->B > SIP_MAX_B) return SIP_ERR_UNSUPPORTED;
     sh.base = c->shard_logits; sh.t = c->t_shards; sh.V_shard = c->V_shard; sh.stride = c->shard_stride;
     V = c->V_shard * c->t_shards;
   } else {
@@ -501,7 +502,7 @@ size_t sip_call_workspace_bytes(const sip_call* c) {
   HistSource h; ShardSource sh; int32_t V = 0;
   if (call_sources(c, h, sh, V) != SIP_OK) return 0;
   if (!shape_ok(c->B, V, (int)c->dtype, h.nnz, c->k_logprobs)) return 0;
-  if (V > SIP_MAX_V || c->k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
+  if (c->B > SIP_MAX_B || V > SIP_MAX_V || c->k_logprobs > SIP_MAX_K_LOGPROBS) return 0;
   const size_t esz = c->dtype == SIP_F32 ? 4 : 2;
   return make_layout(c->B, make_plan(c->B, V, (int)c->dtype, sh.t), h.nnz + h.p_nnz, sh.t ? (size_t)V * esz : 0).total;
 }
@@ -556,7 +557,7 @@ sip_status sip_probe_read(const void* src, size_t bytes, int32_t workgroups, voi
 }
 
 int32_t sip_plan_chunks(int32_t B, int32_t V, sip_dtype dtype, int32_t t_shards) {
-  if (B <= 0 || V <= 0 || (dtype != SIP_F32 && dtype != SIP_BF16) || t_shards < 0 || t_shards > SIP_MAX_SHARDS) return -1;
+  if (B <= 0 || B > SIP_MAX_B || V <= 0 || (dtype != SIP_F32 && dtype != SIP_BF16) || t_shards < 0 || t_shards > SIP_MAX_SHARDS) return -1;
   if (t_shards > 0 && V % t_shards != 0) return -1;
   const Plan p = make_plan(B, V, (int)dtype, t_shards);
   return p.fast ? p.S : 0;
