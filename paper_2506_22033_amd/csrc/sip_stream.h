@@ -409,6 +409,34 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     }
     __syncthreads();
   }
+  // A row that is masked almost everywhere (-inf for all but a few hundred tokens, as a grammar
+  // constraint leaves it) has fewer finite values in its sample than the list asks for, and the
+  // threshold has landed among the -inf (keys up to 511 in 18 bits: -inf and the negative NaNs).
+  // Then the lowest finite sample value is the threshold: the list takes every finite element
+  // from there up, and what lies below it is bulk as usual.  (No finite sample value at all: the
+  // lowest finite float, which makes the finishing kernel pass the row on.)
+  if (key_thr <= 511u) {                                                       // workgroup-uniform
+    float lo = INFINITY;
+#pragma unroll
+    for (int l = 0; l < SLOADS; ++l) {
+      float z[EPL];
+      unpack(smp[l], z);
+#pragma unroll
+      for (int i = 0; i < EPL; ++i)
+        if (z[i] > -INFINITY && z[i] < lo) lo = z[i];
+    }
+    uint32_t klo = last_lane_u32(dpp_scan_min_u32(lo == INFINITY ? 0xFFFFFFFFu : key_of(lo)));
+    __syncthreads();                                                           // red32 is free again
+    if (lane == 0) red32[wave] = klo;
+    __syncthreads();
+    klo = red32[0];
+#pragma unroll
+    for (int w = 1; w < kStreamWaves; ++w) klo = min(klo, red32[w]);
+    const uint32_t k18 = klo == 0xFFFFFFFFu ? 512u : max(klo >> 14, 512u);
+    __syncthreads();
+    if (tid == 0) key_thr = k18;
+    __syncthreads();
+  }
   const uint32_t kb = key_thr << 14;
   const float Tc = value_of(kb);
   const BulkRef ref = make_bulk_ref(Tc, rp);

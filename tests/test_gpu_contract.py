@@ -98,6 +98,10 @@ def test_rows_that_are_almost_entirely_masked(dtype):
         st = H.compare(w, out, 9, step)
         assert st.rows == B
     print(f"[masked {dtype}] row paths {H.last_row_path.tolist()}", flush=True)
+    if dtype == "f32":
+        # the rows with 500 finite tokens are settled from their list (the threshold steps down to
+        # the lowest finite sample value); the normal rows anyway
+        assert (H.last_row_path[[0, 1, 2, 4, 5]] == 1).all(), H.last_row_path
 
 
 def test_tiny_temperatures_are_ordinary_stochastic_rows():
