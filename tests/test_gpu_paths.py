@@ -76,6 +76,27 @@ def test_batches_of_more_rows_than_compute_units_queue_their_hard_rows():
     assert (paths == 15).any() and (paths == 16).any(), np.unique(paths, return_counts=True)
 
 
+def test_large_batch_with_top_k_in_the_thousands():
+    """Beyond 512 rows a row is cut into as few as two chunks, whose queues bound the longest list a
+    row may have: rows with top_k from 1000 to 7000 (with and without history) must come out
+    right whether the list holds them, overflows, or is never made."""
+    rng = np.random.default_rng(5)
+    V, B = 40000, 1024
+    z = (rng.standard_normal((B, V)) * 2.0).astype(np.float32)
+    ks = rng.choice([1000, 3000, 4500, 5500, 7000], B)
+    params = dict(temperature=rng.uniform(0.6, 1.2, B), top_k=ks, top_p=rng.choice([1.0, 0.95], B),
+                  frequency_penalty=rng.choice([0.0, 0.3], B))
+    hist = [rng.integers(0, V, int(n)).tolist() for n in rng.choice([0, 200, 1500], B)]
+    st, paths = _check(H.custom("big_k", z, params, hist, k_logprobs=2), steps=(0,))
+    assert st.rows == B
+    assert (paths[0][ks == 1000] == 1).all(), np.unique(paths[0][ks == 1000], return_counts=True)
+    why = H.last_row_why
+    print("[big_k] (path, reason of the finishing kernel) by k:",
+          {int(k): sorted(set(zip(paths[0][ks == k].tolist(), why[ks == k].tolist()))) for k in np.unique(ks)}, flush=True)
+    assert (why[ks == 1000] == 1).all()                    # settled by the finishing kernel itself
+    assert (why[ks == 7000] != 1).all()                    # beyond what two chunks hand over, or what it sorts
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_nucleus_that_reaches_far_below_the_candidate_list(bf16):
     """top-p alone on flat and on hot distributions keeps tens of thousands of tokens: the cut is
