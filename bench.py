@@ -357,6 +357,41 @@ def in_flight_leg(w, d, bufs, sip, dev, args):
     return out
 
 
+def noalloc_leg(w, d, bufs, sip, dev, stream, args, ref_out):
+    """The entry point that allocates nothing (built-in scratch instead of a workspace) on the same
+    workload, if its scratch holds it: time per step, and its outputs against sip_sample's."""
+    import torch
+    k = w.k_logprobs
+    nnz = 0 if d.tokens is None else d.tokens.numel()
+    dt_code = sip.SIP_F32 if w.dtype == "f32" else sip.SIP_BF16
+    if sip.sip_workspace_bytes(w.B, w.V, dt_code, nnz, k) > sip.sip_noalloc_scratch_bytes():
+        return None
+    ids = torch.empty(w.B, dtype=torch.int32, device=dev)
+    lp_ids = torch.empty(w.B, 1 + k, dtype=torch.int32, device=dev)
+    lp = torch.empty(w.B, 1 + k, dtype=torch.float32, device=dev)
+
+    def step(i):
+        sip.sip_sample_noalloc(bufs[i % len(bufs)], d.params, d.indptr, d.tokens, 0, i, k, out_ids=ids,
+                               out_lp_ids=lp_ids, out_lp=lp, V=w.V, stream=stream)
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        last = args.warmup + args.steps - 1
+        sip.sip_sample(bufs[last % len(bufs)], d.params, d.indptr, d.tokens, 0, last, k, out_ids=ref_out[0],
+                       out_lp_ids=ref_out[1], out_lp=ref_out[2], workspace=ref_out[3], V=w.V, stream=stream)
+        torch.cuda.synchronize()
+    same = bool(torch.equal(ids, ref_out[0]) and torch.equal(lp_ids, ref_out[1]) and
+                torch.equal(lp.view(torch.int32), ref_out[2].view(torch.int32)))
+    return {"ms_per_step": ms, "value": w.B / (ms * 1e-3), "unit": "rows/s", "bit_equal_to_sip_sample": same,
+            "scratch_bytes": sip.sip_noalloc_scratch_bytes()}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -468,6 +503,7 @@ def main() -> int:
     hand_leg = handoff_leg(w, d, bufs, sip, dev, stream, args, ws) if extra else None
     shard_leg = sharded_leg(w, d, bufs, sip, dev, stream, args) if extra else None
     flight_leg = in_flight_leg(w, d, bufs, sip, dev, args) if extra else None
+    na_leg = noalloc_leg(w, d, bufs, sip, dev, stream, args, (out_ids, out_lp_ids, out_lp, ws)) if extra else None
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -509,6 +545,7 @@ def main() -> int:
         "vocabulary_sharded_logits": shard_leg,
         "host_handoff": hand_leg,
         "batches_in_flight": flight_leg,
+        "no_allocation_entry_point": na_leg,
     }
     print(json.dumps(res))
     return 0

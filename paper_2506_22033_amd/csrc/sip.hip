@@ -114,7 +114,7 @@ constexpr int kRescueGrid = 256;         // workgroups of the rescue kernel (one
 // Built-in scratch of sip_sample_noalloc(): one copy per device, at that device's own address.
 // In host code the name below is only a handle for hipGetSymbolAddress; the address the kernels
 // get is the one looked up in device_setup().
-constexpr size_t kNoallocBytes = (size_t)32 << 20;
+constexpr size_t kNoallocBytes = (size_t)40 << 20;     // holds a call of 256 rows at V = 152064 (33.6 MB)
 static __device__ __align__(256) unsigned char scratch[kNoallocBytes];
 
 struct DeviceSetup {

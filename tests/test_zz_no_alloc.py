@@ -45,6 +45,7 @@ def test_noalloc_rejects_what_does_not_fit_before_enqueuing():
     lib = sip.load()
     need = sip.sip_workspace_bytes(2048, 256000, sip.SIP_F32, 0, 0)
     assert need > sip.sip_noalloc_scratch_bytes()
+    assert sip.sip_workspace_bytes(256, 152064, sip.SIP_F32, 256 * 1024, 20) <= sip.sip_noalloc_scratch_bytes()
     st = lib.sip_sample_noalloc(0x10000, 2048, 256000, 256000, sip.SIP_F32, None, None, None, 0, 0, 0,
                                 0x20000, None, None, -1, None)
     assert st == sip.binding.SIP_ERR_SCRATCH
