@@ -1,10 +1,19 @@
-// Finishing kernel of the single-pass path: one workgroup per row turns what the streaming
-// kernel left behind -- a few thousand (value, index) candidates that are complete above a
-// value threshold, plus the integer mass of everything else -- into the row's token, its
-// logprob and the best-n list, without reading the logits again (except for the at most
-// |history| elements that carry a penalty).
+// The heavier per-row logic of the single-pass path, for the rows that the finishing kernel
+// (sip_finish.h) cannot settle from the list the streaming kernel left behind: rescue_row(),
+// run by rescue_kernel on the rows queued for it or, in small batches, by the workgroup that
+// just tried (sip_fused.h).  It tries, in this order,
+//   - the row's list again in register variants that hold up to 24 entries per thread
+//     (fast_row: lists of up to 12288 entries, as top_k in the thousands makes them), with the
+//     history tokens' multiplicities from a bitmap over the vocabulary, popcount ranks and side
+//     tables in LDS;
+//   - a second, longer list, made by reading the row once more with a lower threshold
+//     (restream_row), and the same logic on that one;
+//   - the continuations over the whole row (whole_row_finish): a nucleus that reaches below any
+//     list is cut by a radix descent on the exact fp32 s, and a row without any filter is drawn
+//     over all its elements;
+//   - the exact multi-pass path (sip_exact.h).
 //
-// The candidate list lives in registers: every thread keeps its share of the entries (key,
+// fast_row keeps the list in registers: every thread holds its share of the entries (key,
 // index, mass, value bin) from the moment they are read until the end.  Every sum is an
 // integer sum (masses in units of 2^-40 of the maximum's mass), so no result depends on the
 // order in which threads add.  Selection works on 2048 linear value bins between the
@@ -13,10 +22,9 @@
 // then resolved by all-pairs comparison.  The draw does the same over 2048 bins of the
 // vocabulary index.
 //
-// Whenever the list cannot prove the answer (a cut falls below the completeness threshold,
-// a bin or a segment overflows, too many distinct history tokens, ...) the function returns a
-// reason code > 1 and the caller tries again with a longer list or runs the exact multi-pass
-// path on the row; 1 means the row is finished.
+// Whenever a list cannot prove the answer (a cut falls below the completeness threshold,
+// a bin or a segment overflows, too many distinct history tokens, ...) fast_row returns a
+// reason code > 1 and rescue_row goes on to the next of the above; 1 means the row is finished.
 #pragma once
 #include <type_traits>
 
