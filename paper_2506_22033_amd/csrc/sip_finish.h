@@ -114,27 +114,35 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   uint2* seg = a.cand + ((size_t)b * (size_t)S + (size_t)min(c_seg, S - 1)) * (size_t)a.cap_c;
   uint2 creg[CR];                          // (bits of z, later of z' and then the key of s; index | tag, later index)
   auto slot_of = [&](int bt, int r) { return (bt * CR + r) * tps + j_seg; };
-  auto load_batch = [&](int bt) {          // unchecked against the sizes
+  // Unchecked against the sizes, and unconditional (a branch around a load makes the compiler wait
+  // for every load in flight where the branches meet): slots past the segment's capacity read its
+  // last slot, threads without a segment the last segment's; drop_beyond() discards what they get.
+  auto load_batch = [&](int bt) {
 #pragma unroll
-    for (int r = 0; r < CR; ++r) {
-      const int sl = slot_of(bt, r);
-      creg[r] = make_uint2(0u, kFinNone);
-      if (seg_thread && sl < a.cap_c) creg[r] = seg[sl];
-    }
+    for (int r = 0; r < CR; ++r) creg[r] = seg[min(slot_of(bt, r), a.cap_c - 1)];
   };
-  load_batch(0);
+  // (the two small records first: loads come back in the order of their requests, and what
+  // depends on the records -- the history loads, the plan of the phases -- need not wait for the list)
+  // The early exits below name the list's registers as well: with no use of the list on those
+  // paths the compiler would move the list's loads behind the exits' branches, that is, behind the
+  // wait for the records.
+  auto list_is_used = [&]() {
+#pragma unroll
+    for (int r = 0; r < CR; ++r) asm volatile("" ::"v"(creg[r].x), "v"(creg[r].y));
+  };
   const RowInfo ri = a.rowinfo[b];
+  const ChunkOut co = a.chunks[(size_t)b * S + min(lane, S - 1)];
+  load_batch(0);
   uint32_t my_cnt = 0;
   unsigned long long my_bulk = 0;
   float Tc;
   int R;
   {
-    const ChunkOut co = a.chunks[(size_t)b * S + min(lane, S - 1)];
     if (lane < S) { my_cnt = co.cnt; my_bulk = co.bulk; }
     Tc = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(co.Tc)));   // the chunks of a row share
     R = __builtin_amdgcn_readfirstlane(co.R);                                                      // threshold and exponent
   }
-  if ((ri.target & ~kPromptFlag) == 0) return 2;                             // uniform: k beyond any list
+  if ((ri.target & ~kPromptFlag) == 0) { list_is_used(); return 2; }          // uniform: k beyond any list
   const bool prompt_on = (ri.target & kPromptFlag) != 0;                     // tokens of a separate prompt are tagged too
   RowParams rp;
   rp.tau = ri.tau; rp.top_p = ri.top_p; rp.min_p = ri.min_p; rp.theta = ri.theta; rp.phi = ri.phi; rp.psi = ri.psi;
@@ -194,8 +202,8 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   const uint32_t total = wave_add_u32(my_cnt);
   const uint32_t longest = wave_max_u32(my_cnt);
   const unsigned long long bulk = wave_add_u64(my_bulk);
-  if (any_over || !(Tc == Tc)) return 3;                                     // uniform
-  if (total > (uint32_t)a.nc_cap) return 5;                                  // uniform
+  if (any_over || !(Tc == Tc)) { list_is_used(); return 3; }                 // uniform
+  if (total > (uint32_t)a.nc_cap) { list_is_used(); return 5; }              // uniform
   const int nb = (int)((longest + (uint32_t)(CR * tps) - 1) / (uint32_t)(CR * tps));   // uniform: batches of CR rounds
   const int cnt_seg = seg_thread ? __shfl((int)my_cnt, c_seg, kWave) : 0;    // size of this thread's segment
   // whether round r of batch bt holds anything at all (uniform): every round is unrolled code that
