@@ -126,15 +126,17 @@ __device__ __forceinline__ int finish_row(const Args& a, const int b, FinShared&
   // The early exits below name the list's registers as well: with no use of the list on those
   // paths the compiler would move the list's loads behind the exits' branches, that is, behind the
   // wait for the records.
+  // (The same goes for the part of the chunk summary that the exits do not look at.)
+  unsigned long long my_bulk = 0;
   auto list_is_used = [&]() {
 #pragma unroll
     for (int r = 0; r < CR; ++r) asm volatile("" ::"v"(creg[r].x), "v"(creg[r].y));
+    asm volatile("" ::"v"((uint32_t)my_bulk), "v"((uint32_t)(my_bulk >> 32)));
   };
   const RowInfo ri = a.rowinfo[b];
   const ChunkOut co = a.chunks[(size_t)b * S + min(lane, S - 1)];
   load_batch(0);
   uint32_t my_cnt = 0;
-  unsigned long long my_bulk = 0;
   float Tc;
   int R;
   {
