@@ -121,6 +121,16 @@ __device__ __forceinline__ HistRange hist_range(const Args& a, int b) {
   }
   return h;
 }
+// The same for a call without a state, from the row's two CSR offsets as they were read.
+__device__ __forceinline__ HistRange hist_range_csr(const Args& a, long long lo, long long hi) {
+  HistRange h{0, 0, 0};
+  if (a.indptr && a.tokens && a.nnz > 0) {
+    h.lo = lo < 0 ? 0 : (lo > a.nnz ? a.nnz : lo);
+    h.hi = hi < h.lo ? h.lo : (hi > a.nnz ? a.nnz : hi);
+    h.side = h.lo;
+  }
+  return h;
+}
 // Which tokens of row b carry a penalty and what has to be known about them (Sec. 2.1 step 3 (1);
 // Sec. 5.1 CalcPenalty): the row's history (the generated tokens: all three penalties) and,
 // if the caller hands them in separately, its prompt tokens (repetition penalty only).
@@ -133,13 +143,15 @@ struct PenaltyPlan {
   bool counts;            // the tokens' multiplicities in the history are needed ...
   unsigned int dflt;      // ... otherwise every penalised token is taken to occur this often in it
 };
-__device__ __forceinline__ PenaltyPlan penalty_plan(const Args& a, int b, float theta, float phi, float psi) {
+// (`h`: the row's history extent; `p0`, `p1`: the row's raw offsets into the prompt tokens, looked
+// at only if the call has prompt tokens)
+__device__ __forceinline__ PenaltyPlan penalty_plan_of(const Args& a, const HistRange h, long long p0, long long p1,
+                                                       float theta, float phi, float psi) {
   PenaltyPlan q;
-  q.h = hist_range(a, b);
+  q.h = h;
   q.p_lo = q.p_hi = 0;
   long long p_before = 0;   // prompt tokens of the rows before this one: they shift the row's part of the side tables
   if (a.p_indptr && a.p_tokens && a.p_nnz > 0) {
-    long long p0 = a.p_indptr[b], p1 = a.p_indptr[b + 1];
     p0 = p0 < 0 ? 0 : (p0 > a.p_nnz ? a.p_nnz : p0);
     p1 = p1 < p0 ? p0 : (p1 > a.p_nnz ? a.p_nnz : p1);
     p_before = p0;
@@ -152,6 +164,11 @@ __device__ __forceinline__ PenaltyPlan penalty_plan(const Args& a, int b, float 
   q.dflt = hist ? 1u : 0u;
   q.side = q.h.side + p_before;
   return q;
+}
+__device__ __forceinline__ PenaltyPlan penalty_plan(const Args& a, int b, float theta, float phi, float psi) {
+  long long p0 = 0, p1 = 0;
+  if (a.p_indptr && a.p_tokens && a.p_nnz > 0) { p0 = a.p_indptr[b]; p1 = a.p_indptr[b + 1]; }
+  return penalty_plan_of(a, hist_range(a, b), p0, p1, theta, phi, psi);
 }
 // Base of shard `sh` (uniform or per lane): a chain of selects, because the table lives in the
 // kernel-argument segment and must be indexed with constants.

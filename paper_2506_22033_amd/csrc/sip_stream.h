@@ -163,20 +163,9 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
   // Workgroups are handed to the 8 XCDs round-robin by their id.  The chunks of one row read
   // the same sample, so they are renumbered to land on the same XCD (and its L2): id i works
   // on logical chunk (i % 8) * (n / 8) + i / 8 when n, the grid size, is a multiple of 8.
-  // Device-resident history: this call takes its number from the state's call counter here (one
-  // atomic add, so that calls in flight at once on one state each get their own) and leaves it in
-  // the workspace, where the kernels behind this one read it (step_of()).
-  if (a.call_tick && blockIdx.x == 0 && tid == 0) *a.call_tick = atomicAdd(a.st_tick, 1ull);
-  if (blockIdx.x == 0 && tid == 0) *a.rescue_n = 0;          // the finishing kernel counts from zero
   int wg = blockIdx.x;
   if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   const int b = wg / a.S, ch = wg - b * a.S;
-  const RowParams rp = load_row_params(a, b);
-  const int target = candidate_target(rp, a);
-  if (target == 0) {
-    if (wg - b * a.S == 0 && tid == 0) a.rowinfo[b].target = 0;             // the finishing kernel looks at nothing else
-    return;
-  }
   const int V = a.V;
   // SH (vocabulary-sharded logits): the row's chunks are dealt out to the shards, S / t_shards
   // each, and a chunk lies inside its shard; c0, c1 and every element index below are then
@@ -221,13 +210,62 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     }
   };
 
-  // the first tiles of the chunk are requested before anything else so that they travel
-  // while the threshold is being worked out
+  // ---- The row's small records -- parameters, history and prompt extents -- are read first, all
+  // at once and without a branch in between (where branches meet, the compiler waits for every
+  // load in flight).  Their addresses are the same for the whole workgroup and nothing has been
+  // stored by this kernel so far, so the compiler reads them through the scalar cache into scalar
+  // registers: one round trip, and no vector registers held while they travel.  What a call does
+  // not have (a NULL parameter array, no history) is read from memory that is there anyway and
+  // replaced by its default afterwards.
+  const char* const dummy = reinterpret_cast<const char*>(a.chunks);
+  auto rec = [&](const void* arr, size_t off) { return arr ? reinterpret_cast<const char*>(arr) + off : dummy; };
+  const bool csr_on = !a.slot && a.indptr && a.tokens && a.nnz > 0;
+  const bool prompt_csr = a.p_indptr && a.p_tokens && a.p_nnz > 0;
+  const float r_tau = *reinterpret_cast<const float*>(rec(a.p.temperature, 4 * (size_t)b));
+  const int r_k = *reinterpret_cast<const int*>(rec(a.p.top_k, 4 * (size_t)b));
+  const float r_p = *reinterpret_cast<const float*>(rec(a.p.top_p, 4 * (size_t)b));
+  const float r_minp = *reinterpret_cast<const float*>(rec(a.p.min_p, 4 * (size_t)b));
+  const float r_theta = *reinterpret_cast<const float*>(rec(a.p.repetition_penalty, 4 * (size_t)b));
+  const float r_phi = *reinterpret_cast<const float*>(rec(a.p.frequency_penalty, 4 * (size_t)b));
+  const float r_psi = *reinterpret_cast<const float*>(rec(a.p.presence_penalty, 4 * (size_t)b));
+  const long long r_id = *reinterpret_cast<const long long*>(rec(a.p.row_id, 8 * (size_t)b));
+  const long long r_h0 = *reinterpret_cast<const long long*>(rec(csr_on ? a.indptr : nullptr, 8 * (size_t)b));
+  const long long r_h1 = *reinterpret_cast<const long long*>(rec(csr_on ? a.indptr : nullptr, 8 * (size_t)b + 8));
+  const long long r_p0 = *reinterpret_cast<const long long*>(rec(prompt_csr ? a.p_indptr : nullptr, 8 * (size_t)b));
+  const long long r_p1 = *reinterpret_cast<const long long*>(rec(prompt_csr ? a.p_indptr : nullptr, 8 * (size_t)b + 8));
+  // (all of them are named here, once: otherwise the compiler moves each read to the branch that
+  // first looks at its value, and the round trips follow one another)
+  asm volatile("" ::"s"(r_tau), "s"(r_k), "s"(r_p), "s"(r_minp), "s"(r_theta), "s"(r_phi), "s"(r_psi), "s"(r_id),
+               "s"(r_h0), "s"(r_h1), "s"(r_p0), "s"(r_p1));
+  // ---- the records: defaults for what the call does not have
+  RowParams rp;
+  rp.tau = a.p.temperature ? r_tau : 1.0f;
+  rp.top_k = a.p.top_k ? r_k : 0;
+  rp.top_p = a.p.top_p ? r_p : 1.0f;
+  rp.min_p = a.p.min_p ? r_minp : 0.0f;
+  rp.theta = a.p.repetition_penalty ? r_theta : 1.0f;
+  rp.phi = a.p.frequency_penalty ? r_phi : 0.0f;
+  rp.psi = a.p.presence_penalty ? r_psi : 0.0f;
+  rp.row_id = a.p.row_id ? (unsigned long long)r_id : (unsigned long long)b;
+  rp.greedy = (rp.tau == 0.0f) || (rp.top_k == 1);
+  // what one thread of the grid does for the whole call (on every path out of this kernel)
+  auto once_per_call = [&]() {
+    if (a.call_tick && blockIdx.x == 0 && tid == 0) *a.call_tick = atomicAdd(a.st_tick, 1ull);
+    if (blockIdx.x == 0 && tid == 0) *a.rescue_n = 0;        // the finishing kernel counts from zero
+  };
+  const int target = candidate_target(rp, a);
+  if (target == 0) {
+    once_per_call();
+    if (ch == 0 && tid == 0) a.rowinfo[b].target = 0;                        // the finishing kernel looks at nothing else
+    return;
+  }
+  // ---- the first tiles of the chunk are requested before anything else is worked out, so that
+  // they travel meanwhile
   uint4 buf[kStreamBufs][kStreamLoads];
   int tnext = c0;                                    // first element of the next tile to request
 #pragma unroll
   for (int k = 0; k < kStreamBufs; ++k) {
-    if (tnext < c1) load_tile(tnext, buf[k]);
+    load_tile(tnext, buf[k]);                        // (past the chunk's end: its last 16 bytes again, never looked at)
     tnext += TILE;
   }
 
@@ -238,7 +276,6 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
   // All blocks are requested, whether or not the row's rank calls for the whole sample: a branch
   // around a load makes the compiler wait for that load where the branches meet, one exposed
   // memory latency per block.
-  const bool whole = whole_sample(target, V);        // workgroup-uniform, like everything about the threshold
   uint4 smp[SLOADS];
 #pragma unroll
   for (int j = 0; j < SLOADS; ++j) {
@@ -258,10 +295,19 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
       smp[j] = *reinterpret_cast<const uint4*>(srow + (size_t)e0 * ESZ);
     }
   }
+  // Device-resident history: this call takes its number from the state's call counter here (one
+  // atomic add, so that calls in flight at once on one state each get their own) and leaves it in
+  // the workspace, where the kernels behind this one read it (step_of()).
+  // (Not before the records above have been read: with no store ahead of them in the kernel the
+  // compiler reads them, whose addresses are the same for the whole workgroup, through the scalar
+  // cache, into scalar registers, and their wait is not a wait for the tiles.)
+  once_per_call();
+  const bool whole = whole_sample(target, V);        // workgroup-uniform, like everything about the threshold
   // ---- history bitmap of the chunk: bit (v - g0) for every history token v in [g0, g1), the
   // vocabulary ids this workgroup streams.  Requested here, entered after the first barrier.
-  const PenaltyPlan pen = penalty_plan(a, b, rp.theta, rp.phi, rp.psi);
-  const HistRange hr = pen.h;
+  // (A device-resident state's extent takes two dependent reads of its own.)
+  const HistRange hr = a.slot ? hist_range(a, b) : hist_range_csr(a, r_h0, r_h1);
+  const PenaltyPlan pen = penalty_plan_of(a, hr, r_p0, r_p1, rp.theta, rp.phi, rp.psi);
   const bool has_pen = pen.any;                                                                       // uniform
   const bool hist_pen = has_pen && hr.hi > hr.lo;
   const int g0 = (int)ibase + c0;

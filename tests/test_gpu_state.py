@@ -58,7 +58,7 @@ def _follow(st: O.DecodeState, slot: int, gpu_id: int):
     st.f[slot, gpu_id] += 1
 
 
-def _decode(name, V, B, slots, L_max, slot_of_row, prompts, T, seed, bf16=False, k_lp=4, reassign=None):
+def _decode(name, V, B, slots, L_max, slot_of_row, prompts, T, seed, bf16=False, k_lp=4, reassign=None, tweak=None):
     import workloads
     rng = np.random.default_rng(seed)
     ost = O.DecodeState(slots, L_max, V)
@@ -84,6 +84,8 @@ def _decode(name, V, B, slots, L_max, slot_of_row, prompts, T, seed, bf16=False,
                 z[b, h[-6:]] += 6.0
         logits = workloads.f32_to_bf16_bits(z) if bf16 else z
         p = _params(rng, B, V)
+        if tweak:
+            tweak(p)
         dparams = {k: torch.from_numpy(v).to(DEV) for k, v in p.items()}
         dparams["row_id"] = torch.from_numpy(row_ids).to(DEV)
         dl = H.logits_to_device(logits)
@@ -137,6 +139,22 @@ def test_decode_iterations_on_device_state_match_the_oracle(V, bf16):
     st = _decode(f"state V={V} {'bf16' if bf16 else 'f32'}", V, B, slots, L_max, slot_of_row, prompts, T=6,
                  seed=V, bf16=bf16)
     assert st.rows == 6 * B
+
+
+def test_first_row_of_the_batch_leaves_the_streaming_kernel_early():
+    """Row 0 asks for a top_k that no candidate list holds, so the first workgroup of the streaming
+    kernel -- the one that also takes the call's number from the state and resets the queue of
+    hard rows -- returns before it streams anything.  The call counter, the appended ids and the
+    other rows must not notice."""
+    rng = np.random.default_rng(3)
+    V, B, slots, L_max = 20011, 6, 6, 64
+    prompts = {s: rng.integers(0, V, 10 + 5 * s).tolist() for s in range(slots)}
+
+    def tweak(p):
+        p["top_k"][0] = 15000
+        p["temperature"][0] = 0.9
+    st = _decode("state row 0 exact", V, B, slots, L_max, list(range(B)), prompts, T=4, seed=8, tweak=tweak)
+    assert st.rows == 4 * B
 
 
 def test_long_histories_use_the_tables_the_state_keeps():
