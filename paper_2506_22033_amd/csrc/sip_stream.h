@@ -248,14 +248,17 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
   rp.psi = a.p.presence_penalty ? r_psi : 0.0f;
   rp.row_id = a.p.row_id ? (unsigned long long)r_id : (unsigned long long)b;
   rp.greedy = (rp.tau == 0.0f) || (rp.top_k == 1);
-  // what one thread of the grid does for the whole call (on every path out of this kernel)
-  auto once_per_call = [&]() {
-    if (a.call_tick && blockIdx.x == 0 && tid == 0) *a.call_tick = atomicAdd(a.st_tick, 1ull);
-    if (blockIdx.x == 0 && tid == 0) *a.rescue_n = 0;        // the finishing kernel counts from zero
-  };
   const int target = candidate_target(rp, a);
+  // ---- What one thread of the grid does for the whole call.  Device-resident history: the call
+  // takes its number from the state's call counter (one atomic add, so that calls in flight at once
+  // on one state each get their own) and leaves it in the workspace, where the kernels behind this
+  // one read it (step_of()).  The finishing kernel counts the rows it passes on from zero.
+  // (Here, on the one path that every workgroup takes, and not before the records above have been
+  // read: with no store ahead of them in the kernel the compiler reads them through the scalar
+  // cache.)
+  if (a.call_tick && blockIdx.x == 0 && tid == 0) *a.call_tick = atomicAdd(a.st_tick, 1ull);
+  if (blockIdx.x == 0 && tid == 0) *a.rescue_n = 0;
   if (target == 0) {
-    once_per_call();
     if (ch == 0 && tid == 0) a.rowinfo[b].target = 0;                        // the finishing kernel looks at nothing else
     return;
   }
@@ -295,13 +298,6 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
       smp[j] = *reinterpret_cast<const uint4*>(srow + (size_t)e0 * ESZ);
     }
   }
-  // Device-resident history: this call takes its number from the state's call counter here (one
-  // atomic add, so that calls in flight at once on one state each get their own) and leaves it in
-  // the workspace, where the kernels behind this one read it (step_of()).
-  // (Not before the records above have been read: with no store ahead of them in the kernel the
-  // compiler reads them, whose addresses are the same for the whole workgroup, through the scalar
-  // cache, into scalar registers, and their wait is not a wait for the tiles.)
-  once_per_call();
   const bool whole = whole_sample(target, V);        // workgroup-uniform, like everything about the threshold
   // ---- history bitmap of the chunk: bit (v - g0) for every history token v in [g0, g1), the
   // vocabulary ids this workgroup streams.  Requested here, entered after the first barrier.
