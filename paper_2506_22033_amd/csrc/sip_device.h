@@ -193,6 +193,28 @@ __device__ __attribute__((noinline)) void gather_row(const Args& a, int b) {
   }
   __syncthreads();
 }
+// The kernels read their arguments where they use them, straight from the kernel-argument
+// segment, and a first read of each of its 64-byte lines misses the scalar cache: spread over a
+// kernel those are as many round trips one after the other.  This touches every line at once,
+// at the start (scalar loads only, results thrown away).
+__device__ __forceinline__ void warm_kernel_arguments() {
+  static_assert(sizeof(Args) >= 0x1c4 && sizeof(Args) <= 0x200, "eight lines of 64 bytes");
+  const void* p = (const void*)__builtin_amdgcn_kernarg_segment_ptr();
+  uint32_t t0, t1, t2, t3, t4, t5, t6, t7;
+  asm volatile(
+      "s_load_dword %0, %8, 0x0\n\t"
+      "s_load_dword %1, %8, 0x40\n\t"
+      "s_load_dword %2, %8, 0x80\n\t"
+      "s_load_dword %3, %8, 0xc0\n\t"
+      "s_load_dword %4, %8, 0x100\n\t"
+      "s_load_dword %5, %8, 0x140\n\t"
+      "s_load_dword %6, %8, 0x180\n\t"
+      "s_load_dword %7, %8, 0x1c0\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4), "=&s"(t5), "=&s"(t6), "=&s"(t7)
+      : "s"(p));
+}
+
 // Philox step of this call: on a state, `step` plus the number of calls made on the state before
 // this one.  The streaming kernel takes that number (one atomic add, so that calls in flight at
 // once on one state each get their own) and leaves it in the call's workspace; a call that has no

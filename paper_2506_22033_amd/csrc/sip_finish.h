@@ -812,6 +812,7 @@ __global__ __launch_bounds__(kFinThreads) __attribute__((amdgpu_waves_per_eu(4, 
   // scalar registers from the first instruction on: there are more of them than registers.
   (void)a_by_value;
   const Args& a = *(const Args*)__builtin_amdgcn_kernarg_segment_ptr();
+  warm_kernel_arguments();
   __shared__ FinShared fs;
   const int b = blockIdx.x;
   const int code = finish_row(a, b, fs);

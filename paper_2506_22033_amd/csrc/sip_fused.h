@@ -17,6 +17,7 @@ template <int DT, bool SH>
 __global__ __launch_bounds__(kFinalThreads) void finish_rescue_kernel(Args a_by_value) {
   (void)a_by_value;
   const Args& a = *(const Args*)__builtin_amdgcn_kernarg_segment_ptr();
+  warm_kernel_arguments();
   __shared__ union __align__(16) { FinShared fs; unsigned char raw[kFusedRawBytes]; } u;
   __shared__ ExactShared ex;
   __shared__ FastShared fsr;
